@@ -1,0 +1,193 @@
+/*
+ * coreinfer.h -- C ABI of libcoreinfer.so: the data-parallel hot path of
+ * CoreInfer (arXiv 2410.18311) for one AMD MI355X (gfx950).
+ *
+ * The path has two halves.
+ *   Prefill (once per sentence and FFN layer): the dense FFN produces the
+ *   activation matrix A (one row per prompt token); coreinfer_select turns it
+ *   into the sentence-wise core neuron set S (Sec. 3.1, Def. 1-2, Eq. 1-3);
+ *   coreinfer_compact gathers the weights of S into contiguous buffers
+ *   (Sec. 5.3, "deploying the necessary neurons during pre-filling").
+ *   Decode (every generated token): coreinfer_ffn_decode runs the FFN over
+ *   the frozen set S only (Sec. 4.1 stability-guided prediction; Sec. 4.2).
+ *
+ * Conventions, valid for every entry point unless stated otherwise:
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The
+ *     library allocates and frees nothing; scratch memory is the caller's
+ *     workspace, sized by the matching *_workspace_size query (a pure host
+ *     function that needs no GPU).  Inputs are never modified.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; no call synchronises the device, so outputs
+ *     are valid only after the caller synchronises the stream.
+ *   - Arguments are validated on the host before any HIP call.  The return
+ *     value is CI_OK (0) or a negative ci_status; coreinfer_strerror names it.
+ *     No exception crosses the boundary.
+ *   - Matrices are row-major and dense (leading dimension = row length) unless
+ *     an `ld` argument says otherwise.  Weights use the nn.Linear convention of
+ *     the models the paper runs: w_up, w_gate are [N, d]; w_down is [d, N]
+ *     (CI_DOWN_OUT_MAJOR) or its transpose [N, d] (CI_DOWN_NEURON_MAJOR).
+ *   - d = d_model, N = d_ff (neurons per layer), M = prompt tokens,
+ *     K = |S|, B = sentences decoded together.
+ *   - Element types: CI_F32, CI_F16 (IEEE half), CI_BF16.  Every sum is
+ *     accumulated in fp32 and the hidden activations stay fp32 (Sec. 5,
+ *     "Models": fp16 parameters, fp32 intermediate activations).
+ *   - Pointers must be 16-byte aligned, and d must be a multiple of
+ *     16 / sizeof(element) (8 for 16-bit types, 4 for fp32); otherwise
+ *     CI_ERR_BAD_LAYOUT.
+ *   - Calls are deterministic: the same bits in give the same bits out.
+ */
+#ifndef COREINFER_H_
+#define COREINFER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CI_OK = 0,
+  CI_ERR_INVALID_ARG = -1, /* null pointer, size out of range, fraction outside (0,1] */
+  CI_ERR_BAD_DTYPE = -2,   /* dtype / activation enum not recognised               */
+  CI_ERR_BAD_LAYOUT = -3,  /* alignment, leading dimension or layout enum          */
+  CI_ERR_WORKSPACE = -4,   /* workspace null or smaller than the query says        */
+  CI_ERR_HIP = -5,         /* a HIP runtime call or kernel launch failed           */
+  CI_ERR_UNSUPPORTED = -6  /* valid request that this build does not implement     */
+} ci_status;
+
+typedef enum { CI_F32 = 0, CI_F16 = 1, CI_BF16 = 2 } ci_dtype;
+typedef enum { CI_ACT_RELU = 0, CI_ACT_SWIGLU = 1 } ci_act;
+typedef enum { CI_DOWN_OUT_MAJOR = 0, CI_DOWN_NEURON_MAJOR = 1 } ci_down_layout;
+
+/* Upper limits accepted by the entry points. */
+#define CI_MAX_TOKENS 65535     /* M: counts fit 16 bits                */
+#define CI_MAX_NEURONS 1048576  /* N                                   */
+#define CI_MAX_DMODEL 32768     /* d                                   */
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* coreinfer_strerror(int status);
+
+/* Library ABI version (increases when a signature changes). */
+int coreinfer_version(void);
+
+/*
+ * Development knob for tuning sweeps, never needed for correct use: overrides
+ * a launch-shape parameter process-wide.  Names: "decode_wgs_per_cu" (1..16),
+ * "decode_threads" (0 = derive from d, else a multiple of 64 up to 1024),
+ * "select_wgs_per_cu" (1..8), "gemv_wgs_per_cu" (1..32).  Unknown name or
+ * value out of range: CI_ERR_INVALID_ARG.  Not thread-safe against running
+ * calls.
+ */
+int coreinfer_set_param(const char* name, int value);
+
+/*
+ * Size of "the top `frac` share of n items", the rule every selection below
+ * uses: k = ceil(q * n / 10^6) with q = floor(frac * 10^6 + 0.5), in integer
+ * arithmetic (Def. 1 and Def. 2 leave the rounding open; this is the smallest
+ * set that covers at least the fraction).  Host-only, needs no GPU; lets the
+ * caller size core_idx without a device round trip.
+ * frac outside (0, 1] (or below 1e-6), n < 0 or k == NULL: CI_ERR_INVALID_ARG.
+ */
+int coreinfer_keep_count(double frac, int64_t n, int64_t* k);
+
+/*
+ * Sentence-wise core neuron selection for one FFN layer of one sentence
+ * (Sec. 3.1; Fig. 1 "top-k selection ... top-k commonly activated").
+ *
+ *   act      [M, N] fp32, row stride ld >= N elements: A, the activation of
+ *            every neuron for every prompt token (ReLU output, or
+ *            |SiLU(gate)*up| for gated FFNs).
+ *   step 1   (Def. 1 / Eq. 1) per token m: P = #{a > 0};
+ *            C_m = the keep_count(alpha, P) largest positive entries,
+ *            equal values resolved towards the lower neuron index.
+ *            NaN and values <= 0 are never selected.
+ *   step 2   (Eq. 3) counts[n] = #{m : n in C_m}.
+ *   step 3   (Def. 2 / Eq. 2) S = the K = keep_count(beta, N) neurons that
+ *            come first in the order (count descending, index ascending).
+ *   core_idx [K] int32 out: S in ascending index order.
+ *   counts   [N] int32 out, may be NULL (then it lives in the workspace).
+ *   ws       at least coreinfer_select_workspace_size(M, N) bytes.
+ * Limits: 1 <= M <= CI_MAX_TOKENS, 1 <= N <= CI_MAX_NEURONS.
+ */
+int coreinfer_select_workspace_size(int64_t M, int64_t N, size_t* bytes);
+int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld,
+                     double alpha, double beta,
+                     int32_t* core_idx, int32_t* counts,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Deploy the core neurons (Sec. 5.3): gather rows S of w_up (and w_gate),
+ * entries S of b_up and columns S of w_down into contiguous, neuron-major
+ * buffers:
+ *   w_up_c   [K, d] = w_up[S, :]        w_gate_c [K, d] = w_gate[S, :]
+ *   b_up_c   [K]    = b_up[S]           w_down_c [K, d] = (w_down[:, S])^T
+ * w_gate / w_gate_c must be non-NULL exactly when act == CI_ACT_SWIGLU;
+ * b_up / b_up_c are both NULL or both non-NULL.  core_idx [K] must be strictly
+ * ascending with values in [0, N); an entry that violates this yields an
+ * all-zero row and sets *status (device int32, may be NULL; the caller zeroes
+ * it beforehand) to 1 -- it never causes an out-of-bounds access.
+ * Output buffers are caller-allocated and must not overlap the inputs.
+ */
+int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up,
+                      const void* w_down, int down_layout, int dtype, int act,
+                      int64_t d, int64_t N, const int32_t* core_idx, int64_t K,
+                      void* w_up_c, void* w_gate_c, void* b_up_c, void* w_down_c,
+                      int32_t* status, void* stream);
+
+/*
+ * Weights of one FFN layer as the decode kernel reads them.
+ *   core_idx == NULL: compacted -- the buffers written by coreinfer_compact;
+ *                     K rows each, shared by all B inputs.
+ *   core_idx != NULL: gathered -- the resident dense weights, all neuron-major
+ *                     (w_up, w_gate, w_down are [N, d], b_up is [N]);
+ *                     core_idx is [B, K], row b naming sentence b's core set.
+ *                     Entries outside [0, N) contribute nothing.
+ */
+typedef struct {
+  const void* w_up;        /* [K, d] or [N, d]                          */
+  const void* w_gate;      /* same shape; NULL unless CI_ACT_SWIGLU     */
+  const void* b_up;        /* [K] or [N]; may be NULL                   */
+  const void* w_down;      /* [K, d] or [N, d], neuron-major            */
+  const void* b_down;      /* [d]; may be NULL                          */
+  const int32_t* core_idx; /* NULL (compacted) or [B, K] (gathered)     */
+  int64_t K;               /* core neurons per sentence                 */
+  int64_t d;               /* d_model                                   */
+  int64_t N;               /* rows of the resident weights (gathered)   */
+} ci_ffn_weights;
+
+/*
+ * Decode-stage FFN over the frozen core set (Sec. 4.2):
+ *   ReLU:    y = w_down_c^T max(w_up_c x + b_up_c, 0) + b_down
+ *   SwiGLU:  y = w_down_c^T (SiLU(w_gate_c x) * (w_up_c x)) + b_down
+ * x [B, d] in, y [B, d] out, element type `dtype`; K = 0 gives y = b_down.
+ * ws: at least coreinfer_ffn_decode_workspace_size(B, K, d) bytes.
+ */
+int coreinfer_ffn_decode_workspace_size(int64_t B, int64_t K, int64_t d, size_t* bytes);
+int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w,
+                         int dtype, int act, void* y,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dense FFN over all N neurons (Def. 1: the activation vector A(x) of every
+ * prompt token; with M = 1 also the dense decode baseline).
+ *   ReLU:    H = max(X w_up^T + b_up, 0),           A = H
+ *   SwiGLU:  H = SiLU(X w_gate^T) * (X w_up^T),     A = |H|
+ *   Y = H w_down^T + b_down
+ * X [M, d]; Y [M, d] (element type `dtype`, may be NULL); A [M, N] fp32 (may
+ * be NULL); at least one of Y, A must be given.  For Y, H is rounded to
+ * `dtype` before the second product when M > 4 (matrix-core path).
+ * ws: at least coreinfer_ffn_dense_workspace_size(M, d, N, dtype) bytes.
+ */
+int coreinfer_ffn_dense_workspace_size(int64_t M, int64_t d, int64_t N, int dtype, size_t* bytes);
+int coreinfer_ffn_dense(const void* X, int64_t M,
+                        const void* w_up, const void* w_gate, const void* b_up,
+                        const void* w_down, const void* b_down, int down_layout,
+                        int dtype, int act, int64_t d, int64_t N,
+                        void* Y, float* A,
+                        void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COREINFER_H_ */

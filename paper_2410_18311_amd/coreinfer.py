@@ -1,0 +1,217 @@
+"""ctypes binding over libcoreinfer.so -- argument marshalling only.
+
+Function names mirror the C ABI (include/coreinfer.h).  Tensors are torch
+tensors on the GPU; torch supplies device memory and the current stream,
+every step of the path runs in the library's own HIP kernels.  There is no
+fallback: if the library is missing, importing this module raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # imported first so that the HIP runtime torch ships is the one the library binds to
+
+from .build import LIB_PATH
+
+CI_OK = 0
+CI_ERR_INVALID_ARG = -1
+CI_ERR_BAD_DTYPE = -2
+CI_ERR_BAD_LAYOUT = -3
+CI_ERR_WORKSPACE = -4
+CI_ERR_HIP = -5
+CI_ERR_UNSUPPORTED = -6
+
+CI_F32, CI_F16, CI_BF16 = 0, 1, 2
+CI_ACT_RELU, CI_ACT_SWIGLU = 0, 1
+CI_DOWN_OUT_MAJOR, CI_DOWN_NEURON_MAJOR = 0, 1
+
+DTYPE_CODE = {torch.float32: CI_F32, torch.float16: CI_F16, torch.bfloat16: CI_BF16}
+ACT_CODE = {"relu": CI_ACT_RELU, "swiglu": CI_ACT_SWIGLU}
+LAYOUT_CODE = {"out_major": CI_DOWN_OUT_MAJOR, "neuron_major": CI_DOWN_NEURON_MAJOR}
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is not built; run `python -m paper_2410_18311_amd.build` "
+        "(there is no CPU or PyTorch fallback for the CoreInfer kernels)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i64, _int, _dbl, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_size_t
+
+
+class ci_ffn_weights(ctypes.Structure):
+    _fields_ = [("w_up", _vp), ("w_gate", _vp), ("b_up", _vp), ("w_down", _vp), ("b_down", _vp),
+                ("core_idx", _vp), ("K", _i64), ("d", _i64), ("N", _i64)]
+
+
+_SIGNATURES = {
+    "coreinfer_strerror": (ctypes.c_char_p, [_int]),
+    "coreinfer_version": (_int, []),
+    "coreinfer_set_param": (_int, [ctypes.c_char_p, _int]),
+    "coreinfer_keep_count": (_int, [_dbl, _i64, ctypes.POINTER(_i64)]),
+    "coreinfer_select_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
+    "coreinfer_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
+    "coreinfer_compact": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64,
+                                 _vp, _vp, _vp, _vp, _vp, _vp]),
+    "coreinfer_ffn_decode_workspace_size": (_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
+    "coreinfer_ffn_decode": (_int, [_vp, _i64, ctypes.POINTER(ci_ffn_weights), _int, _int, _vp,
+                                    _vp, _sz, _vp]),
+    "coreinfer_ffn_dense_workspace_size": (_int, [_i64, _i64, _i64, _int, ctypes.POINTER(_sz)]),
+    "coreinfer_ffn_dense": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64,
+                                   _vp, _vp, _vp, _sz, _vp]),
+}
+for _name, (_res, _args) in _SIGNATURES.items():
+    _f = getattr(_lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+EXPORTS = tuple(_SIGNATURES)
+raw = _lib  # the bare C entry points, for tests of the error paths
+
+
+class CoreInferError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+def _check(status: int, where: str):
+    if status != CI_OK:
+        raise CoreInferError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(t: torch.Tensor):
+    return torch.cuda.current_stream(t.device).cuda_stream if t.is_cuda else None
+
+
+def _workspace(nbytes: int, like: torch.Tensor) -> torch.Tensor:
+    return torch.empty(nbytes, dtype=torch.uint8, device=like.device)
+
+
+def strerror(status: int) -> str:
+    return _lib.coreinfer_strerror(status).decode()
+
+
+def version() -> int:
+    return _lib.coreinfer_version()
+
+
+def set_param(name: str, value: int) -> None:
+    _check(_lib.coreinfer_set_param(name.encode(), int(value)), "coreinfer_set_param")
+
+
+def keep_count(frac: float, n: int) -> int:
+    k = _i64(0)
+    _check(_lib.coreinfer_keep_count(float(frac), int(n), ctypes.byref(k)), "coreinfer_keep_count")
+    return k.value
+
+
+def select_workspace_size(M: int, N: int) -> int:
+    b = _sz(0)
+    _check(_lib.coreinfer_select_workspace_size(M, N, ctypes.byref(b)), "coreinfer_select_workspace_size")
+    return b.value
+
+
+def select(act: torch.Tensor, alpha: float, beta: float, core_idx: Optional[torch.Tensor] = None,
+           counts: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """coreinfer_select on A [M, N] fp32 (device).  Returns (core_idx, counts)."""
+    assert act.dim() == 2 and act.dtype == torch.float32 and act.stride(1) == 1
+    M, N = act.shape
+    K = keep_count(beta, N)
+    if core_idx is None:
+        core_idx = torch.empty(K, dtype=torch.int32, device=act.device)
+    if counts is None:
+        counts = torch.empty(N, dtype=torch.int32, device=act.device)
+    if ws is None:
+        ws = _workspace(select_workspace_size(M, N), act)
+    _check(_lib.coreinfer_select(_ptr(act), M, N, act.stride(0), float(alpha), float(beta),
+                                 _ptr(core_idx), _ptr(counts), _ptr(ws), ws.numel(), _stream(act)),
+           "coreinfer_select")
+    return core_idx, counts
+
+
+def compact(w_up, w_gate, b_up, w_down, down_layout: str, act: str, core_idx: torch.Tensor,
+            out: Optional[dict] = None, status: Optional[torch.Tensor] = None) -> dict:
+    """coreinfer_compact.  Returns the dict of compact buffers (allocated when
+    `out` is not given): w_up_c, w_gate_c, b_up_c, w_down_c, all neuron-major."""
+    N, d = w_up.shape
+    K = core_idx.numel()
+    if out is None:
+        out = {
+            "w_up_c": torch.empty((K, d), dtype=w_up.dtype, device=w_up.device),
+            "w_gate_c": None if w_gate is None else torch.empty((K, d), dtype=w_up.dtype, device=w_up.device),
+            "b_up_c": None if b_up is None else torch.empty((K,), dtype=w_up.dtype, device=w_up.device),
+            "w_down_c": torch.empty((K, d), dtype=w_up.dtype, device=w_up.device),
+        }
+    _check(_lib.coreinfer_compact(_ptr(w_up), _ptr(w_gate), _ptr(b_up), _ptr(w_down),
+                                  LAYOUT_CODE[down_layout], DTYPE_CODE[w_up.dtype], ACT_CODE[act],
+                                  d, N, _ptr(core_idx), K, _ptr(out["w_up_c"]), _ptr(out["w_gate_c"]),
+                                  _ptr(out["b_up_c"]), _ptr(out["w_down_c"]), _ptr(status), _stream(w_up)),
+           "coreinfer_compact")
+    return out
+
+
+def ffn_decode_workspace_size(B: int, K: int, d: int) -> int:
+    b = _sz(0)
+    _check(_lib.coreinfer_ffn_decode_workspace_size(B, K, d, ctypes.byref(b)),
+           "coreinfer_ffn_decode_workspace_size")
+    return b.value
+
+
+def make_weights(w_up, w_gate, b_up, w_down, b_down, core_idx=None, K: Optional[int] = None) -> ci_ffn_weights:
+    """Fills the ci_ffn_weights descriptor.  Compacted: pass the [K, d] buffers.
+    Gathered: pass the resident neuron-major [N, d] weights and core_idx [B, K]."""
+    rows, d = w_up.shape
+    if core_idx is None:
+        K = rows if K is None else K
+    else:
+        K = core_idx.shape[-1]
+    return ci_ffn_weights(_ptr(w_up), _ptr(w_gate), _ptr(b_up), _ptr(w_down), _ptr(b_down),
+                          _ptr(core_idx), K, d, rows)
+
+
+def ffn_decode(x: torch.Tensor, weights: ci_ffn_weights, act: str, y: Optional[torch.Tensor] = None,
+               ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """coreinfer_ffn_decode on x [B, d] (or [d])."""
+    x2 = x if x.dim() == 2 else x.unsqueeze(0)
+    B, d = x2.shape
+    if y is None:
+        y = torch.empty_like(x2)
+    if ws is None:
+        ws = _workspace(ffn_decode_workspace_size(B, weights.K, d), x)
+    _check(_lib.coreinfer_ffn_decode(_ptr(x2), B, ctypes.byref(weights), DTYPE_CODE[x.dtype],
+                                     ACT_CODE[act], _ptr(y), _ptr(ws), ws.numel(), _stream(x)),
+           "coreinfer_ffn_decode")
+    return y if x.dim() == 2 else y.squeeze(0)
+
+
+def ffn_dense_workspace_size(M: int, d: int, N: int, dtype: torch.dtype) -> int:
+    b = _sz(0)
+    _check(_lib.coreinfer_ffn_dense_workspace_size(M, d, N, DTYPE_CODE[dtype], ctypes.byref(b)),
+           "coreinfer_ffn_dense_workspace_size")
+    return b.value
+
+
+def ffn_dense(X: torch.Tensor, w_up, w_gate, b_up, w_down, b_down, down_layout: str, act: str,
+              want_y: bool = True, want_a: bool = False, Y=None, A=None, ws=None):
+    """coreinfer_ffn_dense on X [M, d].  Returns (Y or None, A or None)."""
+    M, d = X.shape
+    N = w_up.shape[0]
+    if want_y and Y is None:
+        Y = torch.empty((M, d), dtype=X.dtype, device=X.device)
+    if want_a and A is None:
+        A = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = _workspace(ffn_dense_workspace_size(M, d, N, X.dtype), X)
+    _check(_lib.coreinfer_ffn_dense(_ptr(X), M, _ptr(w_up), _ptr(w_gate), _ptr(b_up), _ptr(w_down),
+                                    _ptr(b_down), LAYOUT_CODE[down_layout], DTYPE_CODE[X.dtype],
+                                    ACT_CODE[act], d, N, _ptr(Y), _ptr(A), _ptr(ws), ws.numel(),
+                                    _stream(X)),
+           "coreinfer_ffn_dense")
+    return Y, A

@@ -1,0 +1,219 @@
+// C ABI of libcoreinfer: argument validation (host only, before any HIP
+// call) and dispatch to the kernel launchers.
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "common.hpp"
+
+namespace ci {
+
+Params& params() {
+  static Params p;
+  return p;
+}
+
+int device_info(DeviceInfo* out) {
+  static std::mutex mu;
+  static int cached_cus[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return CI_ERR_HIP;
+  if (dev < 0 || dev >= 64) return CI_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cached_cus[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      return CI_ERR_HIP;
+    cached_cus[dev] = cus;
+  }
+  out->cus = cached_cus[dev];
+  return CI_OK;
+}
+
+namespace {
+
+bool dtype_ok(int dt) { return dt == CI_F32 || dt == CI_F16 || dt == CI_BF16; }
+bool act_ok(int a) { return a == CI_ACT_RELU || a == CI_ACT_SWIGLU; }
+bool layout_ok(int l) { return l == CI_DOWN_OUT_MAJOR || l == CI_DOWN_NEURON_MAJOR; }
+int vec_of(int dt) { return dt == CI_F32 ? 4 : 8; }
+size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+
+// parts per million of a keep fraction; 0 if the fraction is not in (0, 1]
+int64_t fraction_ppm(double frac) {
+  if (!(frac > 0.0) || !(frac <= 1.0)) return 0;
+  const int64_t q = (int64_t)floor(frac * 1e6 + 0.5);
+  return q < 1 ? 0 : q;
+}
+int64_t keep(int64_t q, int64_t n) { return (q * n + 999999) / 1000000; }
+
+constexpr int64_t kMaxSplits = 1024;
+
+}  // namespace
+}  // namespace ci
+
+using namespace ci;
+
+extern "C" {
+
+const char* coreinfer_strerror(int status) {
+  switch (status) {
+    case CI_OK: return "ok";
+    case CI_ERR_INVALID_ARG: return "invalid argument";
+    case CI_ERR_BAD_DTYPE: return "unknown dtype or activation";
+    case CI_ERR_BAD_LAYOUT: return "bad layout or alignment";
+    case CI_ERR_WORKSPACE: return "workspace missing or too small";
+    case CI_ERR_HIP: return "HIP runtime error";
+    case CI_ERR_UNSUPPORTED: return "unsupported configuration";
+  }
+  return "unknown status";
+}
+
+int coreinfer_version(void) { return 1; }
+
+// Development knob, not part of the documented interface: launch-shape
+// parameters for tuning sweeps.  Returns CI_ERR_INVALID_ARG for unknown names.
+int coreinfer_set_param(const char* name, int value) {
+  if (!name) return CI_ERR_INVALID_ARG;
+  Params& p = params();
+  if (!strcmp(name, "decode_wgs_per_cu") && value >= 1 && value <= 16) p.decode_wgs_per_cu = value;
+  else if (!strcmp(name, "decode_threads") && value >= 0 && value <= 1024) p.decode_threads = value;
+  else if (!strcmp(name, "select_wgs_per_cu") && value >= 1 && value <= 8) p.select_wgs_per_cu = value;
+  else if (!strcmp(name, "gemv_wgs_per_cu") && value >= 1 && value <= 32) p.gemv_wgs_per_cu = value;
+  else return CI_ERR_INVALID_ARG;
+  return CI_OK;
+}
+
+int coreinfer_keep_count(double frac, int64_t n, int64_t* k) {
+  if (!k || n < 0 || n > ((int64_t)1 << 40)) return CI_ERR_INVALID_ARG;
+  const int64_t q = fraction_ppm(frac);
+  if (q == 0) return CI_ERR_INVALID_ARG;
+  *k = keep(q, n);
+  return CI_OK;
+}
+
+int coreinfer_select_workspace_size(int64_t M, int64_t N, size_t* bytes) {
+  if (!bytes || M < 1 || M > CI_MAX_TOKENS || N < 1 || N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+  *bytes = round256((size_t)N * sizeof(int32_t)) + 256;
+  return CI_OK;
+}
+
+int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld, double alpha, double beta,
+                     int32_t* core_idx, int32_t* counts, void* ws, size_t ws_bytes, void* stream) {
+  size_t need = 0;
+  if (coreinfer_select_workspace_size(M, N, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!act || !core_idx) return CI_ERR_INVALID_ARG;
+  const int64_t qa = fraction_ppm(alpha), qb = fraction_ppm(beta);
+  if (qa == 0 || qb == 0) return CI_ERR_INVALID_ARG;
+  if (ld < N) return CI_ERR_BAD_LAYOUT;
+  if ((reinterpret_cast<uintptr_t>(act) & 3u) || (reinterpret_cast<uintptr_t>(core_idx) & 3u) ||
+      (reinterpret_cast<uintptr_t>(counts) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
+  int32_t* cnt = counts ? counts : reinterpret_cast<int32_t*>(ws);
+  return launch_select(act, M, N, ld, qa, keep(qb, N), core_idx, cnt, (hipStream_t)stream);
+}
+
+int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
+                      int down_layout, int dtype, int act, int64_t d, int64_t N,
+                      const int32_t* core_idx, int64_t K, void* w_up_c, void* w_gate_c,
+                      void* b_up_c, void* w_down_c, int32_t* status, void* stream) {
+  if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  if (!layout_ok(down_layout)) return CI_ERR_BAD_LAYOUT;
+  if (d < 1 || d > CI_MAX_DMODEL || N < 1 || N > CI_MAX_NEURONS || K < 0 || K > N) return CI_ERR_INVALID_ARG;
+  if (!w_up || !w_down || !w_up_c || !w_down_c || (K > 0 && !core_idx)) return CI_ERR_INVALID_ARG;
+  if ((act == CI_ACT_SWIGLU) != (w_gate != nullptr) || (w_gate != nullptr) != (w_gate_c != nullptr))
+    return CI_ERR_INVALID_ARG;
+  if ((b_up != nullptr) != (b_up_c != nullptr)) return CI_ERR_INVALID_ARG;
+  if (d % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
+  if (!aligned16(w_up) || !aligned16(w_gate) || !aligned16(w_down) || !aligned16(w_up_c) ||
+      !aligned16(w_gate_c) || !aligned16(w_down_c))
+    return CI_ERR_BAD_LAYOUT;
+  return launch_compact(w_up, w_gate, b_up, w_down, down_layout, dtype, d, N, core_idx, K, w_up_c,
+                        w_gate_c, b_up_c, w_down_c, status, (hipStream_t)stream);
+}
+
+int coreinfer_ffn_decode_workspace_size(int64_t B, int64_t K, int64_t d, size_t* bytes) {
+  if (!bytes || B < 1 || B > 65535 || K < 0 || K > CI_MAX_NEURONS || d < 1 || d > CI_MAX_DMODEL)
+    return CI_ERR_INVALID_ARG;
+  const int64_t splits = K < kMaxSplits ? K : kMaxSplits;
+  *bytes = round256((size_t)B * (size_t)splits * (size_t)d * sizeof(float)) + 256;
+  return CI_OK;
+}
+
+int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,
+                         void* y, void* ws, size_t ws_bytes, void* stream) {
+  if (!w) return CI_ERR_INVALID_ARG;
+  if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  size_t need = 0;
+  if (coreinfer_ffn_decode_workspace_size(B, w->K, w->d, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!x || !y) return CI_ERR_INVALID_ARG;
+  if (w->K > 0 && (!w->w_up || !w->w_down)) return CI_ERR_INVALID_ARG;
+  if (w->K > 0 && (act == CI_ACT_SWIGLU) != (w->w_gate != nullptr)) return CI_ERR_INVALID_ARG;
+  if (w->core_idx && (w->N < 1 || w->N > CI_MAX_NEURONS)) return CI_ERR_INVALID_ARG;
+  if (w->d % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(w->w_up) || !aligned16(w->w_gate) ||
+      !aligned16(w->w_down) || (reinterpret_cast<uintptr_t>(w->core_idx) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
+  return launch_ffn_decode(x, B, w, dtype, act, y, reinterpret_cast<float*>(ws), (hipStream_t)stream);
+}
+
+int coreinfer_ffn_dense_workspace_size(int64_t M, int64_t d, int64_t N, int dtype, size_t* bytes) {
+  if (!dtype_ok(dtype)) return CI_ERR_BAD_DTYPE;
+  if (!bytes || M < 1 || M > CI_MAX_TOKENS || d < 1 || d > CI_MAX_DMODEL || N < 1 || N > CI_MAX_NEURONS)
+    return CI_ERR_INVALID_ARG;
+  // hidden matrix H [M, N]: fp32 on the row-dot path (M <= 4), element type
+  // on the matrix-core path; plus the decode partials for a neuron-major down.
+  size_t b = round256((size_t)M * (size_t)N * sizeof(float));
+  if (M <= 4) b += round256((size_t)M * (size_t)(N < kMaxSplits ? N : kMaxSplits) * (size_t)d * sizeof(float));
+  *bytes = b + 256;
+  return CI_OK;
+}
+
+int coreinfer_ffn_dense(const void* X, int64_t M, const void* w_up, const void* w_gate,
+                        const void* b_up, const void* w_down, const void* b_down, int down_layout,
+                        int dtype, int act, int64_t d, int64_t N, void* Y, float* A, void* ws,
+                        size_t ws_bytes, void* stream) {
+  if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  if (!layout_ok(down_layout)) return CI_ERR_BAD_LAYOUT;
+  size_t need = 0;
+  if (coreinfer_ffn_dense_workspace_size(M, d, N, dtype, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!X || !w_up || (!Y && !A) || (Y && !w_down)) return CI_ERR_INVALID_ARG;
+  if ((act == CI_ACT_SWIGLU) != (w_gate != nullptr)) return CI_ERR_INVALID_ARG;
+  if (d % vec_of(dtype) != 0 || N % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
+  if (!aligned16(X) || !aligned16(w_up) || !aligned16(w_gate) || !aligned16(w_down) ||
+      !aligned16(Y) || !aligned16(A))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
+  hipStream_t s = (hipStream_t)stream;
+
+  if (M <= 4) {
+    float* H = reinterpret_cast<float*>(ws);
+    if (down_layout == CI_DOWN_NEURON_MAJOR && Y) {
+      // all three matrices are neuron-major: this is the decode kernel with S = all neurons
+      if (A) {
+        int rc = launch_up_rows(X, M, w_up, w_gate, b_up, dtype, act, d, N, nullptr, A, s);
+        if (rc != CI_OK) return rc;
+      }
+      ci_ffn_weights w;
+      w.w_up = w_up; w.w_gate = w_gate; w.b_up = b_up; w.w_down = w_down; w.b_down = b_down;
+      w.core_idx = nullptr; w.K = N; w.d = d; w.N = N;
+      float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) +
+                                                round256((size_t)M * (size_t)N * sizeof(float)));
+      return launch_ffn_decode(X, M, &w, dtype, act, Y, partial, s);
+    }
+    int rc = launch_up_rows(X, M, w_up, w_gate, b_up, dtype, act, d, N, Y ? H : nullptr, A, s);
+    if (rc != CI_OK || !Y) return rc;
+    return launch_down_rows(H, M, w_down, b_down, dtype, d, N, Y, s);
+  }
+  void* H = Y ? ws : nullptr;
+  int rc = launch_gemm_up(X, M, w_up, w_gate, b_up, dtype, act, d, N, H, A, s);
+  if (rc != CI_OK || !Y) return rc;
+  return launch_gemm_down(H, M, w_down, b_down, down_layout, dtype, d, N, Y, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,147 @@
+// Shared device / host helpers for libcoreinfer (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "coreinfer.h"
+
+namespace ci {
+
+constexpr int kWave = 64;
+
+// ---- element types ---------------------------------------------------------
+// VEC = elements per 16-byte global load.
+struct F32 {
+  using T = float;
+  static constexpr int VEC = 4;
+  static constexpr int BYTES = 4;
+};
+struct F16 {
+  using T = _Float16;
+  static constexpr int VEC = 8;
+  static constexpr int BYTES = 2;
+};
+struct BF16 {
+  using T = uint16_t;  // raw bits
+  static constexpr int VEC = 8;
+  static constexpr int BYTES = 2;
+};
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+__device__ __forceinline__ uint4 ld16(const void* p) {
+  return *reinterpret_cast<const uint4*>(p);
+}
+
+// Expand one 16-byte vector into fp32 lanes.
+template <class D>
+__device__ __forceinline__ void unpack(const uint4& v, float (&f)[D::VEC]);
+
+template <>
+__device__ __forceinline__ void unpack<F32>(const uint4& v, float (&f)[4]) {
+  f[0] = u2f(v.x); f[1] = u2f(v.y); f[2] = u2f(v.z); f[3] = u2f(v.w);
+}
+template <>
+__device__ __forceinline__ void unpack<F16>(const uint4& v, float (&f)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    half2_t h = __builtin_bit_cast(half2_t, w[i]);
+    f[2 * i] = (float)h[0];
+    f[2 * i + 1] = (float)h[1];
+  }
+}
+template <>
+__device__ __forceinline__ void unpack<BF16>(const uint4& v, float (&f)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = u2f(w[i] << 16);
+    f[2 * i + 1] = u2f(w[i] & 0xffff0000u);
+  }
+}
+
+template <class D>
+__device__ __forceinline__ float to_float(typename D::T v);
+template <> __device__ __forceinline__ float to_float<F32>(float v) { return v; }
+template <> __device__ __forceinline__ float to_float<F16>(_Float16 v) { return (float)v; }
+template <> __device__ __forceinline__ float to_float<BF16>(uint16_t v) { return u2f((uint32_t)v << 16); }
+
+// fp32 -> element, round to nearest even.
+template <class D>
+__device__ __forceinline__ typename D::T from_float(float f);
+template <> __device__ __forceinline__ float from_float<F32>(float f) { return f; }
+template <> __device__ __forceinline__ _Float16 from_float<F16>(float f) { return (_Float16)f; }
+template <> __device__ __forceinline__ uint16_t from_float<BF16>(float f) {
+  uint32_t u = f2u(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
+
+// ---- wave64 primitives -----------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+__device__ __forceinline__ uint64_t lanemask_lt() {
+  return (1ull << (threadIdx.x & 63)) - 1ull;
+}
+
+// ---- host side -------------------------------------------------------------
+struct DeviceInfo {
+  int cus;
+};
+// Compute-unit count of the current device (queried once per device).
+int device_info(DeviceInfo* out);
+
+// Development knobs (see coreinfer_set_param).
+struct Params {
+  int decode_wgs_per_cu = 2;
+  int decode_threads = 0;  // 0 = derived from d
+  int select_wgs_per_cu = 1;
+  int gemv_wgs_per_cu = 4;
+};
+Params& params();
+
+inline int elem_bytes(int dtype) { return dtype == CI_F32 ? 4 : 2; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define CI_HIP_CHECK_LAUNCH()                          \
+  do {                                                 \
+    if (hipGetLastError() != hipSuccess) return CI_ERR_HIP; \
+  } while (0)
+
+// ---- launchers (one per translation unit) ----------------------------------
+int launch_select(const float* act, int64_t M, int64_t N, int64_t ld, int64_t q_alpha, int64_t K,
+                  int32_t* core_idx, int32_t* counts, hipStream_t s);
+int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
+                   int down_layout, int dtype, int64_t d, int64_t N, const int32_t* core_idx,
+                   int64_t K, void* w_up_c, void* w_gate_c, void* b_up_c, void* w_down_c,
+                   int32_t* status, hipStream_t s);
+int decode_splits(int64_t B, int64_t K);
+int launch_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,
+                      void* y, float* partial, hipStream_t s);
+// h[M, N] fp32 = act(X w^T ...) and y = W h + b by row-dot GEMVs (small M).
+int launch_up_rows(const void* X, int64_t M, const void* w_up, const void* w_gate, const void* b_up,
+                   int dtype, int act, int64_t d, int64_t N, float* H, float* A, hipStream_t s);
+int launch_down_rows(const float* H, int64_t M, const void* w_down, const void* b_down, int dtype,
+                     int64_t d, int64_t N, void* Y, hipStream_t s);
+int launch_gemm_up(const void* X, int64_t M, const void* w_up, const void* w_gate, const void* b_up,
+                   int dtype, int act, int64_t d, int64_t N, void* H, float* A, hipStream_t s);
+int launch_gemm_down(const void* H, int64_t M, const void* w_down, const void* b_down,
+                     int down_layout, int dtype, int64_t d, int64_t N, void* Y, hipStream_t s);
+
+}  // namespace ci

@@ -1,0 +1,387 @@
+// Dense prefill FFN (Def. 1 of arXiv 2410.18311: the activation vector A(x)
+// of every prompt token) -- the one real dense contraction of the path, so it
+// runs on the matrix cores.
+//
+//   C[M, Nn] = A[M, Kk] * B^T   with B given as [Nn, Kk] (both operands
+//   k-contiguous, the nn.Linear layout) or, for a neuron-major down matrix, as
+//   [Kk, Nn].
+//
+// gemm_mfma_kernel (fp16 / bf16): 128x128x64 workgroup tiles, 256 threads =
+// 2x2 waves, each wave a 64x64 sub-tile as 2x2 v_mfma_f32_32x32x16 tiles with
+// fp32 accumulators.  Global -> register -> LDS staging with two LDS buffers,
+// so the next tile's global loads are in flight during the MFMAs.  The
+// epilogue is fused: bias + ReLU, or SiLU(gate)*up from two accumulator sets,
+// writing the fp32 score matrix and/or the element-type hidden matrix; or
+// bias + convert for the down projection.
+// gemm_f32_kernel: plain fp32 FMA tiles for the fp32 element type.
+#include "common.hpp"
+
+namespace ci {
+
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+enum { EPI_RELU = 0, EPI_SWIGLU = 1, EPI_LINEAR = 2 };
+
+struct GemmArgs {
+  const void* A;
+  const void* B0;  // EPI_SWIGLU: gate
+  const void* B1;  // EPI_SWIGLU: up
+  const void* bias;
+  void* out_e;     // [M, Nn] element type, may be null
+  float* out_f;    // [M, Nn] fp32, may be null
+  int64_t lda, ldb, ldo;
+  int M, Nn, Kk;
+};
+
+template <class D>
+__device__ __forceinline__ f32x16 mfma32(const uint4& a, const uint4& b, f32x16 c);
+template <>
+__device__ __forceinline__ f32x16 mfma32<F16>(const uint4& a, const uint4& b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ f32x16 mfma32<BF16>(const uint4& a, const uint4& b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int LDK = BK + 8;  // LDS row stride in elements (144 bytes)
+
+// Spreads consecutive tiles over one XCD (workgroup ids go round-robin over the
+// 8 XCDs, each with its own L2), so that tiles sharing a B panel share an L2.
+__device__ __forceinline__ int xcd_swizzle(int id, int n) {
+  if (n % 8 != 0) return id;
+  return (id % 8) * (n / 8) + id / 8;
+}
+
+template <class D, int EPI, bool BNN>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
+  using T = typename D::T;
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  constexpr int NB = DUAL ? 2 : 1;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* smem = reinterpret_cast<T*>(smem_raw);
+  // per stage: A tile, then NB B tiles
+  constexpr int TILE = BM * LDK;
+  constexpr int STAGE = TILE * (1 + NB);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tiles_m = (g.M + BM - 1) / BM;
+  const int t = xcd_swizzle(blockIdx.x, gridDim.x);
+  const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
+  const T* A = reinterpret_cast<const T*>(g.A);
+  const T* Bp[2] = {reinterpret_cast<const T*>(g.B0), reinterpret_cast<const T*>(g.B1)};
+
+  uint4 ra[4], rb[NB][4];
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = tid + 256 * i;
+      {
+        const int row = v >> 3, kc = (v & 7) * 8;
+        ra[i] = make_uint4(0, 0, 0, 0);
+        if (m0 + row < g.M && k0 + kc < g.Kk) ra[i] = ld16(A + (size_t)(m0 + row) * g.lda + k0 + kc);
+      }
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        rb[q][i] = make_uint4(0, 0, 0, 0);
+        if (!BNN) {
+          const int row = v >> 3, kc = (v & 7) * 8;
+          if (n0 + row < g.Nn && k0 + kc < g.Kk)
+            rb[q][i] = ld16(Bp[q] + (size_t)(n0 + row) * g.ldb + k0 + kc);
+        } else {
+          const int krow = v >> 4, nc = (v & 15) * 8;
+          if (k0 + krow < g.Kk && n0 + nc < g.Nn)
+            rb[q][i] = ld16(Bp[q] + (size_t)(k0 + krow) * g.ldb + n0 + nc);
+        }
+      }
+    }
+  };
+  auto store_lds = [&](int stage) {
+    T* sA = smem + stage * STAGE;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = tid + 256 * i;
+      const int row = v >> 3, kc = (v & 7) * 8;
+      *reinterpret_cast<uint4*>(sA + row * LDK + kc) = ra[i];
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        T* sB = sA + TILE * (1 + q);
+        if (!BNN) {
+          *reinterpret_cast<uint4*>(sB + row * LDK + kc) = rb[q][i];
+        } else {
+          const int krow = v >> 4, nc = (v & 15) * 8;
+          const uint32_t w[4] = {rb[q][i].x, rb[q][i].y, rb[q][i].z, rb[q][i].w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint16_t bits = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            reinterpret_cast<uint16_t*>(sB)[(nc + e) * LDK + krow] = bits;
+          }
+        }
+      }
+    }
+  };
+
+  f32x16 acc[NB][2][2];
+#pragma unroll
+  for (int q = 0; q < NB; ++q)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[q][i][j][v] = 0.f;
+
+  const int nk = (g.Kk + BK - 1) / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    const T* sA = smem + cur * STAGE;
+#pragma unroll
+    for (int s = 0; s < BK / 16; ++s) {
+      const int koff = s * 16 + (lane >> 5) * 8;
+      uint4 fa[2], fb[NB][2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        fa[i] = *reinterpret_cast<const uint4*>(sA + (wm * 64 + i * 32 + (lane & 31)) * LDK + koff);
+#pragma unroll
+      for (int q = 0; q < NB; ++q)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          fb[q][j] = *reinterpret_cast<const uint4*>(sA + TILE * (1 + q) +
+                                                     (wn * 64 + j * 32 + (lane & 31)) * LDK + koff);
+#pragma unroll
+      for (int q = 0; q < NB; ++q)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[q][i][j] = mfma32<D>(fa[i], fb[q][j], acc[q][i][j]);
+    }
+    if (kt + 1 < nk) {
+      store_lds(cur ^ 1);  // the other buffer: last read before the previous barrier
+      __syncthreads();
+    }
+  }
+
+  // ---- epilogue.  Accumulator element v of lane l is C[row, col] with
+  // col = l % 32, row = 8 * (v / 4) + 4 * (l / 32) + v % 4 inside a 32x32 tile.
+  const T* bias = reinterpret_cast<const T*>(g.bias);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+    if (col >= g.Nn) continue;
+    const float bv = bias ? to_float<D>(bias[col]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row >= g.M) continue;
+        float h, score;
+        if (EPI == EPI_SWIGLU) {
+          h = silu(acc[0][i][j][v]) * acc[NB - 1][i][j][v];
+          score = fabsf(h);
+        } else if (EPI == EPI_RELU) {
+          h = fmaxf(acc[0][i][j][v] + bv, 0.f);
+          score = h;
+        } else {
+          h = acc[0][i][j][v] + bv;
+          score = h;
+        }
+        const size_t o = (size_t)row * g.ldo + col;
+        if (g.out_f) g.out_f[o] = score;
+        if (g.out_e) reinterpret_cast<T*>(g.out_e)[o] = from_float<D>(h);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// fp32 element type: 64x64x16 tiles, 256 threads, 4x4 outputs per thread.
+template <int EPI, bool BNN>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  constexpr int NB = DUAL ? 2 : 1;
+  __shared__ float sA[16][68];
+  __shared__ float sB[NB][16][68];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int tiles_m = (g.M + 63) / 64;
+  const int m0 = (blockIdx.x % tiles_m) * 64, n0 = (blockIdx.x / tiles_m) * 64;
+  const float* A = reinterpret_cast<const float*>(g.A);
+  const float* Bp[2] = {reinterpret_cast<const float*>(g.B0), reinterpret_cast<const float*>(g.B1)};
+  float acc[NB][4][4];
+#pragma unroll
+  for (int q = 0; q < NB; ++q)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[q][i][j] = 0.f;
+
+  for (int k0 = 0; k0 < g.Kk; k0 += 16) {
+    // 64 rows x 16 k: thread -> (row = tid / 4, k quad = tid % 4)
+    {
+      const int row = tid >> 2, kq = (tid & 3) * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int k = k0 + kq + e;
+        sA[kq + e][row] = (m0 + row < g.M && k < g.Kk) ? A[(size_t)(m0 + row) * g.lda + k] : 0.f;
+      }
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        if (!BNN) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int k = k0 + kq + e;
+            sB[q][kq + e][row] = (n0 + row < g.Nn && k < g.Kk) ? Bp[q][(size_t)(n0 + row) * g.ldb + k] : 0.f;
+          }
+        } else {
+          const int kr = tid >> 4, nq = (tid & 15) * 4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int n = n0 + nq + e;
+            sB[q][kr][nq + e] = (k0 + kr < g.Kk && n < g.Nn) ? Bp[q][(size_t)(k0 + kr) * g.ldb + n] : 0.f;
+          }
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      float a[4], b[NB][4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = sA[k][ty * 4 + i];
+#pragma unroll
+      for (int q = 0; q < NB; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[q][j] = sB[q][k][tx * 4 + j];
+#pragma unroll
+      for (int q = 0; q < NB; ++q)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[q][i][j] = fmaf(a[i], b[q][j], acc[q][i][j]);
+    }
+    __syncthreads();
+  }
+  const float* bias = reinterpret_cast<const float*>(g.bias);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = m0 + ty * 4 + i;
+    if (row >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = n0 + tx * 4 + j;
+      if (col >= g.Nn) continue;
+      const float bv = bias ? bias[col] : 0.f;
+      float h, score;
+      if (EPI == EPI_SWIGLU) {
+        h = silu(acc[0][i][j]) * acc[NB - 1][i][j];
+        score = fabsf(h);
+      } else if (EPI == EPI_RELU) {
+        h = fmaxf(acc[0][i][j] + bv, 0.f);
+        score = h;
+      } else {
+        h = acc[0][i][j] + bv;
+        score = h;
+      }
+      const size_t o = (size_t)row * g.ldo + col;
+      if (g.out_f) g.out_f[o] = score;
+      if (g.out_e) reinterpret_cast<float*>(g.out_e)[o] = h;
+    }
+  }
+}
+
+template <class D, int EPI, bool BNN>
+int launch_mfma(const GemmArgs& g, hipStream_t s) {
+  constexpr int NB = (EPI == EPI_SWIGLU) ? 2 : 1;
+  const size_t lds = (size_t)2 * BM * LDK * (1 + NB) * sizeof(typename D::T);
+  static bool attr_done = false;
+  if (lds > 48 * 1024 && !attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<D, EPI, BNN>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return CI_ERR_HIP;
+    attr_done = true;
+  }
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.Nn + BN - 1) / BN);
+  hipLaunchKernelGGL((gemm_mfma_kernel<D, EPI, BNN>), dim3(tiles), dim3(256), lds, s, g);
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
+
+template <int EPI, bool BNN>
+int launch_f32(const GemmArgs& g, hipStream_t s) {
+  const int tiles = ((g.M + 63) / 64) * ((g.Nn + 63) / 64);
+  hipLaunchKernelGGL((gemm_f32_kernel<EPI, BNN>), dim3(tiles), dim3(256), 0, s, g);
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
+
+template <int EPI, bool BNN>
+int launch_any(int dtype, const GemmArgs& g, hipStream_t s) {
+  switch (dtype) {
+    case CI_F32: return launch_f32<EPI, BNN>(g, s);
+    case CI_F16: return launch_mfma<F16, EPI, BNN>(g, s);
+    case CI_BF16: return launch_mfma<BF16, EPI, BNN>(g, s);
+  }
+  return CI_ERR_BAD_DTYPE;
+}
+
+}  // namespace
+
+int launch_gemm_up(const void* X, int64_t M, const void* w_up, const void* w_gate, const void* b_up,
+                   int dtype, int act, int64_t d, int64_t N, void* H, float* A, hipStream_t s) {
+  GemmArgs g;
+  g.A = X;
+  g.lda = d;
+  g.ldb = d;
+  g.ldo = N;
+  g.M = (int)M;
+  g.Nn = (int)N;
+  g.Kk = (int)d;
+  g.out_e = H;
+  g.out_f = A;
+  if (act == CI_ACT_SWIGLU) {
+    g.B0 = w_gate;
+    g.B1 = w_up;
+    g.bias = nullptr;
+    return launch_any<EPI_SWIGLU, false>(dtype, g, s);
+  }
+  g.B0 = w_up;
+  g.B1 = nullptr;
+  g.bias = b_up;
+  return launch_any<EPI_RELU, false>(dtype, g, s);
+}
+
+int launch_gemm_down(const void* H, int64_t M, const void* w_down, const void* b_down,
+                     int down_layout, int dtype, int64_t d, int64_t N, void* Y, hipStream_t s) {
+  GemmArgs g;
+  g.A = H;
+  g.lda = N;
+  g.B0 = w_down;
+  g.B1 = nullptr;
+  g.bias = b_down;
+  g.out_e = Y;
+  g.out_f = nullptr;
+  g.ldo = d;
+  g.M = (int)M;
+  g.Nn = (int)d;
+  g.Kk = (int)N;
+  if (down_layout == CI_DOWN_OUT_MAJOR) {
+    g.ldb = N;
+    return launch_any<EPI_LINEAR, false>(dtype, g, s);
+  }
+  g.ldb = d;
+  return launch_any<EPI_LINEAR, true>(dtype, g, s);
+}
+
+}  // namespace ci

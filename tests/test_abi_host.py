@@ -1,0 +1,166 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+what include/coreinfer.h declares, and rejects bad arguments before touching
+the device (validation precedes every HIP call)."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import coreinfer_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "coreinfer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(coreinfer_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = _declared_symbols()
+    assert len(names) >= 11
+    for n in names:
+        assert hasattr(lib.raw, n), n
+    assert set(names) == set(lib.EXPORTS)
+    assert lib.version() >= 1
+
+
+def test_strerror_names_every_status(lib):
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5, -6):
+        s = lib.strerror(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 7
+    assert lib.strerror(-99) == "unknown status"
+
+
+def test_keep_count_agrees_with_the_oracle_rule(lib):
+    for n in (0, 1, 2, 3, 7, 10, 30, 1024, 11008, 13824, 16384, 36864):
+        for f in (1e-6, 0.01, 0.1, 0.2, 0.25, 0.3, 1 / 3, 0.34, 0.4, 0.5, 0.6, 0.999999, 1.0):
+            assert lib.keep_count(f, n) == orc.keep_count(f, n), (f, n)
+    assert lib.keep_count(0.4, 16384) == 6554 and lib.keep_count(0.4, 36864) == 14746
+    k = ctypes.c_int64(0)
+    for bad in (0.0, -0.1, 1.0000001, float("nan"), 1e-9):
+        assert lib.raw.coreinfer_keep_count(bad, 10, ctypes.byref(k)) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_keep_count(0.5, -1, ctypes.byref(k)) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_keep_count(0.5, 10, None) == lib.CI_ERR_INVALID_ARG
+
+
+def test_workspace_sizes(lib):
+    assert lib.select_workspace_size(256, 16384) >= 16384 * 4
+    assert lib.ffn_decode_workspace_size(1, 6554, 4096) >= 1024 * 4096 * 4
+    assert lib.ffn_decode_workspace_size(1, 10, 256) >= 10 * 256 * 4
+    assert lib.ffn_decode_workspace_size(8, 14746, 9216) >= 8 * 1024 * 9216 * 4
+    import torch
+    assert lib.ffn_dense_workspace_size(256, 4096, 16384, torch.float16) >= 256 * 16384 * 2
+    b = ctypes.c_size_t(0)
+    assert lib.raw.coreinfer_select_workspace_size(0, 10, ctypes.byref(b)) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_select_workspace_size(70000, 10, ctypes.byref(b)) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_select_workspace_size(4, 10, None) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_ffn_decode_workspace_size(0, 10, 64, ctypes.byref(b)) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_ffn_dense_workspace_size(4, 64, 64, 9, ctypes.byref(b)) == lib.CI_ERR_BAD_DTYPE
+
+
+FAKE = 0x10000  # a non-null, 16-byte aligned address that is never dereferenced on these paths
+
+
+def test_select_rejects_bad_arguments_without_a_gpu(lib):
+    r = lib.raw.coreinfer_select
+    ok_ws = 1 << 20
+    assert r(None, 4, 64, 64, 0.2, 0.4, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 4, 64, 64, 0.2, 0.4, None, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 0, 64, 64, 0.2, 0.4, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 4, 64, 64, 0.0, 0.4, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 4, 64, 64, 0.2, 1.5, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 4, 64, 32, 0.2, 0.4, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(FAKE + 2, 4, 64, 64, 0.2, 0.4, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(FAKE, 4, 64, 64, 0.2, 0.4, FAKE, None, None, ok_ws, None) == lib.CI_ERR_WORKSPACE
+    assert r(FAKE, 4, 64, 64, 0.2, 0.4, FAKE, None, FAKE, 16, None) == lib.CI_ERR_WORKSPACE
+
+
+def test_compact_rejects_bad_arguments_without_a_gpu(lib):
+    r = lib.raw.coreinfer_compact
+    F = FAKE
+    # (w_up, w_gate, b_up, w_down, layout, dtype, act, d, N, idx, K, up_c, gate_c, b_c, down_c, status, stream)
+    assert r(F, None, None, F, 0, 7, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, None, None, F, 0, 1, 5, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, None, None, F, 3, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(None, None, None, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 200, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, None, 8, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
+    # gate given for ReLU / missing for SwiGLU; bias in without bias out
+    assert r(F, F, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, F, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 1, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, F, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
+    # d not a multiple of 8 halfs; misaligned pointer
+    assert r(F, None, None, F, 0, 1, 0, 60, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F + 8, None, None, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_LAYOUT
+
+
+def test_ffn_decode_rejects_bad_arguments_without_a_gpu(lib):
+    r = lib.raw.coreinfer_ffn_decode
+    F = FAKE
+    big = 1 << 30
+
+    def W(**kw):
+        base = dict(w_up=F, w_gate=None, b_up=None, w_down=F, b_down=None, core_idx=None, K=16, d=64, N=16)
+        base.update(kw)
+        return ctypes.byref(lib.ci_ffn_weights(**base))
+
+    assert r(F, 1, None, 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, W(), 9, 0, F, F, big, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, 1, W(), 1, 2, F, F, big, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(None, 1, W(), 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, W(), 1, 0, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 0, W(), 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, W(w_up=None), 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, W(), 1, 1, F, F, big, None) == lib.CI_ERR_INVALID_ARG          # SwiGLU without gate
+    assert r(F, 1, W(w_gate=F), 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG   # ReLU with gate
+    assert r(F, 1, W(d=60), 1, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 1, W(d=62), 0, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F + 4, 1, W(), 1, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 1, W(core_idx=F, N=0), 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, W(), 1, 0, F, None, big, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 1, W(), 1, 0, F, F, 64, None) == lib.CI_ERR_WORKSPACE
+
+
+def test_ffn_dense_rejects_bad_arguments_without_a_gpu(lib):
+    r = lib.raw.coreinfer_ffn_dense
+    F = FAKE
+    big = 1 << 30
+    # (X, M, w_up, w_gate, b_up, w_down, b_down, layout, dtype, act, d, N, Y, A, ws, ws_bytes, stream)
+    assert r(F, 8, F, None, None, F, None, 0, 5, 0, 64, 128, F, None, F, big, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, 8, F, None, None, F, None, 2, 1, 0, 64, 128, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(None, 8, F, None, None, F, None, 0, 1, 0, 64, 128, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 8, F, None, None, F, None, 0, 1, 0, 64, 128, None, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 8, F, None, None, None, None, 0, 1, 0, 64, 128, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 8, F, None, None, F, None, 0, 1, 1, 64, 128, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 8, F, None, None, F, None, 0, 1, 0, 64, 100, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 8, F, None, None, F, None, 0, 1, 0, 64, 128, F, None, None, big, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 8, F, None, None, F, None, 0, 1, 0, 64, 128, F, None, F, 100, None) == lib.CI_ERR_WORKSPACE
+
+
+def test_set_param_validation(lib):
+    assert lib.raw.coreinfer_set_param(b"no_such_knob", 1) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_set_param(b"decode_wgs_per_cu", 0) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_set_param(None, 1) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_set_param(b"decode_wgs_per_cu", 2) == lib.CI_OK
+
+
+def test_workloads_module_has_the_five_configurations():
+    from paper_2410_18311_amd import workloads as wl
+    assert len(wl.WORKLOADS) == 5
+    c2 = wl.WORKLOADS["opt6.7b_relu_f16"]
+    assert (c2.d, c2.N, c2.L, c2.M, c2.alpha, c2.betas) == (4096, 16384, 32, 256, 0.2, (0.4,))
+    t = wl.tiny_relu_f32_numpy()
+    assert t["w_up"].shape == (1024, 256) and t["w_down"].shape == (256, 1024)
+    assert t["x_prefill"].shape == (32, 256) and t["x_decode"].shape == (16, 256)
+    small = c2.scaled(d=64, N=128, M=4, L=1)
+    w = wl.layer_weights(small, 0)
+    assert w["w_up"].shape == (128, 64) and w["w_down"].shape == (64, 128) and w["w_gate"] is None
+    again = wl.layer_weights(small, 0)
+    assert (w["w_up"] == again["w_up"]).all()

@@ -1,0 +1,391 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the
+same seeded inputs.  Index sets and counts bit-exact; FFN outputs within
+TOL * rms(oracle output) (tests/_util.py)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import coreinfer_oracle as orc
+from paper_2410_18311_amd import workloads as wl
+from tests._util import TOL, assert_close_rms, down_out_major64, f64, rand_weights
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# --------------------------------------------------------------------- select
+
+def _select_case(lib, A_np, alpha, beta, what):
+    _say("select case", what, A_np.shape, alpha, beta)
+    A = torch.from_numpy(np.ascontiguousarray(A_np, dtype=np.float32)).to(DEV)
+    S_gpu, c_gpu = lib.select(A, alpha, beta)
+    torch.cuda.synchronize()
+    S_ref, c_ref = orc.select(A_np.astype(np.float32), alpha, beta)
+    assert c_gpu.cpu().numpy().astype(np.int64).tolist() == c_ref.tolist(), what + ": counts"
+    assert S_gpu.cpu().numpy().astype(np.int64).tolist() == S_ref.tolist(), what + ": core set"
+
+
+@pytest.mark.parametrize("M,N,kind,levels,alpha,beta", [
+    (1, 1, "abs", 0, 0.2, 0.4),
+    (1, 64, "relu", 0, 0.5, 0.5),
+    (3, 100, "raw", 0, 0.2, 0.4),
+    (32, 1024, "relu", 0, 0.2, 0.4),
+    (7, 4097, "relu", 0, 0.2, 0.4),
+    (17, 4100, "abs", 5, 0.3, 0.25),          # heavy ties in the activations
+    (64, 11008, "abs", 0, 0.2, 0.4),
+    (33, 16384, "relu", 0, 0.2, 0.4),
+    (300, 2048, "relu", 0, 0.2, 0.4),          # more tokens than workgroups: LDS-private counters
+    (700, 1500, "abs", 3, 0.1, 0.6),
+    (5, 36864, "relu", 0, 0.2, 0.4),
+    (3, 50000, "abs", 0, 0.05, 0.1),           # beyond the register-cached sizes
+    (9, 13824, "abs", 0, 1.0, 1.0),
+    (9, 1000, "relu", 2, 1.0, 0.001),
+])
+def test_select_matches_oracle(lib, M, N, kind, levels, alpha, beta):
+    A = wl.activation_like(M, N, seed=M * 131 + N, kind=kind, levels=levels)
+    _select_case(lib, A, alpha, beta, f"{kind}/{levels}")
+
+
+def test_select_degenerate_rows(lib):
+    rng = np.random.default_rng(5)
+    N = 3000
+    A = np.abs(rng.standard_normal((12, N))).astype(np.float32)
+    A[0] = 0.0                      # no positive activation at all
+    A[1] = 1.25                     # every neuron tied
+    A[2] = -np.abs(A[2])            # all negative
+    A[3, ::2] = np.nan              # NaN is never positive
+    A[4, 7] = np.inf                # +inf ranks first
+    A[5, :] = 0.0
+    A[5, 2999] = 1e-45              # a single denormal positive
+    A[6] = np.float32(1e-38) * np.arange(1, N + 1, dtype=np.float32) / N   # tiny values, low exponents
+    A[7, 100:] = 0.0
+    A[8] = np.repeat(np.arange(N // 4, dtype=np.float32), 4)[:N]           # runs of four equal values
+    _select_case(lib, A, 0.2, 0.4, "degenerate")
+    _select_case(lib, A, 0.5, 0.05, "degenerate2")
+    _select_case(lib, np.zeros((4, 257), dtype=np.float32), 0.2, 0.4, "all-zero sentence")
+
+
+def test_select_strided_rows_and_null_counts(lib):
+    M, N, ld = 10, 1000, 1024
+    A_np = wl.activation_like(M, ld, seed=3, kind="relu")
+    A = torch.from_numpy(A_np).to(DEV)
+    view = A[:, :N]
+    K = lib.keep_count(0.4, N)
+    core = torch.empty(K, dtype=torch.int32, device=DEV)
+    ws = torch.empty(lib.select_workspace_size(M, N), dtype=torch.uint8, device=DEV)
+    rc = lib.raw.coreinfer_select(view.data_ptr(), M, N, ld, 0.2, 0.4, core.data_ptr(), None,
+                                  ws.data_ptr(), ws.numel(), None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    S_ref, _ = orc.select(A_np[:, :N], 0.2, 0.4)
+    assert core.cpu().numpy().tolist() == S_ref.tolist()
+
+
+def test_select_is_deterministic_and_permutation_invariant(lib):
+    A_np = wl.activation_like(200, 4096, seed=9, kind="relu", levels=8)
+    A = torch.from_numpy(A_np).to(DEV)
+    S1, c1 = lib.select(A, 0.2, 0.4)
+    S2, c2 = lib.select(A, 0.2, 0.4)
+    perm = torch.randperm(200, generator=torch.Generator().manual_seed(1)).to(DEV)
+    S3, c3 = lib.select(A[perm].contiguous(), 0.2, 0.4)
+    torch.cuda.synchronize()
+    assert torch.equal(S1, S2) and torch.equal(c1, c2)
+    assert torch.equal(S1, S3) and torch.equal(c1, c3)
+
+
+# -------------------------------------------------------------------- compact
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("act,layout", [("relu", "out_major"), ("swiglu", "out_major"), ("relu", "neuron_major")])
+@pytest.mark.parametrize("d,N,K", [(64, 200, 77), (1024, 3000, 1201), (256, 1024, 1024), (8, 5, 1)])
+def test_compact_matches_oracle(lib, dt, act, layout, d, N, K):
+    _say("compact case", dt, act, layout, d, N, K)
+    dtype = DTYPES[dt]
+    if dt == "f32" and d % 4:
+        pytest.skip("d must be a multiple of 4")
+    w = rand_weights(d, N, dtype, act, layout, seed=d + N + K, device=DEV)
+    S = np.sort(np.random.default_rng(K).choice(N, size=K, replace=False))
+    idx = torch.from_numpy(S.astype(np.int32)).to(DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    out = lib.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], layout, act, idx, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    ref = orc.compact(S, f64(w["w_up"]), down_out_major64(w, layout), f64(w["w_gate"]), f64(w["b_up"]))
+    assert np.array_equal(f64(out["w_up_c"]), ref["w_up_c"])
+    assert np.array_equal(f64(out["w_down_c"]), ref["w_down_c"])
+    if act == "swiglu":
+        assert np.array_equal(f64(out["w_gate_c"]), ref["w_gate_c"])
+    if w["b_up"] is not None:
+        assert np.array_equal(f64(out["b_up_c"]), ref["b_up_c"])
+
+
+def test_compact_flags_bad_indices_without_faulting(lib):
+    d, N = 64, 100
+    w = rand_weights(d, N, torch.float16, "relu", "out_major", seed=1, device=DEV)
+    idx = torch.tensor([3, 5, 5, 250, -1, 40, 41], dtype=torch.int32, device=DEV)  # repeat, out of range, descending
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    out = lib.compact(w["w_up"], None, w["b_up"], w["w_down"], "out_major", "relu", idx, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 1
+    up_c, down_c = f64(out["w_up_c"]), f64(out["w_down_c"])
+    W_up, W_down = f64(w["w_up"]), f64(w["w_down"])
+    for k, n in enumerate([3, 5, None, None, None, 40, 41]):
+        if n is None:
+            assert not up_c[k].any() and not down_c[k].any()
+        else:
+            assert np.array_equal(up_c[k], W_up[n]) and np.array_equal(down_c[k], W_down[:, n])
+
+
+# --------------------------------------------------------------------- decode
+
+def _oracle_ffn(act, x, S, w, layout):
+    Wd = down_out_major64(w, layout)
+    if act == "relu":
+        return orc.ffn_relu(f64(x), S, f64(w["w_up"]), f64(w["b_up"]), Wd, f64(w["b_down"]))
+    return orc.ffn_swiglu(f64(x), S, f64(w["w_gate"]), f64(w["w_up"]), Wd, f64(w["b_down"]))
+
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("act", ["relu", "swiglu"])
+@pytest.mark.parametrize("d,N,K,B", [
+    (256, 1024, 410, 1), (64, 300, 1, 2), (1000, 2500, 999, 1), (4096, 3000, 1201, 1),
+    (5120, 1500, 577, 3), (9216, 700, 333, 2), (2048, 4000, 2765, 1),
+])
+def test_decode_compacted_matches_oracle(lib, dt, act, d, N, K, B):
+    _say("decode compact case", dt, act, d, N, K, B)
+    dtype = DTYPES[dt]
+    w = rand_weights(d, N, dtype, act, "out_major", seed=d * 7 + K, device=DEV)
+    S = np.sort(np.random.default_rng(K + 1).choice(N, size=K, replace=False))
+    idx = torch.from_numpy(S.astype(np.int32)).to(DEV)
+    c = lib.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], "out_major", act, idx)
+    x = torch.randn(B, d, generator=torch.Generator().manual_seed(d + B)).to(dtype).to(DEV)
+    desc = lib.make_weights(c["w_up_c"], c["w_gate_c"], c["b_up_c"], c["w_down_c"], w["b_down"])
+    y = lib.ffn_decode(x, desc, act)
+    y2 = lib.ffn_decode(x, desc, act)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2), "decode must be deterministic"
+    assert_close_rms(y, _oracle_ffn(act, x, S, w, "out_major"), dtype, "decode compacted")
+
+
+@pytest.mark.parametrize("dt,act", [("f16", "relu"), ("bf16", "swiglu"), ("f32", "relu")])
+@pytest.mark.parametrize("d,N,K,B", [(512, 2000, 801, 4), (9216, 1200, 480, 8), (64, 64, 64, 1)])
+def test_decode_gathered_matches_oracle(lib, dt, act, d, N, K, B):
+    _say("decode gathered case", dt, act, d, N, K, B)
+    dtype = DTYPES[dt]
+    w = rand_weights(d, N, dtype, act, "neuron_major", seed=d + N, device=DEV)
+    rng = np.random.default_rng(B * 100 + K)
+    S = np.stack([np.sort(rng.choice(N, size=K, replace=False)) for _ in range(B)])
+    idx = torch.from_numpy(S.astype(np.int32)).to(DEV)
+    x = torch.randn(B, d, generator=torch.Generator().manual_seed(K)).to(dtype).to(DEV)
+    desc = lib.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], core_idx=idx)
+    y = lib.ffn_decode(x, desc, act)
+    torch.cuda.synchronize()
+    for b in range(B):
+        assert_close_rms(y[b], _oracle_ffn(act, x[b], S[b], w, "neuron_major"), dtype, f"gathered b={b}")
+
+
+def test_decode_gathered_ignores_out_of_range_entries(lib):
+    d, N, K = 256, 500, 40
+    w = rand_weights(d, N, torch.float16, "relu", "neuron_major", seed=2, device=DEV)
+    S = np.sort(np.random.default_rng(0).choice(N, size=K, replace=False))
+    bad = S.copy().astype(np.int64)
+    bad[[3, 17]] = [-5, N + 9]
+    idx = torch.from_numpy(bad.astype(np.int32)).to(DEV).unsqueeze(0)
+    x = torch.randn(1, d, generator=torch.Generator().manual_seed(1)).half().to(DEV)
+    y = lib.ffn_decode(x, lib.make_weights(w["w_up"], None, w["b_up"], w["w_down"], w["b_down"], core_idx=idx), "relu")
+    torch.cuda.synchronize()
+    keep = np.delete(S, [3, 17])
+    assert_close_rms(y[0], _oracle_ffn("relu", x[0], keep, w, "neuron_major"), torch.float16, "skip invalid")
+
+
+def test_decode_empty_core_set_gives_the_output_bias(lib):
+    d = 128
+    b_down = (torch.randn(d) * 0.1).half().to(DEV)
+    dummy = torch.zeros(1, d, dtype=torch.float16, device=DEV)
+    x = torch.randn(2, d).half().to(DEV)
+    desc = lib.make_weights(dummy, None, None, dummy, b_down, K=0)
+    y = lib.ffn_decode(x, desc, "relu")
+    torch.cuda.synchronize()
+    assert torch.equal(y[0], b_down) and torch.equal(y[1], b_down)
+
+
+# ---------------------------------------------------------------------- dense
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("act,layout", [("relu", "out_major"), ("swiglu", "out_major"),
+                                        ("relu", "neuron_major"), ("swiglu", "neuron_major")])
+@pytest.mark.parametrize("M,d,N", [(1, 256, 1024), (3, 512, 1000), (32, 256, 1024), (130, 320, 520), (256, 1024, 768)])
+def test_dense_matches_oracle(lib, dt, act, layout, M, d, N):
+    _say("dense case", dt, act, layout, M, d, N)
+    dtype = DTYPES[dt]
+    w = rand_weights(d, N, dtype, act, layout, seed=M + d + N, device=DEV)
+    X = torch.randn(M, d, generator=torch.Generator().manual_seed(M)).to(dtype).to(DEV)
+    Y, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], layout, act,
+                         want_y=True, want_a=True)
+    torch.cuda.synchronize()
+    if act == "relu":
+        A_ref = orc.score_relu(f64(X), f64(w["w_up"]), f64(w["b_up"]))
+    else:
+        A_ref = orc.score_swiglu(f64(X), f64(w["w_gate"]), f64(w["w_up"]))
+    # the scores are fp32 whatever the element type: hold them to the fp32 bar
+    # (1e-5 * rms would be below fp32 summation noise for 16-bit inputs of length d; use 1e-4)
+    rms = np.sqrt(np.mean(A_ref ** 2))
+    assert np.max(np.abs(f64(A) - A_ref)) <= 1e-4 * rms
+    assert_close_rms(Y, _oracle_ffn(act, X, None, w, layout), dtype, "dense Y")
+    # A only (no Y) must give the same scores
+    _, A2 = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], None, None, layout, act,
+                          want_y=False, want_a=True)
+    torch.cuda.synchronize()
+    assert torch.equal(A, A2)
+
+
+# ------------------------------------------------------------- whole small path
+
+def test_tiny_fp32_configuration_end_to_end(lib):
+    """The small fp32 configuration, whole: prefill 32 tokens, select, compact,
+    16 decode steps; every stage against the oracle."""
+    cfg = wl.WORKLOADS["tiny_relu_f32"]
+    t = wl.tiny_relu_f32_numpy()
+    g = {k: (None if v is None else torch.from_numpy(v).to(DEV)) for k, v in t.items()}
+    Y, A = lib.ffn_dense(g["x_prefill"], g["w_up"], None, g["b_up"], g["w_down"], g["b_down"],
+                         "out_major", "relu", want_y=True, want_a=True)
+    torch.cuda.synchronize()
+    A_ref = orc.score_relu(t["x_prefill"], t["w_up"], t["b_up"])
+    assert_close_rms(A, A_ref, torch.float32, "prefill scores")
+    assert_close_rms(Y, orc.ffn_relu(t["x_prefill"], None, t["w_up"], t["b_up"], t["w_down"], t["b_down"]),
+                     torch.float32, "prefill Y")
+    # selection: bit-exact on identical activation bits (the GPU's own fp32 A) ...
+    S_gpu, c_gpu = lib.select(A, cfg.alpha, cfg.betas[0])
+    torch.cuda.synchronize()
+    S_ref, c_ref = orc.select(A.cpu().numpy(), cfg.alpha, cfg.betas[0])
+    assert S_gpu.cpu().numpy().tolist() == S_ref.tolist() and len(S_ref) == 410
+    assert c_gpu.cpu().numpy().tolist() == c_ref.tolist()
+    # ... and on the oracle's activations rounded to fp32
+    A32 = A_ref.astype(np.float32)
+    S_gpu2, _ = lib.select(torch.from_numpy(A32).to(DEV), cfg.alpha, cfg.betas[0])
+    S_ref2, _ = orc.select(A32, cfg.alpha, cfg.betas[0])
+    assert S_gpu2.cpu().numpy().tolist() == S_ref2.tolist()
+    _say("tiny: core-set similarity GPU-A vs oracle-A:", orc.core_similarity(S_ref, S_ref2))
+    # deploy + decode
+    c = lib.compact(g["w_up"], None, g["b_up"], g["w_down"], "out_major", "relu", S_gpu)
+    ref_c = orc.compact(S_ref, t["w_up"], t["w_down"], None, t["b_up"])
+    assert np.array_equal(c["w_up_c"].cpu().numpy(), ref_c["w_up_c"])
+    assert np.array_equal(c["w_down_c"].cpu().numpy(), ref_c["w_down_c"])
+    assert np.array_equal(c["b_up_c"].cpu().numpy(), ref_c["b_up_c"])
+    desc = lib.make_weights(c["w_up_c"], None, c["b_up_c"], c["w_down_c"], g["b_down"])
+    for i in range(cfg.decode_tokens):
+        y = lib.ffn_decode(g["x_decode"][i], desc, "relu")
+        y_ref = orc.ffn_relu(t["x_decode"][i], S_ref, t["w_up"], t["b_up"], t["w_down"], t["b_down"])
+        assert_close_rms(y, y_ref, torch.float32, f"decode token {i}")
+    # dense decode (one token through ffn_dense) against the dense oracle
+    Yd, _ = lib.ffn_dense(g["x_decode"][:1], g["w_up"], None, g["b_up"], g["w_down"], g["b_down"],
+                          "out_major", "relu")
+    assert_close_rms(Yd[0], orc.ffn_relu(t["x_decode"][0], None, t["w_up"], t["b_up"], t["w_down"], t["b_down"]),
+                     torch.float32, "dense decode")
+
+
+def test_keep_fraction_one_reproduces_the_dense_ffn(lib):
+    d, N, M = 512, 1536, 24
+    for dt, act in (("f16", "relu"), ("bf16", "swiglu")):
+        dtype = DTYPES[dt]
+        w = rand_weights(d, N, dtype, act, "out_major", seed=77, device=DEV)
+        X = torch.randn(M, d, generator=torch.Generator().manual_seed(4)).to(dtype).to(DEV)
+        _, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], "out_major", act,
+                             want_y=False, want_a=True)
+        S, _ = lib.select(A, 0.2, 1.0)
+        torch.cuda.synchronize()
+        assert S.cpu().numpy().tolist() == list(range(N))
+        c = lib.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], "out_major", act, S)
+        assert torch.equal(c["w_up_c"], w["w_up"]) and torch.equal(c["w_down_c"], w["w_down"].t().contiguous())
+        x = X[:1].contiguous()
+        y = lib.ffn_decode(x, lib.make_weights(c["w_up_c"], c["w_gate_c"], c["b_up_c"], c["w_down_c"], w["b_down"]), act)
+        assert_close_rms(y[0], _oracle_ffn(act, x[0], None, w, "out_major"), dtype, "beta=1 vs dense oracle")
+
+
+# ---------------------------------------------- full-size layers, bench launch shape
+
+def _full_layer(lib, name, beta, check_sentences=1):
+    cfg = wl.WORKLOADS[name]
+    _say("full-size layer", name, "beta", beta)
+    dtype = cfg.torch_dtype
+    w = wl.layer_weights(cfg, 0, DEV)
+    X = wl.prefill_hidden(cfg, 0, DEV)
+    _, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], None, None, cfg.down_layout, cfg.act,
+                         want_y=False, want_a=True)
+    S, counts = lib.select(A, cfg.alpha, beta)
+    torch.cuda.synchronize()
+    # sampled rows of A against the oracle (full rows would need the whole fp64 product)
+    rows = [0, cfg.M // 2, cfg.M - 1]
+    Wu = f64(w["w_up"])
+    if cfg.act == "relu":
+        A_ref = orc.score_relu(f64(X[rows]), Wu, f64(w["b_up"]))
+    else:
+        A_ref = orc.score_swiglu(f64(X[rows]), f64(w["w_gate"]), Wu)
+    rms = np.sqrt(np.mean(A_ref ** 2))
+    assert np.max(np.abs(f64(A[rows]) - A_ref)) <= 1e-4 * rms, "prefill scores"
+    # selection bit-exact on the GPU's own activation bits
+    S_ref, c_ref = orc.select(A.cpu().numpy(), cfg.alpha, beta)
+    assert counts.cpu().numpy().tolist() == c_ref.tolist()
+    assert S.cpu().numpy().tolist() == S_ref.tolist()
+    assert len(S_ref) == orc.keep_count(beta, cfg.N)
+    return cfg, w, S, S_ref, Wu
+
+
+@pytest.mark.parametrize("name,beta", [("opt6.7b_relu_f16", 0.4), ("llama2_7b_swiglu_bf16", 0.4),
+                                       ("llama2_13b_swiglu_bf16", 0.2)])
+def test_full_size_layer_compacted(lib, name, beta):
+    cfg, w, S, S_ref, Wu = _full_layer(lib, name, beta)
+    c = lib.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act, S)
+    desc = lib.make_weights(c["w_up_c"], c["w_gate_c"], c["b_up_c"], c["w_down_c"], w["b_down"])
+    x = wl.decode_hidden(cfg, 0, DEV, tokens=3)
+    Wd = f64(w["w_down"])
+    Wg = f64(w["w_gate"])
+    for i in range(3):
+        y = lib.ffn_decode(x[i], desc, cfg.act)
+        if cfg.act == "relu":
+            y_ref = orc.ffn_relu(f64(x[i]), S_ref, Wu, f64(w["b_up"]), Wd, f64(w["b_down"]))
+        else:
+            y_ref = orc.ffn_swiglu(f64(x[i]), S_ref, Wg, Wu, Wd, f64(w["b_down"]))
+        rel = assert_close_rms(y, y_ref, cfg.torch_dtype, f"{name} decode token {i}")
+        _say(f"  token {i}: max err / rms = {rel:.2e}")
+
+
+def test_full_size_layer_gathered_eight_sentences(lib):
+    """OPT-66B-shaped layer, eight sentences with their own core sets, rows
+    gathered from the resident weights (two sentences checked on the CPU)."""
+    cfg = wl.WORKLOADS["opt66b_relu_f16_8sent"]
+    _say("full-size gathered layer", cfg.name)
+    w = wl.layer_weights(cfg, 0, DEV)
+    sets = []
+    for s in range(cfg.sentences):
+        X = wl.prefill_hidden(cfg, 0, DEV, sentence=s)
+        _, A = lib.ffn_dense(X, w["w_up"], None, w["b_up"], None, None, cfg.down_layout, "relu",
+                             want_y=False, want_a=True)
+        S, counts = lib.select(A, cfg.alpha, cfg.betas[0])
+        if s in (0, 5):
+            S_ref, c_ref = orc.select(A.cpu().numpy(), cfg.alpha, cfg.betas[0])
+            assert counts.cpu().numpy().tolist() == c_ref.tolist()
+            assert S.cpu().numpy().tolist() == S_ref.tolist() and len(S_ref) == 14746
+        sets.append(S)
+        del A, X
+    idx = torch.stack(sets).contiguous()
+    x = torch.stack([wl.decode_hidden(cfg, 0, DEV, sentence=s, tokens=1)[0] for s in range(cfg.sentences)])
+    desc = lib.make_weights(w["w_up"], None, w["b_up"], w["w_down"], w["b_down"], core_idx=idx)
+    y = lib.ffn_decode(x, desc, "relu")
+    torch.cuda.synchronize()
+    for s in (0, 5):
+        Sn = sets[s].cpu().numpy().astype(np.int64)
+        up_rows = f64(w["w_up"][sets[s].long()])
+        down_rows = f64(w["w_down"][sets[s].long()])          # neuron-major rows
+        # the oracle proper, fed the pre-gathered rows as a dense layer (bounds host memory:
+        # the full fp64 matrices would take 5.4 GB); indexing by S is what its own S path does
+        y_ref = orc.ffn_relu(f64(x[s]), None, up_rows, f64(w["b_up"])[Sn], down_rows.T, f64(w["b_down"]))
+        rel = assert_close_rms(y[s], y_ref, torch.float16, f"gathered sentence {s}")
+        _say(f"  sentence {s}: max err / rms = {rel:.2e}")
