@@ -109,10 +109,12 @@ int device_info(DeviceInfo* out);
 
 // Development knobs (see coreinfer_set_param).
 struct Params {
-  int decode_wgs_per_cu = 2;
+  int decode_wgs_per_cu = 1;
   int decode_threads = 0;  // 0 = derived from d
+  int decode_depth = 4;    // weight rows in flight per thread (4, 8 or 16)
   int select_wgs_per_cu = 1;
   int gemv_wgs_per_cu = 4;
+  int decode_skip_reduce = 0;  // timing only: launch the slice kernel without the reduction
 };
 Params& params();
 

@@ -18,7 +18,7 @@ namespace ci {
 
 namespace {
 
-constexpr int kSuper = 128;  // rows of a slice handled between two barriers
+constexpr int kSuper = 64;  // rows of a slice handled between two barriers (<= smallest workgroup)
 
 struct DecodeArgs {
   const void* x;
@@ -31,13 +31,92 @@ struct DecodeArgs {
   int K, d, N, n_wg;
 };
 
-template <class D, int NI, bool SWIGLU, bool GATHER>
-__global__ __launch_bounds__(1024) void ffn_decode_kernel(DecodeArgs a) {
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte streaming load: the weights are read once per token and never
+// reused, so they are marked non-temporal.
+__device__ __forceinline__ uint4 ld16_stream(const void* p) {
+  const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(t[0], t[1], t[2], t[3]);
+}
+
+// Sums DEPTH per-lane values across the wave with a halving butterfly: after
+// the call every lane holds the wave-wide sum of value number
+// lane / (64 / DEPTH) -- for DEPTH = 8, 10 shuffles instead of 48.
+template <int N, int BIT>
+__device__ __forceinline__ void halve_rows(float* v, int lane) {
+  if constexpr (N > 1) {
+    const bool hi = (lane & BIT) != 0;
+#pragma unroll
+    for (int i = 0; i < N / 2; ++i) {
+      const float send = hi ? v[i] : v[i + N / 2];
+      const float keep = hi ? v[i + N / 2] : v[i];
+      v[i] = keep + __shfl_xor(send, BIT, kWave);
+    }
+    halve_rows<N / 2, BIT / 2>(v, lane);
+  } else {
+    float r = v[0];
+#pragma unroll
+    for (int bit = BIT; bit >= 1; bit >>= 1) r += __shfl_xor(r, bit, kWave);
+    v[0] = r;
+  }
+}
+template <int DEPTH>
+__device__ __forceinline__ float wave_sum_rows(float (&v)[DEPTH], int lane) {
+  static_assert(DEPTH == 4 || DEPTH == 8 || DEPTH == 16, "ring depth");
+  halve_rows<DEPTH, 32>(v, lane);
+  return v[0];
+}
+
+// Weight row that super-chunk-local neuron r names (gathered: through the
+// index list staged in LDS, -1 = skip; compacted: consecutive rows).
+template <bool GATHER>
+__device__ __forceinline__ size_t decode_row_of(int r, int row_base, const int* sidx) {
+  if (GATHER) {
+    const int n = sidx[r];
+    return n < 0 ? (size_t)0 : (size_t)n;
+  }
+  return (size_t)(row_base + r);
+}
+
+// Issues the 16-byte loads of ring position `pos` into one register slot.
+// Ring positions of one super-chunk of Rs neurons (QB = NDOT * Rs dot rows):
+//   [0, lead)               filler so that lead + QB is a multiple of DEPTH
+//   [lead, lead + QB)       rows of the gate (SwiGLU only) and up matrices -> dot with x
+//   [lead + QB, NQ)         rows of the down matrix                        -> axpy into y
+//   [NQ, ...)               filler
+// EVERY position issues its loads, filler positions from the (cache-resident)
+// x vector: with the same number of loads on every control path the compiler
+// can count outstanding loads exactly and waits only for the slot it consumes.
+template <class T, int NI, bool SWIGLU, bool GATHER>
+__device__ __forceinline__ void decode_issue(int pos, int lead, int Rs, int QB, int NQ,
+                                             const char* __restrict__ gate,
+                                             const char* __restrict__ up,
+                                             const char* __restrict__ down,
+                                             const char* __restrict__ filler, size_t rowbytes,
+                                             int row_base, const int* sidx,
+                                             const uint32_t (&coff)[NI], uint4 (&dst)[NI]) {
+  const int q = pos - lead;
+  const bool valid = q >= 0 && pos < NQ;
+  const bool is_dot = q < QB;
+  const bool second = SWIGLU && q >= Rs;  // SwiGLU: gate rows first, then up rows
+  int r = is_dot ? (second ? q - Rs : q) : q - QB;
+  r = r < 0 ? 0 : (r > Rs - 1 ? Rs - 1 : r);
+  const char* base = is_dot ? ((SWIGLU && !second) ? gate : up) : down;
+  const char* prow = base + decode_row_of<GATHER>(r, row_base, sidx) * rowbytes;
+  prow = valid ? prow : filler;
+#pragma unroll
+  for (int i = 0; i < NI; ++i) dst[i] = ld16_stream(prow + coff[i]);
+}
+
+// DEPTH rows are always in flight per thread; the loads of the down rows are
+// issued while the dots are still being reduced, so the memory pipeline never
+// drains at the phase boundary.
+template <class D, int NI, bool SWIGLU, bool GATHER, int DEPTH>
+__global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(DecodeArgs a) {
   using T = typename D::T;
   constexpr int VEC = D::VEC;
-  // rows in flight per thread: at most 16 sixteen-byte loads outstanding
-  constexpr int RCB = NI <= 2 ? 8 : 4;            // phase B
-  constexpr int RCA = SWIGLU ? RCB / 2 : RCB;     // phase A (two matrices when gated)
+  constexpr int NDOT = SWIGLU ? 2 : 1;  // matrices that are dotted with x
 
   extern __shared__ float smem[];
   const int tid = threadIdx.x, nt = blockDim.x;
@@ -47,39 +126,29 @@ __global__ __launch_bounds__(1024) void ffn_decode_kernel(DecodeArgs a) {
   const int r1 = (int)(((int64_t)(wg + 1) * a.K) / a.n_wg);
   const int R = r1 - r0;
 
-  float* red_u = smem;                         // [nw][kSuper]
-  float* red_g = red_u + nw * kSuper;          // [nw][kSuper] (SwiGLU only)
-  float* hbuf = SWIGLU ? red_g + nw * kSuper : red_g;  // [kSuper]
+  float* red = smem;                            // [nw][NDOT * kSuper] wave partial dots
+  float* hbuf = red + nw * NDOT * kSuper;       // [kSuper] hidden values
+  int* sidx = reinterpret_cast<int*>(hbuf + kSuper);  // [kSuper] weight row of each slice neuron (-1: skip)
 
-  const int32_t* idx = GATHER ? a.core_idx + (size_t)b * a.K + r0 : nullptr;
   const size_t rowbytes = (size_t)a.d * sizeof(T);
   const char* up = reinterpret_cast<const char*>(a.w_up);
   const char* gate = reinterpret_cast<const char*>(a.w_gate);
   const char* down = reinterpret_cast<const char*>(a.w_down);
-
-  // Row of the weight matrices that slice-local neuron r names; `ok` is false
-  // for a gathered index outside [0, N) (it then contributes nothing).
-  auto row_of = [&](int r, bool& ok) -> size_t {
-    if (GATHER) {
-      int n = idx[r];
-      ok = (n >= 0) && (n < a.N);
-      return ok ? (size_t)n : (size_t)0;
-    }
-    ok = true;
-    return (size_t)(r0 + r);
-  };
+  const char* xrow = reinterpret_cast<const char*>(a.x) + (size_t)b * rowbytes;
 
   // columns owned by this thread
-  int col[NI];
+  uint32_t coff[NI];
   bool cv[NI];
+  uint4 xraw[NI];
   float xr[NI][VEC];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    col[i] = (i * nt + tid) * VEC;
-    cv[i] = col[i] < a.d;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (cv[i]) v = ld16(reinterpret_cast<const T*>(a.x) + (size_t)b * a.d + col[i]);
-    unpack<D>(v, xr[i]);
+    const int col = (i * nt + tid) * VEC;
+    cv[i] = col < a.d;
+    // a column past the end re-reads column 0: its x is zeroed and it is never stored, so every
+    // load is unconditional and the loop body stays free of per-lane branches
+    coff[i] = cv[i] ? (uint32_t)col * sizeof(T) : 0u;
+    xraw[i] = ld16(xrow + coff[i]);  // unpacked after the first weight loads are in flight
   }
 
   float acc[NI][VEC];
@@ -90,155 +159,179 @@ __global__ __launch_bounds__(1024) void ffn_decode_kernel(DecodeArgs a) {
 
   for (int s0 = 0; s0 < R; s0 += kSuper) {
     const int Rs = min(kSuper, R - s0);
+    const int QB = NDOT * Rs;
+    const int lead = (DEPTH - QB % DEPTH) % DEPTH;
+    const int QBp = lead + QB;  // multiple of DEPTH: the phase boundary falls between two groups
+    const int NQ = QBp + Rs;
 
-    // ---- phase A: z_k = <W_up_c[k, :], x> (and the gate's) ----
-    for (int rb = 0; rb < Rs; rb += RCA) {
-      uint4 wu[RCA][NI];
-      uint4 wgt[SWIGLU ? RCA : 1][NI];
-#pragma unroll
-      for (int j = 0; j < RCA; ++j) {
-        const int r = s0 + min(rb + j, Rs - 1);
-        bool ok;
-        const size_t row = row_of(r, ok);
-        const char* pu = up + row * rowbytes;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-          wu[j][i] = make_uint4(0, 0, 0, 0);
-          if (cv[i]) wu[j][i] = ld16(pu + (size_t)col[i] * sizeof(T));
-        }
-        if (SWIGLU) {
-          const char* pg = gate + row * rowbytes;
-#pragma unroll
-          for (int i = 0; i < NI; ++i) {
-            wgt[j][i] = make_uint4(0, 0, 0, 0);
-            if (cv[i]) wgt[j][i] = ld16(pg + (size_t)col[i] * sizeof(T));
-          }
-        }
+    if (GATHER) {
+      __syncthreads();  // previous super-chunk done with sidx
+      for (int r = tid; r < Rs; r += nt) {
+        const int n = a.core_idx[(size_t)b * a.K + r0 + s0 + r];
+        sidx[r] = (n >= 0 && n < a.N) ? n : -1;
       }
-      float pu_[RCA], pg_[RCA];
+      __syncthreads();
+    }
+    const int row_base = r0 + s0;
+    // up-projection bias of "my" neurons, fetched ahead of the weight stream: loads return in
+    // order, so waiting for it later never drains the ring
+    uint32_t bias_bits = 0;  // raw element bits; converted only where used, after phase A
+    if (!SWIGLU && a.b_up && tid < Rs) {
+      const T braw = reinterpret_cast<const T*>(a.b_up)[decode_row_of<GATHER>(tid, row_base, sidx)];
+      if constexpr (sizeof(T) == 4) bias_bits = __builtin_bit_cast(uint32_t, braw);
+      else bias_bits = (uint32_t)__builtin_bit_cast(uint16_t, braw);
+    }
+    uint4 buf[DEPTH][NI];
+#define CI_ISSUE(pos, slot)                                                                     \
+  decode_issue<T, NI, SWIGLU, GATHER>((pos), lead, Rs, QB, NQ, gate, up, down, xrow, rowbytes, \
+                                      row_base, sidx, coff, buf[slot])
+
 #pragma unroll
-      for (int j = 0; j < RCA; ++j) {
-        float su = 0.f, sg = 0.f;
+    for (int s = 0; s < DEPTH; ++s) CI_ISSUE(s, s);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      // opaque to the optimiser, so that the unpacking (and with it the wait for x) is not
+      // hoisted above the first weight loads
+      asm volatile("" : "+v"(xraw[i].x), "+v"(xraw[i].y), "+v"(xraw[i].z), "+v"(xraw[i].w));
+      unpack<D>(xraw[i], xr[i]);
+      if (!cv[i]) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) xr[i][v] = 0.f;
+      }
+    }
+
+    // ---- phase A: dots of the gate / up rows with x ----
+    for (int g0 = 0; g0 < QBp; g0 += DEPTH) {
+      float p[DEPTH];
+#pragma unroll
+      for (int s = 0; s < DEPTH; ++s) {
+        float sum = 0.f;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
           float f[VEC];
-          unpack<D>(wu[j][i], f);
+          unpack<D>(buf[s][i], f);
 #pragma unroll
-          for (int v = 0; v < VEC; ++v) su = fmaf(f[v], xr[i][v], su);
-          if (SWIGLU) {
-            unpack<D>(wgt[j][i], f);
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) sg = fmaf(f[v], xr[i][v], sg);
-          }
+          for (int v = 0; v < VEC; ++v) sum = fmaf(f[v], xr[i][v], sum);
         }
-        pu_[j] = wave_sum(su);
-        if (SWIGLU) pg_[j] = wave_sum(sg);
+        p[s] = sum;  // filler positions give a value that is never stored
+        // keep the ring order: the slot is refilled right after it has been consumed and
+        // before the next slot is waited for (the scheduler would otherwise batch the loads)
+        __builtin_amdgcn_sched_barrier(0);
+        CI_ISSUE(g0 + s + DEPTH, s);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      if (lane == 0) {
-#pragma unroll
-        for (int j = 0; j < RCA; ++j) {
-          if (rb + j < Rs) {
-            red_u[wave * kSuper + rb + j] = pu_[j];
-            if (SWIGLU) red_g[wave * kSuper + rb + j] = pg_[j];
-          }
-        }
-      }
+      const float tot = wave_sum_rows<DEPTH>(p, lane);
+      constexpr int SH = DEPTH == 16 ? 2 : (DEPTH == 8 ? 3 : 4);  // 64 / DEPTH lanes share a row
+      const int q = g0 + (lane >> SH) - lead;
+      if ((lane & ((1 << SH) - 1)) == 0 && q >= 0) red[wave * NDOT * kSuper + q] = tot;
     }
     __syncthreads();
 
-    // ---- hidden value of each neuron of the slice, fp32 ----
-    for (int r = tid; r < Rs; r += nt) {
-      float zu = 0.f, zg = 0.f;
+    // ---- hidden value of each neuron of the super-chunk, fp32 ----
+    if (tid < Rs) {  // Rs <= kSuper <= blockDim.x
+      const int r = tid;
+      float z0 = 0.f, z1 = 0.f;
       for (int w = 0; w < nw; ++w) {
-        zu += red_u[w * kSuper + r];
-        if (SWIGLU) zg += red_g[w * kSuper + r];
+        z0 += red[w * NDOT * kSuper + r];
+        if (SWIGLU) z1 += red[w * NDOT * kSuper + Rs + r];
       }
-      bool ok;
-      const size_t row = row_of(s0 + r, ok);
       float h;
-      if (SWIGLU) {
-        h = silu(zg) * zu;
-      } else {
-        if (a.b_up) zu += to_float<D>(reinterpret_cast<const T*>(a.b_up)[row]);
-        h = fmaxf(zu, 0.f);
+      if (SWIGLU) h = silu(z0) * z1;  // z0: gate, z1: up
+      else {
+        // opaque: keeps the conversion (and the wait for the bias load) down here
+        asm volatile("" : "+v"(bias_bits));
+        float bias;
+        if constexpr (sizeof(T) == 4) bias = u2f(bias_bits);
+        else bias = to_float<D>(__builtin_bit_cast(T, (uint16_t)bias_bits));
+        h = fmaxf(z0 + bias, 0.f);
       }
-      hbuf[r] = ok ? h : 0.f;
+      if (GATHER && sidx[r] < 0) h = 0.f;
+      hbuf[r] = h;
     }
     __syncthreads();
 
     // ---- phase B: y += h_k * W_down_c[k, :] ----
-    for (int rb = 0; rb < Rs; rb += RCB) {
-      uint4 wd[RCB][NI];
+    for (int g0 = QBp; g0 < NQ; g0 += DEPTH) {
 #pragma unroll
-      for (int j = 0; j < RCB; ++j) {
-        const int r = s0 + min(rb + j, Rs - 1);
-        bool ok;
-        const size_t row = row_of(r, ok);
-        const char* pd = down + row * rowbytes;
+      for (int s = 0; s < DEPTH; ++s) {
+        const int pos = g0 + s;
+        if (pos < NQ) {  // uniform; no load inside, so the load count stays path-independent
+          const float hj = hbuf[pos - QBp];
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-          wd[j][i] = make_uint4(0, 0, 0, 0);
-          if (cv[i]) wd[j][i] = ld16(pd + (size_t)col[i] * sizeof(T));
+          for (int i = 0; i < NI; ++i) {
+            float f[VEC];
+            unpack<D>(buf[s][i], f);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[i][v] = fmaf(hj, f[v], acc[i][v]);
+          }
         }
-      }
-#pragma unroll
-      for (int j = 0; j < RCB; ++j) {
-        const float hj = (rb + j < Rs) ? hbuf[rb + j] : 0.f;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-          float f[VEC];
-          unpack<D>(wd[j][i], f);
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) acc[i][v] = fmaf(hj, f[v], acc[i][v]);
-        }
+        __builtin_amdgcn_sched_barrier(0);
+        CI_ISSUE(pos + DEPTH, s);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
-    // the next super-chunk's phase A writes red_*, its h pass writes hbuf only
-    // after the barrier that follows phase A, which every thread reaches after
-    // finishing the reads above.
+    // the filler loads issued past the end are still outstanding: drain them here (vmcnt(0)),
+    // so that the next super-chunk's first loads need not wait on these registers
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    // red / hbuf are rewritten only after the next super-chunk's barriers
+    __syncthreads();
+#undef CI_ISSUE
   }
 
   float* out = a.partial + ((size_t)b * a.n_wg + wg) * a.d;
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     if (cv[i]) {
+      const int col = (i * nt + tid) * VEC;
 #pragma unroll
       for (int v = 0; v < VEC; v += 4)
-        *reinterpret_cast<float4*>(out + col[i] + v) =
+        *reinterpret_cast<float4*>(out + col + v) =
             make_float4(acc[i][v], acc[i][v + 1], acc[i][v + 2], acc[i][v + 3]);
     }
   }
 }
 
-// y[b, c] = sum_w partial[b, w, c] + b_down[c]; 256 threads = 16 column
-// quads x 16 partial groups; fixed summation order.
+// y[b, c] = sum_w partial[b, w, c] + b_down[c].  256 threads = 8 column quads
+// (32 columns, 128 contiguous bytes per partial row) x 32 partial groups; the
+// order of summation is fixed, so the result is deterministic.
 template <class D>
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ partial,
                                                             const void* __restrict__ b_down,
                                                             void* __restrict__ y, int n_wg, int d) {
   using T = typename D::T;
-  __shared__ float4 sm[16][17];
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-  const int c = (blockIdx.x * 16 + tx) * 4;
+  __shared__ float4 sm[32][9];
+  const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
+  const int c = (blockIdx.x * 8 + tx) * 4;
   const int b = blockIdx.y;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (c < d) {
     const float* p = partial + (size_t)b * n_wg * d + c;
-    for (int w = ty; w < n_wg; w += 16) {
+#pragma unroll 4
+    for (int w = ty; w < n_wg; w += 32) {
       const float4 v = *reinterpret_cast<const float4*>(p + (size_t)w * d);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
   }
   sm[ty][tx] = s;
   __syncthreads();
-  if (ty == 0 && c < d) {
-    float4 t = sm[0][tx];
+  if (ty < 4) {  // groups ty*8 .. ty*8+7
+    float4 t = sm[ty * 8][tx];
 #pragma unroll
-    for (int k = 1; k < 16; ++k) {
-      const float4 v = sm[k][tx];
+    for (int k = 1; k < 8; ++k) {
+      const float4 v = sm[ty * 8 + k][tx];
       t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
     }
-    float o[4] = {t.x, t.y, t.z, t.w};
+    sm[ty * 8][tx] = t;
+  }
+  __syncthreads();
+  if (ty == 0 && c < d) {
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float4 v = sm[k * 8][tx];
+      o[0] += v.x; o[1] += v.y; o[2] += v.z; o[3] += v.w;
+    }
     if (b_down) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) o[k] += to_float<D>(reinterpret_cast<const T*>(b_down)[c + k]);
@@ -249,39 +342,67 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
   }
 }
 
+template <class D, int NI, bool SWIGLU, bool GATHER>
+int launch_depth(const DecodeArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
+  int depth = params().decode_depth;
+  if (NI >= 4) depth = 4;                 // 1024-thread workgroups: 128 VGPRs
+  if (NI == 3 && depth > 8) depth = 8;
+  switch (depth) {
+    case 4: hipLaunchKernelGGL((ffn_decode_kernel<D, NI, SWIGLU, GATHER, 4>), grid, block, lds, s, a); break;
+    case 16: hipLaunchKernelGGL((ffn_decode_kernel<D, NI, SWIGLU, GATHER, 16>), grid, block, lds, s, a); break;
+    default: hipLaunchKernelGGL((ffn_decode_kernel<D, NI, SWIGLU, GATHER, 8>), grid, block, lds, s, a); break;
+  }
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
+
 template <class D, bool SWIGLU, bool GATHER>
 int launch_typed(const DecodeArgs& a, int B, int nt, int ni, const void* b_down, void* y,
                  hipStream_t s) {
   if (a.n_wg > 0) {
     const int nw = nt / 64;
-    const size_t lds = (size_t)((SWIGLU ? 2 : 1) * nw + 1) * kSuper * sizeof(float);
+    const size_t lds = (size_t)((SWIGLU ? 2 : 1) * nw + 2) * kSuper * sizeof(float);
     dim3 grid(a.n_wg, B), block(nt);
+    int rc;
     switch (ni) {
-      case 1: hipLaunchKernelGGL((ffn_decode_kernel<D, 1, SWIGLU, GATHER>), grid, block, lds, s, a); break;
-      case 2: hipLaunchKernelGGL((ffn_decode_kernel<D, 2, SWIGLU, GATHER>), grid, block, lds, s, a); break;
-      case 3: hipLaunchKernelGGL((ffn_decode_kernel<D, 3, SWIGLU, GATHER>), grid, block, lds, s, a); break;
-      case 4: hipLaunchKernelGGL((ffn_decode_kernel<D, 4, SWIGLU, GATHER>), grid, block, lds, s, a); break;
+      case 1: rc = launch_depth<D, 1, SWIGLU, GATHER>(a, grid, block, lds, s); break;
+      case 2: rc = launch_depth<D, 2, SWIGLU, GATHER>(a, grid, block, lds, s); break;
+      case 3: rc = launch_depth<D, 3, SWIGLU, GATHER>(a, grid, block, lds, s); break;
+      case 4: rc = launch_depth<D, 4, SWIGLU, GATHER>(a, grid, block, lds, s); break;
       default: return CI_ERR_UNSUPPORTED;
     }
-    CI_HIP_CHECK_LAUNCH();
+    if (rc != CI_OK) return rc;
   }
-  dim3 rgrid((a.d + 63) / 64, B);
+  if (params().decode_skip_reduce) return CI_OK;
+  dim3 rgrid((a.d + 31) / 32, B);
   hipLaunchKernelGGL((decode_reduce_kernel<D>), rgrid, dim3(256), 0, s, a.partial, b_down, y,
                      a.n_wg, a.d);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
 
+// Workgroup width for a row of `vecs` 16-byte vectors: NI loads per thread
+// and row.  Up to three loads the workgroup has at most 512 threads (the
+// register ring needs the 256-VGPR budget); four loads cover d up to 32768.
+inline void pick_shape(int vecs, int* nt, int* ni) {
+  for (int n = (vecs <= 64 ? 1 : 2); n <= 4; ++n) {
+    const int t = ((vecs + n - 1) / n + 63) / 64 * 64;
+    if (t <= (n >= 4 ? 1024 : 512)) { *nt = t; *ni = n; return; }
+  }
+  *nt = 1024;
+  *ni = (vecs + 1023) / 1024;
+}
+
 template <class D>
 int launch_dtype(const DecodeArgs& a, int B, int act, const void* b_down, void* y, hipStream_t s) {
-  // threads per workgroup: aim at two 16-byte loads per thread and row
-  int nt = params().decode_threads;
-  if (nt <= 0) {
-    const int vecs = (a.d + D::VEC - 1) / D::VEC;
-    nt = ((vecs + 1) / 2 + 63) / 64 * 64;
+  const int vecs = (a.d + D::VEC - 1) / D::VEC;
+  int nt, ni;
+  pick_shape(vecs, &nt, &ni);
+  const int want = params().decode_threads / 64 * 64;  // tuning override, if it fits the bounds
+  if (want >= 64) {
+    const int n = (vecs + want - 1) / want;
+    if (n <= 4 && want <= (n >= 4 ? 1024 : 512)) { nt = want; ni = n; }
   }
-  nt = nt < 64 ? 64 : (nt > 1024 ? 1024 : nt / 64 * 64);
-  const int ni = (a.d + nt * D::VEC - 1) / (nt * D::VEC);
   const bool gather = a.core_idx != nullptr;
   if (act == CI_ACT_SWIGLU)
     return gather ? launch_typed<D, true, true>(a, B, nt, ni, b_down, y, s)
