@@ -29,6 +29,7 @@ struct DecodeArgs {
   const int32_t* core_idx;
   float* partial;
   int K, d, N, n_wg;
+  int nt_store;
 };
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -279,59 +280,61 @@ __global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(Decode
 #undef CI_ISSUE
   }
 
+  const bool NT_STORE = a.nt_store != 0;
   float* out = a.partial + ((size_t)b * a.n_wg + wg) * a.d;
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     if (cv[i]) {
       const int col = (i * nt + tid) * VEC;
 #pragma unroll
-      for (int v = 0; v < VEC; v += 4)
-        *reinterpret_cast<float4*>(out + col + v) =
-            make_float4(acc[i][v], acc[i][v + 1], acc[i][v + 2], acc[i][v + 3]);
+      for (int v = 0; v < VEC; v += 4) {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const f32x4 t = {acc[i][v], acc[i][v + 1], acc[i][v + 2], acc[i][v + 3]};
+        if (NT_STORE) __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(out + col + v));
+        else *reinterpret_cast<f32x4*>(out + col + v) = t;
+      }
     }
   }
 }
 
-// y[b, c] = sum_w partial[b, w, c] + b_down[c].  256 threads = 8 column quads
-// (32 columns, 128 contiguous bytes per partial row) x 32 partial groups; the
-// order of summation is fixed, so the result is deterministic.
-template <class D>
+// y[b, c] = sum_w partial[b, w, c] + b_down[c].  256 threads = CQ column quads
+// (4 * CQ columns, contiguous in every partial row) x 256 / CQ partial groups;
+// the order of summation is fixed, so the result is deterministic.
+template <class D, int CQ>
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ partial,
                                                             const void* __restrict__ b_down,
                                                             void* __restrict__ y, int n_wg, int d) {
   using T = typename D::T;
-  __shared__ float4 sm[32][9];
-  const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
-  const int c = (blockIdx.x * 8 + tx) * 4;
+  constexpr int G = 256 / CQ;
+  __shared__ float4 sm[G][CQ + 1];
+  const int tx = threadIdx.x % CQ, ty = threadIdx.x / CQ;
+  const int c = (blockIdx.x * CQ + tx) * 4;
   const int b = blockIdx.y;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (c < d) {
     const float* p = partial + (size_t)b * n_wg * d + c;
 #pragma unroll 4
-    for (int w = ty; w < n_wg; w += 32) {
-      const float4 v = *reinterpret_cast<const float4*>(p + (size_t)w * d);
-      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    for (int w = ty; w < n_wg; w += G) {
+      const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + (size_t)w * d));
+      s.x += u2f(t[0]); s.y += u2f(t[1]); s.z += u2f(t[2]); s.w += u2f(t[3]);
     }
   }
   sm[ty][tx] = s;
   __syncthreads();
-  if (ty < 4) {  // groups ty*8 .. ty*8+7
-    float4 t = sm[ty * 8][tx];
+  // tree over the G groups, pairwise in a fixed order
 #pragma unroll
-    for (int k = 1; k < 8; ++k) {
-      const float4 v = sm[ty * 8 + k][tx];
+  for (int half = G / 2; half >= 1; half >>= 1) {
+    if (ty < half) {
+      const float4 v = sm[ty + half][tx];
+      float4 t = sm[ty][tx];
       t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+      sm[ty][tx] = t;
     }
-    sm[ty * 8][tx] = t;
+    __syncthreads();
   }
-  __syncthreads();
   if (ty == 0 && c < d) {
-    float o[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const float4 v = sm[k * 8][tx];
-      o[0] += v.x; o[1] += v.y; o[2] += v.z; o[3] += v.w;
-    }
+    const float4 t = sm[0][tx];
+    float o[4] = {t.x, t.y, t.z, t.w};
     if (b_down) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) o[k] += to_float<D>(reinterpret_cast<const T*>(b_down)[c + k]);
@@ -374,9 +377,19 @@ int launch_typed(const DecodeArgs& a, int B, int nt, int ni, const void* b_down,
     if (rc != CI_OK) return rc;
   }
   if (params().decode_skip_reduce) return CI_OK;
-  dim3 rgrid((a.d + 31) / 32, B);
-  hipLaunchKernelGGL((decode_reduce_kernel<D>), rgrid, dim3(256), 0, s, a.partial, b_down, y,
-                     a.n_wg, a.d);
+  switch (params().reduce_cq) {
+    case 4:
+      hipLaunchKernelGGL((decode_reduce_kernel<D, 4>), dim3((a.d + 15) / 16, B), dim3(256), 0, s,
+                         a.partial, b_down, y, a.n_wg, a.d);
+      break;
+    case 16:
+      hipLaunchKernelGGL((decode_reduce_kernel<D, 16>), dim3((a.d + 63) / 64, B), dim3(256), 0, s,
+                         a.partial, b_down, y, a.n_wg, a.d);
+      break;
+    default:
+      hipLaunchKernelGGL((decode_reduce_kernel<D, 8>), dim3((a.d + 31) / 32, B), dim3(256), 0, s,
+                         a.partial, b_down, y, a.n_wg, a.d);
+  }
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
@@ -441,6 +454,7 @@ int launch_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dty
   a.d = (int)w->d;
   a.N = (int)w->N;
   a.n_wg = decode_splits(B, w->K);
+  a.nt_store = params().decode_nt_store;
   switch (dtype) {
     case CI_F32: return launch_dtype<F32>(a, (int)B, act, w->b_down, y, s);
     case CI_F16: return launch_dtype<F16>(a, (int)B, act, w->b_down, y, s);

@@ -1,0 +1,72 @@
+"""Small driver for hardware-counter runs of the decode kernel.
+
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d OUT -- \
+        python3 -m paper_2410_18311_amd.pmc_probe --workload opt6.7b_relu_f16
+
+It launches (a) a plain device-to-device copy of a known size (the calibration
+against which the FETCH_SIZE / WRITE_SIZE readings are scaled) and (b) the
+sparse decode FFN of every layer of the workload, on random compacted buffers
+of the workload's shapes, a few times.  Nothing is timed here.
+"""
+
+from __future__ import annotations
+
+import argparse
+
+import torch
+
+from . import coreinfer as ci
+from . import workloads as wl
+
+COPY_BYTES = 256 << 20
+
+
+def main():
+    p = argparse.ArgumentParser()
+    p.add_argument("--workload", default="opt6.7b_relu_f16")
+    p.add_argument("--layers", type=int, default=8)
+    p.add_argument("--reps", type=int, default=3)
+    args = p.parse_args()
+    cfg = wl.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    d, N, B = cfg.d, cfg.N, cfg.sentences
+    K = ci.keep_count(cfg.betas[0], N)
+    dt = cfg.torch_dtype
+
+    src = torch.empty(COPY_BYTES, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)                       # calibration: reads and writes COPY_BYTES each
+    torch.cuda.synchronize()
+
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    mk = lambda *s: (torch.randn(*s, generator=g, device=dev) * 0.02).to(dt)
+    gathered = B > 1
+    rows = N if gathered else K
+    layers = []
+    for _ in range(args.layers):
+        up, down = mk(rows, d), mk(rows, d)
+        gate = mk(rows, d) if cfg.act == "swiglu" else None
+        bias = mk(rows) if cfg.b_up is not None else None
+        idx = None
+        if gathered:
+            idx = torch.stack([torch.sort(torch.randperm(N, generator=g, device=dev)[:K]).values
+                               for _ in range(B)]).to(torch.int32).contiguous()
+        layers.append((ci.make_weights(up, gate, bias, down, None, core_idx=idx), (up, gate, bias, down, idx)))
+    x = mk(B, d) * 50
+    y = torch.empty_like(x)
+    ws = torch.empty(ci.ffn_decode_workspace_size(B, K, d), dtype=torch.uint8, device=dev)
+    for _ in range(args.reps):
+        for desc, _keep in layers:
+            ci.ffn_decode(x, desc, cfg.act, y=y, ws=ws)
+    torch.cuda.synchronize()
+    n_mat = cfg.n_mat
+    e = 2 if cfg.dtype != "f32" else 4
+    print(f"workload {cfg.name}: K={K} d={d} B={B}; algorithmic bytes per decode launch = "
+          f"{B * (n_mat * K * d * e + (K * e if cfg.b_up is not None else 0) + 2 * d * e)}; "
+          f"calibration copy = {COPY_BYTES} bytes read + {COPY_BYTES} bytes written")
+
+
+if __name__ == "__main__":
+    main()
