@@ -73,7 +73,8 @@ int coreinfer_version(void);
 
 /*
  * Development knob for tuning sweeps, never needed for correct use: overrides
- * a launch-shape parameter process-wide.  Names: "decode_wgs_per_cu" (1..16),
+ * a launch-shape parameter process-wide.  Names: "decode_wgs_per_cu" (1..16), "decode_wgs" (0 = use the per-CU rule,
+ * else the number of neuron slices per sentence, up to 1024),
  * "decode_threads" (0 = derive from d, else a multiple of 64 up to 1024),
  * "decode_depth" (4, 8 or 16 weight rows in flight per thread), "reduce_cq"
  * (4, 8, 16 column quads per reduction workgroup), "decode_nt_store" (0/1),

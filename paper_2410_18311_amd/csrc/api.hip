@@ -77,6 +77,7 @@ int coreinfer_set_param(const char* name, int value) {
   if (!name) return CI_ERR_INVALID_ARG;
   Params& p = params();
   if (!strcmp(name, "decode_wgs_per_cu") && value >= 1 && value <= 16) p.decode_wgs_per_cu = value;
+  else if (!strcmp(name, "decode_wgs") && value >= 0 && value <= 1024) p.decode_wgs = value;
   else if (!strcmp(name, "decode_threads") && value >= 0 && value <= 1024) p.decode_threads = value;
   else if (!strcmp(name, "decode_depth") && (value == 4 || value == 8 || value == 16)) p.decode_depth = value;
   else if (!strcmp(name, "reduce_cq") && (value == 4 || value == 8 || value == 16)) p.reduce_cq = value;
@@ -115,8 +116,10 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld, double 
     return CI_ERR_BAD_LAYOUT;
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
+  // workspace: [N] counters (used when the caller passes none), then the ticket word
   int32_t* cnt = counts ? counts : reinterpret_cast<int32_t*>(ws);
-  return launch_select(act, M, N, ld, qa, keep(qb, N), core_idx, cnt, (hipStream_t)stream);
+  uint32_t* ticket = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(ws) + round256((size_t)N * sizeof(int32_t)));
+  return launch_select(act, M, N, ld, qa, keep(qb, N), core_idx, cnt, ticket, (hipStream_t)stream);
 }
 
 int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,

@@ -110,6 +110,7 @@ int device_info(DeviceInfo* out);
 // Development knobs (see coreinfer_set_param).
 struct Params {
   int decode_wgs_per_cu = 1;
+  int decode_wgs = 0;        // absolute number of neuron slices per sentence (0 = per-CU rule)
   int decode_threads = 0;  // 0 = derived from d
   int decode_depth = 4;    // weight rows in flight per thread (4, 8 or 16)
   int select_wgs_per_cu = 1;
@@ -130,7 +131,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // ---- launchers (one per translation unit) ----------------------------------
 int launch_select(const float* act, int64_t M, int64_t N, int64_t ld, int64_t q_alpha, int64_t K,
-                  int32_t* core_idx, int32_t* counts, hipStream_t s);
+                  int32_t* core_idx, int32_t* counts, uint32_t* ticket, hipStream_t s);
 int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                    int down_layout, int dtype, int64_t d, int64_t N, const int32_t* core_idx,
                    int64_t K, void* w_up_c, void* w_gate_c, void* b_up_c, void* w_down_c,

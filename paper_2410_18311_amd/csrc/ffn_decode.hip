@@ -434,6 +434,7 @@ int decode_splits(int64_t B, int64_t K) {
   int cus = 256;
   if (device_info(&di) == CI_OK) cus = di.cus;
   int64_t n = ((int64_t)cus * params().decode_wgs_per_cu + B - 1) / B;
+  if (params().decode_wgs > 0) n = params().decode_wgs;
   if (n > 1024) n = 1024;
   if (n > K) n = K;
   if (n < 1) n = 1;
