@@ -78,7 +78,9 @@ int coreinfer_version(void);
  * "decode_threads" (0 = derive from d, else a multiple of 64 up to 1024),
  * "decode_depth" (4, 8 or 16 weight rows in flight per thread), "reduce_cq"
  * (4, 8, 16 column quads per reduction workgroup), "decode_nt_store" (0/1),
- * "select_wgs_per_cu" (1..8), "gemv_wgs_per_cu" (1..32), "decode_skip_reduce"
+ * "select_wgs_per_cu" (1..8), "select_debug" (timing only: 1 stops after the
+ * per-token phase, 2 after the ticket; core_idx is then NOT written),
+ * "gemv_wgs_per_cu" (1..32), "decode_skip_reduce"
  * (0/1; 1 launches only the first decode kernel so that it can be timed
  * alone -- y is then NOT written).  Unknown name or value out of range:
  * CI_ERR_INVALID_ARG.  Not thread-safe against running

@@ -114,6 +114,7 @@ struct Params {
   int decode_threads = 0;  // 0 = derived from d
   int decode_depth = 4;    // weight rows in flight per thread (4, 8 or 16)
   int select_wgs_per_cu = 1;
+  int select_debug = 0;
   int gemv_wgs_per_cu = 4;
   int reduce_cq = 8;        // column quads per reduce workgroup (4, 8, 16)
   int decode_nt_store = 1;  // non-temporal stores for the partial sums

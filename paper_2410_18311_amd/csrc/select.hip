@@ -4,23 +4,23 @@
 //   * Def. 1 / Eq. 1 and Eq. 3.  One workgroup per prompt token (looping when
 //     M exceeds the grid).  The token's N activations become integer keys
 //     (the IEEE bits of a positive float are monotone in its value;
-//     everything that is not > 0 becomes key 0) held in registers.  The value
-//     T of the k-th largest key (k = the share alpha of the positive keys) is
-//     built bit by bit, most significant first: a candidate bit stays set if
-//     at least k keys are >= the candidate.  Counting is a vector compare, a
-//     scalar popcount of the lane mask and one LDS exchange per step -- no
-//     atomics, no cross-lane shuffles.  Keys > T are token-wise core neurons;
-//     of the keys == T the lowest indices fill the remaining places (ordered
-//     ballot / popcount prefix; skipped when all of them are taken).  Each
-//     chosen neuron's counter is incremented: in an LDS-private packed-u16
-//     histogram when the workgroup sees several tokens (flushed once with
-//     integer atomics), else directly in global memory.  Integer adds commute,
-//     so the counts do not depend on scheduling.
+//     everything that is not > 0 becomes key 0), loaded once and kept in
+//     registers.  A three-pass most-significant-digit radix select (11 + 11 +
+//     9 bits) over LDS histograms finds the value T of the k-th largest key,
+//     k being the share alpha of the positive keys.  The histograms are
+//     replicated eight times by lane so that activations sharing an exponent
+//     do not serialise on one LDS address.  Keys > T are token-wise core
+//     neurons; of the keys == T the lowest indices fill the remaining places
+//     (ordered ballot / popcount prefix; skipped when all of them are taken).
+//     Each chosen neuron's counter is incremented: in an LDS-private
+//     packed-u16 histogram when the workgroup sees several tokens (flushed
+//     once with integer atomics), else directly in global memory.  Integer
+//     adds commute, so the counts do not depend on scheduling.
 //   * Def. 2 / Eq. 2.  The workgroup that finishes last (a ticket taken after a
 //     device-scope fence) selects the K neurons first in the order (count
-//     descending, index ascending): the threshold count by the same bitwise
-//     search, then a ballot-based ordered compaction that writes S in ascending
-//     index order: position = #greater before + min(#equal before, need).
+//     descending, index ascending): threshold count by a two-pass radix select
+//     over the counts (<= 65535), then a ballot-based ordered compaction that
+//     writes S ascending: position = #greater before + min(#equal before, need).
 // zero_i32_kernel clears the counters and the ticket beforehand.
 #include "common.hpp"
 
@@ -28,26 +28,79 @@ namespace ci {
 
 namespace {
 
+constexpr int kBins = 2048;              // largest digit: 11 bits
+constexpr int kCopies = 8;               // histogram replicas, chosen by lane & 7
+constexpr int kCopyStride = kBins + 8;   // words; the +8 spreads the replicas over LDS banks
+constexpr int kHistWords = kCopies * kCopyStride;
 constexpr int kMaxWaves = 16;
 
 struct SelShared {
-  uint32_t wcnt[2][kMaxWaves];  // per-wave tallies, double buffered: one barrier per exchange
+  uint32_t wave_tot[kMaxWaves];
+  uint32_t bin;      // chosen digit
+  uint32_t above;    // keys in higher digits
+  uint32_t in_bin;   // keys in the chosen digit
   uint32_t ticket;
 };
 
-// Number of lanes of this wave for which `pred` holds (wave-uniform).
 __device__ __forceinline__ uint32_t wave_count(bool pred) { return (uint32_t)__popcll(__ballot(pred)); }
 
-// Block-wide sum of one value per wave (already wave-uniform).  `phase`
-// alternates between calls, so successive calls need no second barrier.
-__device__ __forceinline__ uint32_t block_sum_waves(uint32_t wave_value, SelShared* sh, int& phase) {
+// Block-wide sum of one wave-uniform value per wave (every thread gets it).
+__device__ __forceinline__ uint32_t block_sum_waves(uint32_t wave_value, SelShared* sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  if (lane == 0) sh->wcnt[phase][wave] = wave_value;
+  __syncthreads();
+  if (lane == 0) sh->wave_tot[wave] = wave_value;
   __syncthreads();
   uint32_t t = 0;
-  for (int w = 0; w < nw; ++w) t += sh->wcnt[phase][w];
-  phase ^= 1;
+  for (int w = 0; w < nw; ++w) t += sh->wave_tot[w];
   return t;
+}
+
+// hist holds kCopies replicas of nbins digit counts.  Finds the digit that
+// contains the k-th largest key (1 <= k <= total) and how many keys lie in
+// higher digits.  Result in sh->bin / above / in_bin, visible to all threads on
+// return.
+__device__ __forceinline__ void find_digit(const uint32_t* hist, int nbins, uint32_t k, SelShared* sh) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+  const int per = (nbins + nt - 1) / nt;  // digits per thread, contiguous; higher thread = higher digits
+  const int b0 = tid * per;
+  auto bin_total = [&](int bidx) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int r = 0; r < kCopies; ++r) c += hist[r * kCopyStride + bidx];
+    return c;
+  };
+  uint32_t mine = 0;
+  for (int j = 0; j < per; ++j)
+    if (b0 + j < nbins) mine += bin_total(b0 + j);
+  uint32_t suf = mine;  // inclusive suffix sum over the wave
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_down(suf, off, kWave);
+    if (lane + off < 64) suf += o;
+  }
+  if (lane == 0) sh->wave_tot[wave] = suf;
+  __syncthreads();
+  uint32_t higher = 0;
+  for (int w = wave + 1; w < nw; ++w) higher += sh->wave_tot[w];
+  const uint32_t incl = suf + higher;  // keys in my digits and above
+  const uint32_t excl = incl - mine;   // keys strictly above my digits
+  if (excl < k && k <= incl) {
+    uint32_t run = excl;
+    for (int j = per - 1; j >= 0; --j) {
+      const int bidx = b0 + j;
+      if (bidx >= nbins) continue;
+      const uint32_t c = bin_total(bidx);
+      if (run + c >= k) {
+        sh->bin = (uint32_t)bidx;
+        sh->above = run;
+        sh->in_bin = c;
+        break;
+      }
+      run += c;
+    }
+  }
+  __syncthreads();
 }
 
 // Runs f(i) for i in [0, n_iter).  With ITEMS > 0 the loop is unrolled to a
@@ -63,42 +116,44 @@ __device__ __forceinline__ void for_items(int n_iter, F f) {
   }
 }
 
-// Largest T in [0, 2^(top_bit+1)) such that at least k keys are >= T.  On
-// return ge_T = number of keys >= T (unchanged if T stays 0: the caller
-// presets it to the number of valid keys).  Every thread gets the same result.
+// One radix pass: histogram of the digit (key >> shift) & (nb - 1) over the
+// keys that match `prefix` under `prefix_mask`, then the digit holding the
+// k-th largest of them.  Updates prefix / prefix_mask / k; n_eq = keys in it.
 template <int ITEMS, class KeyAt>
-__device__ __forceinline__ uint32_t kth_largest(KeyAt key_at, int n_iter, uint32_t k, int top_bit,
-                                                SelShared* sh, int& phase, uint32_t& ge_T) {
-  uint32_t T = 0;
-  for (int bit = top_bit; bit >= 0; --bit) {
-    const uint32_t cand = T | (1u << bit);
-    uint32_t c = 0;
-    for_items<ITEMS>(n_iter, [&](int i) {
-      bool valid;
-      const uint32_t key = key_at(i, valid);
-      c += wave_count(valid && key >= cand);
-    });
-    c = block_sum_waves(c, sh, phase);
-    if (c >= k) {
-      T = cand;
-      ge_T = c;
-    }
-  }
-  return T;
+__device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, int nb, uint32_t* hist,
+                                           SelShared* sh, uint32_t& prefix, uint32_t& prefix_mask,
+                                           uint32_t& k, uint32_t& n_eq) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  uint32_t* my_hist = hist + (tid & (kCopies - 1)) * kCopyStride;
+  // clear the replicas (the padding words are never read)
+  for (int j = tid; j < kCopies * nb; j += nt) hist[(j / nb) * kCopyStride + (j % nb)] = 0;
+  __syncthreads();
+  for_items<ITEMS>(n_iter, [&](int i) {
+    const uint32_t key = key_at(i);
+    if ((key & prefix_mask) == prefix) atomicAdd(&my_hist[(key >> shift) & (nb - 1)], 1u);
+  });
+  __syncthreads();
+  find_digit(hist, nb, k, sh);
+  prefix |= sh->bin << shift;
+  prefix_mask |= (uint32_t)(nb - 1) << shift;
+  k -= sh->above;
+  n_eq = sh->in_bin;
+  __syncthreads();  // sh is reused by the next pass
 }
 
 template <int ITEMS>
 __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ act, int M, int N,
                                                       int64_t ld, int64_t q_alpha, int K,
                                                       int32_t* counts, int32_t* core_idx,
-                                                      uint32_t* ticket, int privatise) {
+                                                      uint32_t* ticket, int privatise, int debug) {
   __shared__ SelShared sh;
-  extern __shared__ uint32_t lcount[];  // [ceil(N/2)] packed u16 pairs when privatised
+  extern __shared__ uint32_t dyn[];  // [kHistWords] histograms, then [ceil(N/2)] packed u16 counters
+  uint32_t* hist = dyn;
+  uint32_t* lcount = dyn + kHistWords;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int n_iter = (N + nt - 1) / nt;
   const int npair = (N + 1) / 2;
-  int phase = 0;
 
   if (privatise) {
     for (int j = tid; j < npair; j += nt) lcount[j] = 0;
@@ -111,15 +166,16 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
     uint32_t kc[ITEMS > 0 ? ITEMS : 1];
     uint32_t npos = 0;
     if (ITEMS > 0) {
+      float av[ITEMS > 0 ? ITEMS : 1];
+#pragma unroll
+      for (int i = 0; i < ITEMS; ++i) {  // branch-free: all loads are issued back to back
+        const int e = i * nt + tid;
+        av[i] = row[e < N ? e : N - 1];
+      }
 #pragma unroll
       for (int i = 0; i < ITEMS; ++i) {
         const int e = i * nt + tid;
-        uint32_t key = 0;
-        if (e < N) {
-          const float a = row[e];
-          key = (a > 0.f) ? f2u(a) : 0u;
-        }
-        kc[i] = key;
+        kc[i] = (e < N && av[i] > 0.f) ? f2u(av[i]) : 0u;
       }
 #pragma unroll
       for (int i = 0; i < ITEMS; ++i) npos += wave_count(kc[i] != 0);
@@ -129,31 +185,32 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
         npos += wave_count(e < N && row[e] > 0.f);
       }
     }
-    auto key_at = [&](int i, bool& valid) -> uint32_t {
-      const int e = i * nt + tid;
-      valid = e < N;
+    // key of this thread's i-th element; 0 (never a candidate) past the end
+    auto key_at = [&](int i) -> uint32_t {
       if (ITEMS > 0) return kc[ITEMS > 0 ? i : 0];  // i is a constant after unrolling
-      if (!valid) return 0u;
+      const int e = i * nt + tid;
+      if (e >= N) return 0u;
       const float a = row[e];
       return (a > 0.f) ? f2u(a) : 0u;
     };
+    // for the histogram passes a zero key must match no prefix: map it to all-ones
+    // (bit 31 set, which no prefix mask ever covers with a zero prefix... see radix_pass use)
+    auto key_sel = [&](int i) -> uint32_t {
+      const uint32_t key = key_at(i);
+      return key != 0 ? key : 0xffffffffu;
+    };
 
-    const uint32_t P = block_sum_waves(npos, &sh, phase);
+    const uint32_t P = block_sum_waves(npos, &sh);
     const uint32_t k = (uint32_t)((q_alpha * (int64_t)P + 999999) / 1000000);  // share of the positives
     if (k == 0) continue;  // uniform: no positive activation
 
-    // positive keys are <= 0x7f800000 (+inf): bit 30 is the top one.  k <= P, so T >= 1.
-    uint32_t ge_T = 0;
-    const uint32_t T = kth_largest<ITEMS>(key_at, n_iter, k, 30, &sh, phase, ge_T);
-    uint32_t gt = 0;
-    for_items<ITEMS>(n_iter, [&](int i) {
-      bool valid;
-      const uint32_t key = key_at(i, valid);
-      gt += wave_count(valid && key > T);
-    });
-    gt = block_sum_waves(gt, &sh, phase);
-    const uint32_t need = k - gt;      // how many of the keys == T belong to the top k
-    const uint32_t n_eq = ge_T - gt;   // how many keys == T exist
+    // 31-bit keys: digits of 11, 11 and 9 bits.  Bit 31 is part of the mask from the start,
+    // so the all-ones stand-in of a zero key never matches.
+    uint32_t prefix = 0, prefix_mask = 0x80000000u, need = k, n_eq = 0;
+    radix_pass<ITEMS>(key_sel, n_iter, 20, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
+    radix_pass<ITEMS>(key_sel, n_iter, 9, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
+    radix_pass<ITEMS>(key_sel, n_iter, 0, 512, hist, &sh, prefix, prefix_mask, need, n_eq);
+    const uint32_t T = prefix;  // the k-th largest key; `need` of the n_eq keys == T are in the top k
 
     auto bump = [&](int e) {
       if (privatise) atomicAdd(&lcount[e >> 1], 1u << (16 * (e & 1)));
@@ -163,30 +220,30 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
     const bool all_ties = (need == n_eq);  // uniform
     uint32_t base = 0;                      // ties seen in earlier iterations
     for_items<ITEMS>(n_iter, [&](int i) {
-      bool valid;
-      const uint32_t key = key_at(i, valid);
+      const uint32_t key = key_at(i);  // T >= 1, so elements past the end (key 0) never match
       const int e = i * nt + tid;
-      if (valid && key > T) bump(e);
+      if (key > T) bump(e);
       if (all_ties) {
-        if (valid && key == T) bump(e);
+        if (key == T) bump(e);
       } else if (base < need) {  // uniform condition
         // index order = iteration, then wave, then lane
-        const bool tie = valid && key == T;
+        const bool tie = key == T;
         const uint64_t bal = __ballot(tie);
-        if (lane == 0) sh.wcnt[phase][wave] = (uint32_t)__popcll(bal);
+        __syncthreads();
+        if (lane == 0) sh.wave_tot[wave] = (uint32_t)__popcll(bal);
         __syncthreads();
         uint32_t before = base, tot = 0;
         for (int w = 0; w < nw; ++w) {
-          const uint32_t c = sh.wcnt[phase][w];
+          const uint32_t c = sh.wave_tot[w];
           if (w < wave) before += c;
           tot += c;
         }
-        phase ^= 1;
         const uint32_t rank = before + (uint32_t)__popcll(bal & lanemask_lt());
         if (tie && rank < need) bump(e);
         base += tot;
       }
     });
+    __syncthreads();
   }
 
   if (privatise) {
@@ -201,73 +258,133 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
   // ------------------------------------------------ Def. 2 / Eq. 2 -----------
   // The last workgroup to arrive sees every counter update: each workgroup's
   // atomics are complete (device-scope fence) before it takes its ticket.
-  __threadfence();
+  if (debug & 1) return;
+  // Every wave first waits until its own counter updates have been performed (vmcnt(0)); the
+  // barrier orders them before thread 0, whose single device-scope fence then publishes the
+  // workgroup's updates before the ticket is taken.  (A fence in every wave costs far more.)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
-  if (tid == 0) sh.ticket = atomicAdd(ticket, 1u);
+  if (tid == 0) {
+    __threadfence();
+    sh.ticket = atomicAdd(ticket, 1u);
+  }
   __syncthreads();
   if (sh.ticket != gridDim.x - 1) return;
   __threadfence();
+  if (debug & 2) return;
 
-  auto count_at = [&](int i, bool& valid) -> uint32_t {
-    const int e = i * nt + tid;
-    valid = e < N;
-    if (!valid) return 0u;
-    return (uint32_t)__hip_atomic_load(&counts[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  };
   uint32_t cc[ITEMS > 0 ? ITEMS : 1];
+  auto load_count = [&](int i) -> uint32_t {  // past the end: element N-1, masked by the callers
+    const int e = i * nt + tid;
+    return (uint32_t)__hip_atomic_load(&counts[e < N ? e : N - 1], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+  };
   if (ITEMS > 0) {
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) cc[i] = load_count(i);
+  }
+  auto ckey_valid = [&](int i, bool& valid) -> uint32_t {
+    valid = i * nt + tid < N;
+    return ITEMS > 0 ? cc[ITEMS > 0 ? i : 0] : load_count(i);
+  };
+  auto ckey_sel = [&](int i) -> uint32_t {  // all-ones (never matches) past the end
+    bool valid;
+    const uint32_t c = ckey_valid(i, valid);
+    return valid ? c : 0xffffffffu;
+  };
+
+  // counts are <= M <= 65535: two 8-bit digits; the high one is skipped when M < 256
+  uint32_t prefix = 0, prefix_mask = 0xffff0000u, need = (uint32_t)K, n_eq = 0;
+  if (M >= 256) radix_pass<ITEMS>(ckey_sel, n_iter, 8, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
+  else prefix_mask |= 0xff00u;
+  radix_pass<ITEMS>(ckey_sel, n_iter, 0, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
+  const uint32_t T = prefix;
+
+  // ordered compaction.  pos = (#greater before) + min(#equal before, need), "before" in index
+  // order = iteration, then wave, then lane.
+  if constexpr (ITEMS > 0) {
+    // tallies per (iteration, wave) go to a table, one wave scans it, then every thread
+    // places its elements: three barriers in all
+    uint32_t* tab = hist;  // [n_iter * nw], (#greater << 16) | #equal, each <= 64 before the scan
+    uint64_t bgs[ITEMS], bes[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
       bool valid;
-      cc[i] = count_at(i, valid);
+      const uint32_t key = ckey_valid(i, valid);
+      bgs[i] = __ballot(valid && key > T);
+      bes[i] = __ballot(valid && key == T);
+      if (lane == 0 && i < n_iter) tab[i * nw + wave] = ((uint32_t)__popcll(bgs[i]) << 16) | (uint32_t)__popcll(bes[i]);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      // exclusive scan of the n_iter * nw entries; the two 16-bit fields cannot overflow into
+      // each other because N <= 16 * 1024 here (#equal < 65536 is needed: it is <= N)
+      const int n_ent = n_iter * nw;
+      const int per = (n_ent + 63) / 64;
+      uint32_t g_sum = 0, e_sum = 0;
+      for (int j = 0; j < per; ++j) {
+        const int idx = lane * per + j;
+        if (idx < n_ent) { g_sum += tab[idx] >> 16; e_sum += tab[idx] & 0xffffu; }
+      }
+      uint32_t g_inc = g_sum, e_inc = e_sum;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t og = __shfl_up(g_inc, off, kWave), oe = __shfl_up(e_inc, off, kWave);
+        if (lane >= off) { g_inc += og; e_inc += oe; }
+      }
+      uint32_t g_run = g_inc - g_sum, e_run = e_inc - e_sum;
+      uint32_t* gtab = tab + n_ent;  // exclusive #greater / #equal prefixes, full 32 bits each
+      uint32_t* etab = gtab + n_ent;
+      for (int j = 0; j < per; ++j) {
+        const int idx = lane * per + j;
+        if (idx < n_ent) {
+          const uint32_t c = tab[idx];
+          gtab[idx] = g_run;
+          etab[idx] = e_run;
+          g_run += c >> 16;
+          e_run += c & 0xffffu;
+        }
+      }
+    }
+    __syncthreads();
+    const uint32_t* gtab = tab + n_iter * nw;
+    const uint32_t* etab = gtab + n_iter * nw;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+      if (i < n_iter) {
+        const bool isg = (bgs[i] >> lane) & 1, ise = (bes[i] >> lane) & 1;
+        const uint32_t g_before = gtab[i * nw + wave] + (uint32_t)__popcll(bgs[i] & lanemask_lt());
+        const uint32_t e_before = etab[i * nw + wave] + (uint32_t)__popcll(bes[i] & lanemask_lt());
+        const uint32_t pos = g_before + (e_before < need ? e_before : need);
+        if (isg || (ise && e_before < need)) core_idx[pos] = i * nt + tid;
+      }
+    }
+  } else {
+    // large N: running totals over the iterations, two barriers per iteration
+    uint32_t g_base = 0, e_base = 0;
+    for (int i = 0; i < n_iter; ++i) {
+      bool valid;
+      const uint32_t key = ckey_valid(i, valid);
+      const bool isg = valid && key > T, ise = valid && key == T;
+      const uint64_t bg = __ballot(isg), be = __ballot(ise);
+      __syncthreads();
+      if (lane == 0) sh.wave_tot[wave] = ((uint32_t)__popcll(bg) << 16) | (uint32_t)__popcll(be);  // <= 64 each
+      __syncthreads();
+      uint32_t g_before = g_base, e_before = e_base, g_tot = 0, e_tot = 0;
+      for (int w = 0; w < nw; ++w) {
+        const uint32_t c = sh.wave_tot[w];
+        if (w < wave) { g_before += c >> 16; e_before += c & 0xffffu; }
+        g_tot += c >> 16;
+        e_tot += c & 0xffffu;
+      }
+      g_before += (uint32_t)__popcll(bg & lanemask_lt());
+      e_before += (uint32_t)__popcll(be & lanemask_lt());
+      const uint32_t pos = g_before + (e_before < need ? e_before : need);
+      if (isg || (ise && e_before < need)) core_idx[pos] = i * nt + tid;
+      g_base += g_tot;
+      e_base += e_tot;
     }
   }
-  auto ckey_at = [&](int i, bool& valid) -> uint32_t {
-    if (ITEMS > 0) {
-      valid = i * nt + tid < N;
-      return cc[ITEMS > 0 ? i : 0];
-    }
-    return count_at(i, valid);
-  };
-
-  // counts lie in [0, M]: search only the bits M can have
-  const int top_bit = 31 - __clz((uint32_t)(M | 1));
-  uint32_t ge_T = (uint32_t)N;  // T = 0 holds for every neuron
-  const uint32_t T = kth_largest<ITEMS>(ckey_at, n_iter, (uint32_t)K, top_bit, &sh, phase, ge_T);
-  uint32_t gt = 0;
-  for_items<ITEMS>(n_iter, [&](int i) {
-    bool valid;
-    const uint32_t key = ckey_at(i, valid);
-    gt += wave_count(valid && key > T);
-  });
-  gt = block_sum_waves(gt, &sh, phase);
-  const uint32_t need = (uint32_t)K - gt;
-
-  // ordered compaction: running totals of (#greater, #equal) over earlier iterations
-  uint32_t g_base = 0, e_base = 0;
-  for_items<ITEMS>(n_iter, [&](int i) {
-    bool valid;
-    const uint32_t key = ckey_at(i, valid);
-    const bool isg = valid && key > T, ise = valid && key == T;
-    const uint64_t bg = __ballot(isg), be = __ballot(ise);
-    if (lane == 0) sh.wcnt[phase][wave] = ((uint32_t)__popcll(bg) << 16) | (uint32_t)__popcll(be);  // <= 64 each
-    __syncthreads();
-    uint32_t g_before = g_base, e_before = e_base, g_tot = 0, e_tot = 0;
-    for (int w = 0; w < nw; ++w) {
-      const uint32_t c = sh.wcnt[phase][w];
-      if (w < wave) { g_before += c >> 16; e_before += c & 0xffffu; }
-      g_tot += c >> 16;
-      e_tot += c & 0xffffu;
-    }
-    phase ^= 1;
-    g_before += (uint32_t)__popcll(bg & lanemask_lt());
-    e_before += (uint32_t)__popcll(be & lanemask_lt());
-    // position in the ascending output = selected neurons with a lower index
-    const uint32_t pos = g_before + (e_before < need ? e_before : need);
-    if (isg || (ise && e_before < need)) core_idx[pos] = i * nt + tid;
-    g_base += g_tot;
-    e_base += e_tot;
-  });
 }
 
 __global__ void zero_i32_kernel(int32_t* p, int n, uint32_t* ticket) {
@@ -280,13 +397,15 @@ template <int ITEMS>
 int launch_sel(const float* act, int M, int N, int64_t ld, int64_t q_alpha, int K, int32_t* counts,
                int32_t* core_idx, uint32_t* ticket, int grid, int nt, int privatise, size_t lds,
                hipStream_t s) {
-  if (lds > 48 * 1024) {
+  static bool attr_done = false;  // raise the dynamic-LDS ceiling once (64 KB by default)
+  if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<ITEMS>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024) != hipSuccess)
       return CI_ERR_HIP;
+    attr_done = true;
   }
   hipLaunchKernelGGL((select_kernel<ITEMS>), dim3(grid), dim3(nt), lds, s, act, M, N, ld, q_alpha, K,
-                     counts, core_idx, ticket, privatise);
+                     counts, core_idx, ticket, privatise, params().select_debug);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
@@ -309,10 +428,11 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
   if (grid > M) grid = M;
   const int tokens_per_wg = (M + grid - 1) / grid;
   // private u16 counters pay off only when a workgroup sees several tokens
-  // and they fit LDS
+  // and they fit LDS next to the digit histograms
+  const size_t hist_bytes = (size_t)kHistWords * 4;
   const size_t priv_bytes = (size_t)((N + 1) / 2) * 4;
-  const int privatise = (tokens_per_wg >= 2 && priv_bytes <= 128 * 1024) ? 1 : 0;
-  const size_t lds = privatise ? priv_bytes : 0;
+  const int privatise = (tokens_per_wg >= 2 && priv_bytes <= 88 * 1024) ? 1 : 0;
+  const size_t lds = hist_bytes + (privatise ? priv_bytes : 0);
 
 #define CI_SEL(I) launch_sel<I>(act, M, N, ld, q_alpha, K, counts, core_idx, ticket, grid, nt, privatise, lds, s)
   if (items <= 4) return CI_SEL(4);
