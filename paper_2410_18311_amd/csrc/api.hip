@@ -176,7 +176,12 @@ int coreinfer_ffn_dense_workspace_size(int64_t M, int64_t d, int64_t N, int dtyp
   // hidden matrix H [M, N]: fp32 on the row-dot path (M <= 4), element type
   // on the matrix-core path; plus the decode partials for a neuron-major down.
   size_t b = round256((size_t)M * (size_t)N * sizeof(float));
-  if (M <= 4) b += round256((size_t)M * (size_t)(N < kMaxSplits ? N : kMaxSplits) * (size_t)d * sizeof(float));
+  if (M <= 4) {
+    b += round256((size_t)M * (size_t)(N < kMaxSplits ? N : kMaxSplits) * (size_t)d * sizeof(float));
+  } else {
+    const int splits = gemm_down_splits(M, d, N, dtype);  // split-K partial products of Y
+    if (splits > 1) b += round256((size_t)splits * (size_t)M * (size_t)d * sizeof(float));
+  }
   *bytes = b + 256;
   return CI_OK;
 }
@@ -221,7 +226,9 @@ int coreinfer_ffn_dense(const void* X, int64_t M, const void* w_up, const void* 
   void* H = Y ? ws : nullptr;
   int rc = launch_gemm_up(X, M, w_up, w_gate, b_up, dtype, act, d, N, H, A, s);
   if (rc != CI_OK || !Y) return rc;
-  return launch_gemm_down(H, M, w_down, b_down, down_layout, dtype, d, N, Y, s);
+  float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) +
+                                            round256((size_t)M * (size_t)N * sizeof(float)));
+  return launch_gemm_down(H, M, w_down, b_down, down_layout, dtype, d, N, Y, partial, s);
 }
 
 }  // extern "C"

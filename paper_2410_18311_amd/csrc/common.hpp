@@ -147,7 +147,9 @@ int launch_down_rows(const float* H, int64_t M, const void* w_down, const void* 
                      int64_t d, int64_t N, void* Y, hipStream_t s);
 int launch_gemm_up(const void* X, int64_t M, const void* w_up, const void* w_gate, const void* b_up,
                    int dtype, int act, int64_t d, int64_t N, void* H, float* A, hipStream_t s);
+int gemm_down_splits(int64_t M, int64_t d, int64_t N, int dtype);
 int launch_gemm_down(const void* H, int64_t M, const void* w_down, const void* b_down,
-                     int down_layout, int dtype, int64_t d, int64_t N, void* Y, hipStream_t s);
+                     int down_layout, int dtype, int64_t d, int64_t N, void* Y, float* partial,
+                     hipStream_t s);
 
 }  // namespace ci

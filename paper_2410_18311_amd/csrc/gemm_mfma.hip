@@ -35,6 +35,8 @@ struct GemmArgs {
   float* out_f;    // [M, Nn] fp32, may be null
   int64_t lda, ldb, ldo;
   int M, Nn, Kk;
+  int k_chunk;     // k range handled by one workgroup along blockIdx.y (a multiple of the k tile)
+  float* partial;  // split-K only: [gridDim.y][M][Nn] fp32 partial products (epilogue skipped)
 };
 
 template <class D>
@@ -139,13 +141,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[q][i][j][v] = 0.f;
 
-  const int nk = (g.Kk + BK - 1) / BK;
-  load_global(0);
+  const int k_begin = blockIdx.y * g.k_chunk;
+  const int k_end = min(g.Kk, k_begin + g.k_chunk);
+  const int nk = (k_end - k_begin + BK - 1) / BK;
+  load_global(k_begin);
   store_lds(0);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    if (kt + 1 < nk) load_global(k_begin + (kt + 1) * BK);
     const T* sA = smem + cur * STAGE;
 #pragma unroll
     for (int s = 0; s < BK / 16; ++s) {
@@ -175,6 +179,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 
   // ---- epilogue.  Accumulator element v of lane l is C[row, col] with
   // col = l % 32, row = 8 * (v / 4) + 4 * (l / 32) + v % 4 inside a 32x32 tile.
+  if (g.partial) {  // split-K: raw fp32 partial products, reduced by splitk_reduce_kernel
+    float* part = g.partial + (size_t)blockIdx.y * g.M * g.Nn;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+      if (col >= g.Nn) continue;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (row < g.M) part[(size_t)row * g.Nn + col] = acc[0][i][j][v];
+        }
+    }
+    return;
+  }
   const T* bias = reinterpret_cast<const T*>(g.bias);
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
@@ -301,6 +321,32 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
   }
 }
 
+// Y[m, n] = sum_s partial[s][m][n] + bias[n], converted to the element type.
+template <class D>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial,
+                                                            const void* __restrict__ bias,
+                                                            void* __restrict__ out, int splits,
+                                                            int M, int Nn) {
+  using T = typename D::T;
+  const size_t total4 = (size_t)M * Nn / 4;
+  const size_t i4 = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i4 >= total4) return;
+  float4 a = reinterpret_cast<const float4*>(partial)[i4];
+  for (int s = 1; s < splits; ++s) {
+    const float4 v = reinterpret_cast<const float4*>(partial + (size_t)s * M * Nn)[i4];
+    a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+  }
+  const int col = (int)((i4 * 4) % Nn);
+  float o[4] = {a.x, a.y, a.z, a.w};
+  if (bias) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o[k] += to_float<D>(reinterpret_cast<const T*>(bias)[col + k]);
+  }
+  T* y = reinterpret_cast<T*>(out) + i4 * 4;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) y[k] = from_float<D>(o[k]);
+}
+
 template <class D, int EPI, bool BNN>
 int launch_mfma(const GemmArgs& g, hipStream_t s) {
   constexpr int NB = (EPI == EPI_SWIGLU) ? 2 : 1;
@@ -313,8 +359,15 @@ int launch_mfma(const GemmArgs& g, hipStream_t s) {
     attr_done = true;
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.Nn + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_mfma_kernel<D, EPI, BNN>), dim3(tiles), dim3(256), lds, s, g);
+  const int splits = g.partial ? (g.Kk + g.k_chunk - 1) / g.k_chunk : 1;
+  hipLaunchKernelGGL((gemm_mfma_kernel<D, EPI, BNN>), dim3(tiles, splits), dim3(256), lds, s, g);
   CI_HIP_CHECK_LAUNCH();
+  if (g.partial) {
+    const size_t total4 = (size_t)g.M * g.Nn / 4;
+    hipLaunchKernelGGL((splitk_reduce_kernel<D>), dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s,
+                       g.partial, g.bias, g.out_e, splits, g.M, g.Nn);
+    CI_HIP_CHECK_LAUNCH();
+  }
   return CI_OK;
 }
 
@@ -350,6 +403,8 @@ int launch_gemm_up(const void* X, int64_t M, const void* w_up, const void* w_gat
   g.Kk = (int)d;
   g.out_e = H;
   g.out_f = A;
+  g.k_chunk = (int)d;
+  g.partial = nullptr;
   if (act == CI_ACT_SWIGLU) {
     g.B0 = w_gate;
     g.B1 = w_up;
@@ -362,8 +417,22 @@ int launch_gemm_up(const void* X, int64_t M, const void* w_up, const void* w_gat
   return launch_any<EPI_RELU, false>(dtype, g, s);
 }
 
+// Number of k splits of the down projection: few output tiles (small M) would
+// leave most CUs idle, so the long reduction over N is cut into chunks.  A
+// pure function of the shape, so the workspace query can use it.
+int gemm_down_splits(int64_t M, int64_t d, int64_t N, int dtype) {
+  if (dtype == CI_F32) return 1;
+  const int64_t tiles = ((M + BM - 1) / BM) * ((d + BN - 1) / BN);
+  int64_t s = (512 + tiles - 1) / tiles;
+  const int64_t max_by_k = (N + 4 * BK - 1) / (4 * BK);  // at least four k tiles per split
+  if (s > max_by_k) s = max_by_k;
+  if (s > 8) s = 8;
+  return s < 1 ? 1 : (int)s;
+}
+
 int launch_gemm_down(const void* H, int64_t M, const void* w_down, const void* b_down,
-                     int down_layout, int dtype, int64_t d, int64_t N, void* Y, hipStream_t s) {
+                     int down_layout, int dtype, int64_t d, int64_t N, void* Y, float* partial,
+                     hipStream_t s) {
   GemmArgs g;
   g.A = H;
   g.lda = N;
@@ -376,6 +445,13 @@ int launch_gemm_down(const void* H, int64_t M, const void* w_down, const void* b
   g.M = (int)M;
   g.Nn = (int)d;
   g.Kk = (int)N;
+  const int splits = gemm_down_splits(M, d, N, dtype);
+  g.k_chunk = (int)N;
+  g.partial = nullptr;
+  if (splits > 1) {
+    g.k_chunk = (int)(((N + splits - 1) / splits + BK - 1) / BK * BK);
+    g.partial = partial;
+  }
   if (down_layout == CI_DOWN_OUT_MAJOR) {
     g.ldb = N;
     return launch_any<EPI_LINEAR, false>(dtype, g, s);
