@@ -80,7 +80,7 @@ int coreinfer_version(void);
  * (4, 8, 16 column quads per reduction workgroup), "decode_nt_store" (0/1),
  * "select_wgs_per_cu" (1..8), "select_debug" (timing only: 1 stops after the
  * per-token phase, 2 after the ticket; core_idx is then NOT written),
- * "gemv_wgs_per_cu" (1..32), "decode_skip_reduce"
+ * "gemv_wgs_per_cu" (1..32), "gemm_ring" (0/1), "decode_skip_reduce"
  * (0/1; 1 launches only the first decode kernel so that it can be timed
  * alone -- y is then NOT written).  Unknown name or value out of range:
  * CI_ERR_INVALID_ARG.  Not thread-safe against running

@@ -116,6 +116,7 @@ struct Params {
   int select_wgs_per_cu = 1;
   int select_debug = 0;
   int gemv_wgs_per_cu = 4;
+  int gemm_ring = 1;         // register-ring GEMM kernel where it applies
   int reduce_cq = 8;        // column quads per reduce workgroup (4, 8, 16)
   int decode_nt_store = 1;  // non-temporal stores for the partial sums
   int decode_skip_reduce = 0;  // timing only: launch the slice kernel without the reduction

@@ -62,6 +62,61 @@ __device__ __forceinline__ int xcd_swizzle(int id, int n) {
   return (id % 8) * (n / 8) + id / 8;
 }
 
+// Fused epilogue shared by the two MFMA kernels.  Accumulator element v of lane
+// l is C[row, col] with col = l % 32, row = 8 * (v / 4) + 4 * (l / 32) + v % 4
+// inside a 32x32 tile.
+template <class D, int EPI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16 (&acc)[EPI == EPI_SWIGLU ? 2 : 1][2][2],
+                                              int m0, int n0, int wm, int wn, int lane) {
+  using T = typename D::T;
+  constexpr int NB = (EPI == EPI_SWIGLU) ? 2 : 1;
+  if (g.partial) {  // split-K: raw fp32 partial products, reduced by splitk_reduce_kernel
+    float* part = g.partial + (size_t)blockIdx.y * g.M * g.Nn;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+      if (col >= g.Nn) continue;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (row < g.M) part[(size_t)row * g.Nn + col] = acc[0][i][j][v];
+        }
+    }
+    return;
+  }
+  const T* bias = reinterpret_cast<const T*>(g.bias);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+    if (col >= g.Nn) continue;
+    const float bv = bias ? to_float<D>(bias[col]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row >= g.M) continue;
+        float h, score;
+        if (EPI == EPI_SWIGLU) {
+          h = silu(acc[0][i][j][v]) * acc[NB - 1][i][j][v];
+          score = fabsf(h);
+        } else if (EPI == EPI_RELU) {
+          h = fmaxf(acc[0][i][j][v] + bv, 0.f);
+          score = h;
+        } else {
+          h = acc[0][i][j][v] + bv;
+          score = h;
+        }
+        const size_t o = (size_t)row * g.ldo + col;
+        if (g.out_f) g.out_f[o] = score;
+        if (g.out_e) reinterpret_cast<T*>(g.out_e)[o] = from_float<D>(h);
+      }
+    }
+  }
+}
+
 template <class D, int EPI, bool BNN>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   using T = typename D::T;
@@ -177,53 +232,121 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     }
   }
 
-  // ---- epilogue.  Accumulator element v of lane l is C[row, col] with
-  // col = l % 32, row = 8 * (v / 4) + 4 * (l / 32) + v % 4 inside a 32x32 tile.
-  if (g.partial) {  // split-K: raw fp32 partial products, reduced by splitk_reduce_kernel
-    float* part = g.partial + (size_t)blockIdx.y * g.M * g.Nn;
+  gemm_epilogue<D, EPI>(g, acc, m0, n0, wm, wn, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Fast path of the kernel above for k-contiguous B and a reduction length that
+// is a multiple of the k tile: the global loads of the next RD k-tiles are kept
+// in flight in a register ring (a tile is written to LDS only when it is about
+// to be used), because one k-tile of MFMA work (~0.4 us) is far shorter than a
+// memory round trip.  Every load is unconditional (rows past the edge are
+// clamped: they only feed outputs that are never stored), so the number of
+// outstanding loads is the same on every path and the waits are exact.
+template <class D, int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
+  using T = typename D::T;
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  constexpr int NB = DUAL ? 2 : 1;
+  constexpr int RD = DUAL ? 2 : 3;  // k-tiles in flight per thread
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* smem = reinterpret_cast<T*>(smem_raw);
+  constexpr int TILE = BM * LDK;
+  constexpr int STAGE = TILE * (1 + NB);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tiles_m = (g.M + BM - 1) / BM;
+  const int t = xcd_swizzle(blockIdx.x, gridDim.x);
+  const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
+  const int k_begin = blockIdx.y * g.k_chunk;
+  const int k_end = min(g.Kk, k_begin + g.k_chunk);
+  const int nk = (k_end - k_begin) / BK;
+
+  const T* pa[4];
+  const T* pb[NB][4];
+  int lds_off[4];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-      if (col >= g.Nn) continue;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          if (row < g.M) part[(size_t)row * g.Nn + col] = acc[0][i][j][v];
-        }
-    }
-    return;
+  for (int i = 0; i < 4; ++i) {
+    const int v = tid + 256 * i;
+    const int row = v >> 3, kc = (v & 7) * 8;
+    lds_off[i] = row * LDK + kc;
+    pa[i] = reinterpret_cast<const T*>(g.A) + (size_t)min(m0 + row, g.M - 1) * g.lda + k_begin + kc;
+    pb[0][i] = reinterpret_cast<const T*>(g.B0) + (size_t)min(n0 + row, g.Nn - 1) * g.ldb + k_begin + kc;
+    if (DUAL) pb[NB - 1][i] = reinterpret_cast<const T*>(g.B1) + (size_t)min(n0 + row, g.Nn - 1) * g.ldb + k_begin + kc;
   }
-  const T* bias = reinterpret_cast<const T*>(g.bias);
+
+  uint4 ra[RD][4], rb[RD][NB][4];
+#define CI_GEMM_ISSUE(slot, tile)                                   \
+  do {                                                              \
+    const int kk_ = min((tile), nk - 1) * BK;                       \
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {              \
+      ra[slot][i_] = ld16(pa[i_] + kk_);                            \
+      _Pragma("unroll") for (int q_ = 0; q_ < NB; ++q_)             \
+        rb[slot][q_][i_] = ld16(pb[q_][i_] + kk_);                  \
+    }                                                               \
+  } while (0)
+
+  f32x16 acc[NB][2][2];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-    if (col >= g.Nn) continue;
-    const float bv = bias ? to_float<D>(bias[col]) : 0.f;
+  for (int q = 0; q < NB; ++q)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row >= g.M) continue;
-        float h, score;
-        if (EPI == EPI_SWIGLU) {
-          h = silu(acc[0][i][j][v]) * acc[NB - 1][i][j][v];
-          score = fabsf(h);
-        } else if (EPI == EPI_RELU) {
-          h = fmaxf(acc[0][i][j][v] + bv, 0.f);
-          score = h;
-        } else {
-          h = acc[0][i][j][v] + bv;
-          score = h;
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[q][i][j][v] = 0.f;
+
+#pragma unroll
+  for (int r = 0; r < RD; ++r) {
+    CI_GEMM_ISSUE(r, r);
+    __builtin_amdgcn_sched_barrier(0);  // oldest tile first: the waits below count on this order
+  }
+
+  for (int kt0 = 0; kt0 < nk; kt0 += RD) {
+#pragma unroll
+    for (int r = 0; r < RD; ++r) {
+      const int kt = kt0 + r;
+      T* sA = smem + (kt & 1) * STAGE;
+      // tile kt: registers -> LDS (this buffer was last read two iterations ago, before the
+      // previous barrier), then the slot is refilled with tile kt + RD
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        *reinterpret_cast<uint4*>(sA + lds_off[i]) = ra[r][i];
+#pragma unroll
+        for (int q = 0; q < NB; ++q) *reinterpret_cast<uint4*>(sA + TILE * (1 + q) + lds_off[i]) = rb[r][q][i];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      CI_GEMM_ISSUE(r, kt + RD);
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+      if (kt < nk) {  // padding iterations (nk not a multiple of RD) skip the arithmetic only
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+          const int koff = s * 16 + (lane >> 5) * 8;
+          uint4 fa[2], fb[NB][2];
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            fa[i] = *reinterpret_cast<const uint4*>(sA + (wm * 64 + i * 32 + (lane & 31)) * LDK + koff);
+#pragma unroll
+          for (int q = 0; q < NB; ++q)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              fb[q][j] = *reinterpret_cast<const uint4*>(sA + TILE * (1 + q) +
+                                                         (wn * 64 + j * 32 + (lane & 31)) * LDK + koff);
+#pragma unroll
+          for (int q = 0; q < NB; ++q)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+              for (int j = 0; j < 2; ++j) acc[q][i][j] = mfma32<D>(fa[i], fb[q][j], acc[q][i][j]);
         }
-        const size_t o = (size_t)row * g.ldo + col;
-        if (g.out_f) g.out_f[o] = score;
-        if (g.out_e) reinterpret_cast<T*>(g.out_e)[o] = from_float<D>(h);
       }
     }
   }
+#undef CI_GEMM_ISSUE
+
+  gemm_epilogue<D, EPI>(g, acc, m0, n0, wm, wn, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -360,7 +483,19 @@ int launch_mfma(const GemmArgs& g, hipStream_t s) {
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.Nn + BN - 1) / BN);
   const int splits = g.partial ? (g.Kk + g.k_chunk - 1) / g.k_chunk : 1;
-  hipLaunchKernelGGL((gemm_mfma_kernel<D, EPI, BNN>), dim3(tiles, splits), dim3(256), lds, s, g);
+  const bool ring = !BNN && g.Kk % BK == 0 && g.k_chunk % BK == 0 && params().gemm_ring;
+  if (ring) {
+    static bool ring_attr_done = false;
+    if (lds > 48 * 1024 && !ring_attr_done) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_ring_kernel<D, EPI>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return CI_ERR_HIP;
+      ring_attr_done = true;
+    }
+    hipLaunchKernelGGL((gemm_mfma_ring_kernel<D, EPI>), dim3(tiles, splits), dim3(256), lds, s, g);
+  } else {
+    hipLaunchKernelGGL((gemm_mfma_kernel<D, EPI, BNN>), dim3(tiles, splits), dim3(256), lds, s, g);
+  }
   CI_HIP_CHECK_LAUNCH();
   if (g.partial) {
     const size_t total4 = (size_t)g.M * g.Nn / 4;
