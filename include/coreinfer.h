@@ -124,6 +124,47 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld,
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The two halves of coreinfer_select as separate calls, for callers that keep
+ * running counts while a sentence grows (Fig. 1 names a "stability estimation"
+ * that decides how the set is updated but does not specify it; Eq. 3 is a sum
+ * over tokens, so counts of new tokens simply add to the old ones):
+ *   coreinfer_count_tokens  steps 1-2 of coreinfer_select over the M rows of
+ *                           act; counts [N] is cleared first unless
+ *                           accumulate != 0, in which case it is added to.
+ *   coreinfer_count_select  step 3 on given counts (every value must lie in
+ *                           [0, max_count], max_count <= CI_MAX_TOKENS);
+ *                           core_idx [keep_count(beta, N)] ascending;
+ *                           ws: at least 256 bytes.
+ */
+int coreinfer_count_tokens(const float* act, int64_t M, int64_t N, int64_t ld, double alpha,
+                           int32_t* counts, int accumulate, void* stream);
+int coreinfer_count_select(const int32_t* counts, int64_t N, int64_t max_count, double beta,
+                           int32_t* core_idx, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Similarity-guided prediction, group step (Sec. 4.1): the core neurons of a
+ * semantic group are the top gamma share of neurons that appear most often in
+ * the core sets of the group's sentences.
+ *   core_sets [G, K] int32: the G sentences' core sets (any order; entries
+ *             outside [0, N) are ignored);  counts[n] = #{g : n in set g}
+ *             (out, may be NULL);  core_idx [keep_count(gamma, N)] ascending,
+ *             ties towards the lower index as in coreinfer_select.
+ *   ws: at least coreinfer_select_workspace_size(G, N) bytes.  G <= CI_MAX_TOKENS.
+ * How sentences are grouped (labels, K-Means; App. A.2.3) is outside this library.
+ */
+int coreinfer_group_select(const int32_t* core_sets, int64_t G, int64_t K, int64_t N, double gamma,
+                           int32_t* core_idx, int32_t* counts, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Core-neuron similarity of two sets (Sec. 3.2, Insight-2: identical neurons
+ * over all neurons involved).  set_a [Ka], set_b [Kb]: ascending, duplicate
+ * free.  out [2] int32 (device): out[0] = |a and b|, out[1] = |a or b|; the
+ * similarity is out[0] / out[1] (1 if both are empty).
+ */
+int coreinfer_core_similarity(const int32_t* set_a, int64_t Ka, const int32_t* set_b, int64_t Kb,
+                              int32_t* out, void* stream);
+
+/*
  * Deploy the core neurons (Sec. 5.3): gather rows S of w_up (and w_gate),
  * entries S of b_up and columns S of w_down into contiguous, neuron-major
  * buffers:

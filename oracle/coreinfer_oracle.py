@@ -24,6 +24,10 @@ What is here, and the passage each part follows:
   pre-filling": the rows / columns of the weights that S names.
 * ``core_similarity``       -- Insight-2 (Sec. 3.2): identical neurons over
   all neurons involved.
+* ``group_core_neurons``    -- similarity-guided prediction, group step
+  (Sec. 4.1): top-gamma of neurons by how many of the group's sentences have
+  them in their core set.
+* ``count_tokens_into``     -- Eq. 3 as a running sum when a sentence grows.
 
 Readings taken where the paper is silent or ambiguous (each is also listed in
 the design document):
@@ -223,6 +227,30 @@ def compact(S, W_up, W_down, W_gate=None, b_up=None):
     if b_up is not None:
         out["b_up_c"] = np.asarray(b_up)[S]
     return out
+
+
+def count_tokens_into(counts, A, alpha: float) -> np.ndarray:
+    """Running form of Eq. 3: the count set of a sentence that grew by the
+    tokens in A is the old count set plus the new tokens' contributions."""
+    return np.asarray(counts, dtype=np.int64) + count_set(A, alpha)
+
+
+def group_core_neurons(core_sets, n_neurons: int, gamma: float):
+    """Similarity-guided prediction, group step (Sec. 4.1): the top-gamma share
+    of neurons that appear most often in the core sets of the group's
+    sentences.  Returns (S ascending, counts)."""
+    counts = np.zeros(int(n_neurons), dtype=np.int64)
+    for S in core_sets:
+        for n in S:
+            if 0 <= int(n) < n_neurons:
+                counts[int(n)] += 1
+    return sentence_core_neurons(counts, gamma), counts
+
+
+def core_similarity_counts(S1, S2):
+    """(identical neurons, neurons involved) of Insight-2's similarity."""
+    a, b = set(int(v) for v in S1), set(int(v) for v in S2)
+    return len(a & b), len(a | b)
 
 
 def core_similarity(S1, S2) -> float:

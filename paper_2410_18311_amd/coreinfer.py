@@ -54,6 +54,10 @@ _SIGNATURES = {
     "coreinfer_keep_count": (_int, [_dbl, _i64, ctypes.POINTER(_i64)]),
     "coreinfer_select_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
+    "coreinfer_count_tokens": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _int, _vp]),
+    "coreinfer_count_select": (_int, [_vp, _i64, _i64, _dbl, _vp, _vp, _sz, _vp]),
+    "coreinfer_group_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _vp, _vp, _sz, _vp]),
+    "coreinfer_core_similarity": (_int, [_vp, _i64, _vp, _i64, _vp, _vp]),
     "coreinfer_compact": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64,
                                  _vp, _vp, _vp, _vp, _vp, _vp]),
     "coreinfer_ffn_decode_workspace_size": (_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
@@ -134,6 +138,57 @@ def select(act: torch.Tensor, alpha: float, beta: float, core_idx: Optional[torc
                                  _ptr(core_idx), _ptr(counts), _ptr(ws), ws.numel(), _stream(act)),
            "coreinfer_select")
     return core_idx, counts
+
+
+def count_tokens(act: torch.Tensor, alpha: float, counts: Optional[torch.Tensor] = None,
+                 accumulate: bool = False) -> torch.Tensor:
+    """coreinfer_count_tokens: Eq. 3 over the rows of act, optionally added to existing counts."""
+    assert act.dim() == 2 and act.dtype == torch.float32 and act.stride(1) == 1
+    M, N = act.shape
+    if counts is None:
+        assert not accumulate
+        counts = torch.empty(N, dtype=torch.int32, device=act.device)
+    _check(_lib.coreinfer_count_tokens(_ptr(act), M, N, act.stride(0), float(alpha), _ptr(counts),
+                                       1 if accumulate else 0, _stream(act)), "coreinfer_count_tokens")
+    return counts
+
+
+def count_select(counts: torch.Tensor, max_count: int, beta: float,
+                 core_idx: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """coreinfer_count_select: Def. 2 on given counts."""
+    N = counts.numel()
+    if core_idx is None:
+        core_idx = torch.empty(keep_count(beta, N), dtype=torch.int32, device=counts.device)
+    if ws is None:
+        ws = _workspace(256, counts)
+    _check(_lib.coreinfer_count_select(_ptr(counts), N, int(max_count), float(beta), _ptr(core_idx),
+                                       _ptr(ws), ws.numel(), _stream(counts)), "coreinfer_count_select")
+    return core_idx
+
+
+def group_select(core_sets: torch.Tensor, N: int, gamma: float, core_idx: Optional[torch.Tensor] = None,
+                 counts: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """coreinfer_group_select on core_sets [G, K] int32.  Returns (core_idx, counts)."""
+    assert core_sets.dim() == 2 and core_sets.dtype == torch.int32 and core_sets.is_contiguous()
+    G, K = core_sets.shape
+    if core_idx is None:
+        core_idx = torch.empty(keep_count(gamma, N), dtype=torch.int32, device=core_sets.device)
+    if counts is None:
+        counts = torch.empty(N, dtype=torch.int32, device=core_sets.device)
+    if ws is None:
+        ws = _workspace(select_workspace_size(G, N), core_sets)
+    _check(_lib.coreinfer_group_select(_ptr(core_sets), G, K, N, float(gamma), _ptr(core_idx), _ptr(counts),
+                                       _ptr(ws), ws.numel(), _stream(core_sets)), "coreinfer_group_select")
+    return core_idx, counts
+
+
+def core_similarity(set_a: torch.Tensor, set_b: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """coreinfer_core_similarity.  Returns the device tensor [identical, involved]."""
+    if out is None:
+        out = torch.empty(2, dtype=torch.int32, device=set_a.device)
+    _check(_lib.coreinfer_core_similarity(_ptr(set_a), set_a.numel(), _ptr(set_b), set_b.numel(), _ptr(out),
+                                          _stream(set_a)), "coreinfer_core_similarity")
+    return out
 
 
 def compact(w_up, w_gate, b_up, w_down, down_layout: str, act: str, core_idx: torch.Tensor,

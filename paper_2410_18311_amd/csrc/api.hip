@@ -121,7 +121,65 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld, double 
   // workspace: [N] counters (used when the caller passes none), then the ticket word
   int32_t* cnt = counts ? counts : reinterpret_cast<int32_t*>(ws);
   uint32_t* ticket = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(ws) + round256((size_t)N * sizeof(int32_t)));
-  return launch_select(act, M, N, ld, qa, keep(qb, N), core_idx, cnt, ticket, (hipStream_t)stream);
+  return launch_select(act, M, N, ld, qa, keep(qb, N), M, core_idx, cnt, ticket,
+                       kSelZero | kSelTokens | kSelFinal, (hipStream_t)stream);
+}
+
+int coreinfer_count_tokens(const float* act, int64_t M, int64_t N, int64_t ld, double alpha,
+                           int32_t* counts, int accumulate, void* stream) {
+  if (!act || !counts || M < 1 || M > CI_MAX_TOKENS || N < 1 || N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+  const int64_t qa = fraction_ppm(alpha);
+  if (qa == 0) return CI_ERR_INVALID_ARG;
+  if (ld < N) return CI_ERR_BAD_LAYOUT;
+  if ((reinterpret_cast<uintptr_t>(act) & 3u) || (reinterpret_cast<uintptr_t>(counts) & 3u)) return CI_ERR_BAD_LAYOUT;
+  return launch_select(act, M, N, ld, qa, 1, M, nullptr, counts, nullptr,
+                       (accumulate ? 0 : kSelZero) | kSelTokens, (hipStream_t)stream);
+}
+
+int coreinfer_count_select(const int32_t* counts, int64_t N, int64_t max_count, double beta,
+                           int32_t* core_idx, void* ws, size_t ws_bytes, void* stream) {
+  if (!counts || !core_idx || N < 1 || N > CI_MAX_NEURONS || max_count < 0 || max_count > CI_MAX_TOKENS)
+    return CI_ERR_INVALID_ARG;
+  const int64_t qb = fraction_ppm(beta);
+  if (qb == 0) return CI_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(counts) & 3u) || (reinterpret_cast<uintptr_t>(core_idx) & 3u)) return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < 256) return CI_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
+  return launch_select(nullptr, 0, N, N, 1, keep(qb, N), max_count, core_idx, const_cast<int32_t*>(counts),
+                       reinterpret_cast<uint32_t*>(ws), kSelFinal, (hipStream_t)stream);
+}
+
+int coreinfer_group_select(const int32_t* core_sets, int64_t G, int64_t K, int64_t N, double gamma,
+                           int32_t* core_idx, int32_t* counts, void* ws, size_t ws_bytes, void* stream) {
+  size_t need = 0;
+  if (G < 1 || G > CI_MAX_TOKENS || coreinfer_select_workspace_size(G, N, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!core_sets || !core_idx || K < 0 || K > N) return CI_ERR_INVALID_ARG;
+  const int64_t qg = fraction_ppm(gamma);
+  if (qg == 0) return CI_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(core_sets) & 3u) || (reinterpret_cast<uintptr_t>(core_idx) & 3u) ||
+      (reinterpret_cast<uintptr_t>(counts) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
+  int32_t* cnt = counts ? counts : reinterpret_cast<int32_t*>(ws);
+  uint32_t* ticket = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(ws) + round256((size_t)N * sizeof(int32_t)));
+  hipStream_t s = (hipStream_t)stream;
+  // clear the counters, count the groups' members, then Def. 2 with gamma on the counters
+  int rc = launch_select(nullptr, 0, N, N, 1, 1, G, nullptr, cnt, ticket, kSelZero, s);
+  if (rc != CI_OK) return rc;
+  rc = launch_scatter_count(core_sets, G * K, N, cnt, s);
+  if (rc != CI_OK) return rc;
+  return launch_select(nullptr, 0, N, N, 1, keep(qg, N), G, core_idx, cnt, ticket, kSelFinal, s);
+}
+
+int coreinfer_core_similarity(const int32_t* set_a, int64_t Ka, const int32_t* set_b, int64_t Kb,
+                              int32_t* out, void* stream) {
+  if (!out || Ka < 0 || Kb < 0 || Ka > CI_MAX_NEURONS || Kb > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+  if ((Ka > 0 && !set_a) || (Kb > 0 && !set_b)) return CI_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(set_a) & 3u) || (reinterpret_cast<uintptr_t>(set_b) & 3u) ||
+      (reinterpret_cast<uintptr_t>(out) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  return launch_similarity(set_a, Ka, set_b, Kb, out, (hipStream_t)stream);
 }
 
 int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,

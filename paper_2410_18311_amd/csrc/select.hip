@@ -145,7 +145,8 @@ template <int ITEMS>
 __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ act, int M, int N,
                                                       int64_t ld, int64_t q_alpha, int K,
                                                       int32_t* counts, int32_t* core_idx,
-                                                      uint32_t* ticket, int privatise, int debug) {
+                                                      uint32_t* ticket, int privatise, int max_count,
+                                                      int debug) {
   __shared__ SelShared sh;
   extern __shared__ uint32_t dyn[];  // [kHistWords] histograms, then [ceil(N/2)] packed u16 counters
   uint32_t* hist = dyn;
@@ -293,9 +294,9 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
     return valid ? c : 0xffffffffu;
   };
 
-  // counts are <= M <= 65535: two 8-bit digits; the high one is skipped when M < 256
+  // counts are <= max_count <= 65535: two 8-bit digits; the high one is skipped below 256
   uint32_t prefix = 0, prefix_mask = 0xffff0000u, need = (uint32_t)K, n_eq = 0;
-  if (M >= 256) radix_pass<ITEMS>(ckey_sel, n_iter, 8, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
+  if (max_count >= 256) radix_pass<ITEMS>(ckey_sel, n_iter, 8, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
   else prefix_mask |= 0xff00u;
   radix_pass<ITEMS>(ckey_sel, n_iter, 0, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
   const uint32_t T = prefix;
@@ -390,13 +391,52 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
 __global__ void zero_i32_kernel(int32_t* p, int n, uint32_t* ticket) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
-  if (i == 0) *ticket = 0;
+  if (i == 0 && ticket) *ticket = 0;
+}
+
+// counts[idx] += 1 for every entry of an index list (entries outside [0, N)
+// are ignored).  Integer atomics: the result does not depend on the order.
+__global__ void scatter_count_kernel(const int32_t* __restrict__ idx, int64_t n_idx, int N,
+                                     int32_t* counts) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_idx) {
+    const int n = idx[i];
+    if (n >= 0 && n < N) atomicAdd(&counts[n], 1);
+  }
+}
+
+// out[0] = |a ∩ b|, out[1] = |a ∪ b| for two ascending duplicate-free index
+// lists (Insight-2's similarity is out[0] / out[1]).  One workgroup; every
+// element of a is looked up in b by binary search.
+__global__ __launch_bounds__(1024) void similarity_kernel(const int32_t* __restrict__ a, int Ka,
+                                                          const int32_t* __restrict__ b, int Kb,
+                                                          int32_t* out) {
+  __shared__ uint32_t wsum[kMaxWaves];
+  uint32_t hits = 0;
+  for (int i = threadIdx.x; i < Ka; i += blockDim.x) {
+    const int v = a[i];
+    int lo = 0, hi = Kb;  // first position with b[pos] >= v
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (b[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    hits += (lo < Kb && b[lo] == v);
+  }
+  hits = (uint32_t)wave_sum((int)hits);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = hits;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t t = 0;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += wsum[w];
+    out[0] = (int32_t)t;
+    out[1] = Ka + Kb - (int32_t)t;
+  }
 }
 
 template <int ITEMS>
 int launch_sel(const float* act, int M, int N, int64_t ld, int64_t q_alpha, int K, int32_t* counts,
                int32_t* core_idx, uint32_t* ticket, int grid, int nt, int privatise, size_t lds,
-               hipStream_t s) {
+               int max_count, int stop, hipStream_t s) {
   static bool attr_done = false;  // raise the dynamic-LDS ceiling once (64 KB by default)
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<ITEMS>),
@@ -405,27 +445,37 @@ int launch_sel(const float* act, int M, int N, int64_t ld, int64_t q_alpha, int 
     attr_done = true;
   }
   hipLaunchKernelGGL((select_kernel<ITEMS>), dim3(grid), dim3(nt), lds, s, act, M, N, ld, q_alpha, K,
-                     counts, core_idx, ticket, privatise, params().select_debug);
+                     counts, core_idx, ticket, privatise, max_count, stop);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
 
 }  // namespace
 
+// The three stages of the selection, individually switchable:
+//   kSelZero   clear the counters (else they are accumulated into: Eq. 3 is a sum over tokens)
+//   kSelTokens Def. 1 + Eq. 3 over the M rows of act
+//   kSelFinal  Def. 2 on the counters (values <= max_count)
 int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_t q_alpha,
-                  int64_t K64, int32_t* core_idx, int32_t* counts, uint32_t* ticket, hipStream_t s) {
-  const int M = (int)M64, N = (int)N64, K = (int)K64;
+                  int64_t K64, int64_t max_count, int32_t* core_idx, int32_t* counts,
+                  uint32_t* ticket, int what, hipStream_t s) {
+  const int M = (what & kSelTokens) ? (int)M64 : 0, N = (int)N64, K = (int)K64;
   DeviceInfo di;
   int rc = device_info(&di);
   if (rc != CI_OK) return rc;
 
-  hipLaunchKernelGGL(zero_i32_kernel, dim3((N + 255) / 256), dim3(256), 0, s, counts, N, ticket);
-  CI_HIP_CHECK_LAUNCH();
+  if ((what & kSelZero) || (what & kSelFinal)) {
+    const int nz = (what & kSelZero) ? N : 0;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3(nz > 0 ? (nz + 255) / 256 : 1), dim3(256), 0, s, counts, nz, ticket);
+    CI_HIP_CHECK_LAUNCH();
+  }
+  if (!(what & (kSelTokens | kSelFinal))) return CI_OK;
 
   const int nt = N >= 4096 ? 1024 : 256;
   const int items = (N + nt - 1) / nt;
   int grid = di.cus * params().select_wgs_per_cu;
   if (grid > M) grid = M;
+  if (grid < 1) grid = 1;
   const int tokens_per_wg = (M + grid - 1) / grid;
   // private u16 counters pay off only when a workgroup sees several tokens
   // and they fit LDS next to the digit histograms
@@ -433,13 +483,29 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
   const size_t priv_bytes = (size_t)((N + 1) / 2) * 4;
   const int privatise = (tokens_per_wg >= 2 && priv_bytes <= 88 * 1024) ? 1 : 0;
   const size_t lds = hist_bytes + (privatise ? priv_bytes : 0);
+  const int stop = (what & kSelFinal) ? params().select_debug : 1;  // 1: return before the ticket
+  const int mc = (int)max_count;
 
-#define CI_SEL(I) launch_sel<I>(act, M, N, ld, q_alpha, K, counts, core_idx, ticket, grid, nt, privatise, lds, s)
+#define CI_SEL(I) launch_sel<I>(act, M, N, ld, q_alpha, K, counts, core_idx, ticket, grid, nt, privatise, lds, mc, stop, s)
   if (items <= 4) return CI_SEL(4);
   if (items <= 8) return CI_SEL(8);
   if (items <= 16) return CI_SEL(16);
   return CI_SEL(0);
 #undef CI_SEL
+}
+
+int launch_scatter_count(const int32_t* idx, int64_t n_idx, int64_t N, int32_t* counts, hipStream_t s) {
+  if (n_idx <= 0) return CI_OK;
+  hipLaunchKernelGGL(scatter_count_kernel, dim3((unsigned)((n_idx + 255) / 256)), dim3(256), 0, s, idx, n_idx,
+                     (int)N, counts);
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
+
+int launch_similarity(const int32_t* a, int64_t Ka, const int32_t* b, int64_t Kb, int32_t* out, hipStream_t s) {
+  hipLaunchKernelGGL(similarity_kernel, dim3(1), dim3(1024), 0, s, a, (int)Ka, b, (int)Kb, out);
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
 }
 
 }  // namespace ci

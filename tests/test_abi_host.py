@@ -21,7 +21,7 @@ def _declared_symbols():
 
 def test_library_exports_every_declared_symbol(lib):
     names = _declared_symbols()
-    assert len(names) >= 11
+    assert len(names) >= 15
     for n in names:
         assert hasattr(lib.raw, n), n
     assert set(names) == set(lib.EXPORTS)
@@ -142,6 +142,33 @@ def test_ffn_dense_rejects_bad_arguments_without_a_gpu(lib):
     assert r(F, 8, F, None, None, F, None, 0, 1, 0, 64, 100, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
     assert r(F, 8, F, None, None, F, None, 0, 1, 0, 64, 128, F, None, None, big, None) == lib.CI_ERR_WORKSPACE
     assert r(F, 8, F, None, None, F, None, 0, 1, 0, 64, 128, F, None, F, 100, None) == lib.CI_ERR_WORKSPACE
+
+
+def test_next_row_entry_points_reject_bad_arguments_without_a_gpu(lib):
+    F = FAKE
+    r = lib.raw.coreinfer_count_tokens
+    assert r(None, 4, 64, 64, 0.2, F, 0, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 64, 0.2, None, 0, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 64, 1.2, F, 0, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 10, 0.2, F, 0, None) == lib.CI_ERR_BAD_LAYOUT
+    r = lib.raw.coreinfer_count_select
+    assert r(None, 64, 10, 0.4, F, F, 256, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 64, 70000, 0.4, F, F, 256, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 64, 10, 0.0, F, F, 256, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 64, 10, 0.4, F, None, 256, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 64, 10, 0.4, F, F, 8, None) == lib.CI_ERR_WORKSPACE
+    r = lib.raw.coreinfer_group_select
+    big = 1 << 20
+    assert r(None, 3, 8, 64, 0.2, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 0, 8, 64, 0.2, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 3, 80, 64, 0.2, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 3, 8, 64, 2.0, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 3, 8, 64, 0.2, F, None, F, 16, None) == lib.CI_ERR_WORKSPACE
+    r = lib.raw.coreinfer_core_similarity
+    assert r(F, 4, F, 4, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(None, 4, F, 4, F, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, -1, F, 4, F, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F + 2, 4, F, 4, F, None) == lib.CI_ERR_BAD_LAYOUT
 
 
 def test_set_param_validation(lib):

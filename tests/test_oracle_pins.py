@@ -331,3 +331,44 @@ def test_sparse_error_shrinks_as_beta_grows():
     dense = orc.ffn_relu(t["x"], None, t["W_up"], t["b_up"], t["W_down"], t["b_down"])
     S, _ = orc.select(A, 0.5, 1.0)
     assert np.abs(orc.ffn_relu(t["x"], S, t["W_up"], t["b_up"], t["W_down"], t["b_down"]) - dense).max() == 0.0
+
+
+# ------------------------------------------- group sets, running counts, similarity
+
+def test_group_core_neurons_hand_example_and_identity():
+    # three sentences' core sets over 6 neurons: neuron 1 in all three, 0 and 4 in two, 3 in one
+    sets = [[0, 1, 4], [1, 4, 3], [0, 1, 5]]
+    S, counts = orc.group_core_neurons(sets, 6, 0.5)
+    assert counts.tolist() == [2, 3, 0, 1, 2, 1]
+    assert S.tolist() == [0, 1, 4]                      # K = 3: counts 3, 2, 2
+    S2, _ = orc.group_core_neurons(sets, 6, 0.67)       # K = ceil(4.02) = 5: tie at count 1 -> lower index 3
+    assert S2.tolist() == [0, 1, 3, 4, 5][:5] and len(S2) == 5
+    # identity: the group step equals Def. 1-2 applied to the 0/1 membership matrix with alpha = 1
+    rng = np.random.default_rng(8)
+    N, G, K = 50, 7, 12
+    sets = [np.sort(rng.choice(N, size=K, replace=False)) for _ in range(G)]
+    member = np.zeros((G, N))
+    for g, S_g in enumerate(sets):
+        member[g, S_g] = 1.0
+    for gamma in (0.1, 0.3, 0.8):
+        S_a, c_a = orc.group_core_neurons(sets, N, gamma)
+        S_b, c_b = orc.select(member, 1.0, gamma)
+        assert S_a.tolist() == S_b.tolist() and c_a.tolist() == c_b.tolist()
+
+
+def test_running_counts_equal_counts_of_the_whole_sentence():
+    from paper_2410_18311_amd.workloads import activation_like
+    A = activation_like(20, 64, seed=4, kind="relu")
+    whole = orc.count_set(A, 0.25)
+    run = np.zeros(64, dtype=np.int64)
+    for lo, hi in ((0, 7), (7, 8), (8, 20)):
+        run = orc.count_tokens_into(run, A[lo:hi], 0.25)
+    assert run.tolist() == whole.tolist()
+
+
+def test_similarity_counts_hand_values():
+    assert orc.core_similarity_counts([0, 1, 2], [1, 2, 3]) == (2, 4)
+    assert orc.core_similarity_counts([], []) == (0, 0)
+    assert orc.core_similarity_counts([5], [5]) == (1, 1)
+    i, u = orc.core_similarity_counts([1, 4, 9], [2, 4])
+    assert (i, u) == (1, 4) and orc.core_similarity([1, 4, 9], [2, 4]) == 0.25

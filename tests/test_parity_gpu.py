@@ -389,3 +389,91 @@ def test_full_size_layer_gathered_eight_sentences(lib):
         y_ref = orc.ffn_relu(f64(x[s]), None, up_rows, f64(w["b_up"])[Sn], down_rows.T, f64(w["b_down"]))
         rel = assert_close_rms(y[s], y_ref, torch.float16, f"gathered sentence {s}")
         _say(f"  sentence {s}: max err / rms = {rel:.2e}")
+
+
+# --------------------------------- running counts, group sets, similarity (next rows)
+
+def test_running_counts_and_count_select_match_oracle(lib):
+    A_np = wl.activation_like(300, 5000, seed=21, kind="relu", levels=16)
+    A = torch.from_numpy(A_np).to(DEV)
+    counts = lib.count_tokens(A[:100].contiguous(), 0.2)
+    lib.count_tokens(A[100:101].contiguous(), 0.2, counts=counts, accumulate=True)
+    lib.count_tokens(A[101:].contiguous(), 0.2, counts=counts, accumulate=True)
+    S = lib.count_select(counts, 300, 0.4)
+    S_all, c_all = lib.select(A, 0.2, 0.4)
+    torch.cuda.synchronize()
+    ref = np.zeros(5000, dtype=np.int64)
+    for lo, hi in ((0, 100), (100, 101), (101, 300)):
+        ref = orc.count_tokens_into(ref, A_np[lo:hi], 0.2)
+    assert counts.cpu().numpy().tolist() == ref.tolist()
+    assert S.cpu().numpy().tolist() == orc.sentence_core_neurons(ref, 0.4).tolist()
+    assert torch.equal(S, S_all) and torch.equal(counts, c_all)
+    # count_select on arbitrary counts, small and large bounds, huge tie classes
+    rng = np.random.default_rng(3)
+    for N, mx, beta in ((1000, 3, 0.5), (16384, 255, 0.4), (16384, 256, 0.4), (40000, 65535, 0.1), (7, 1, 1.0)):
+        c = rng.integers(0, mx + 1, size=N).astype(np.int32)
+        got = lib.count_select(torch.from_numpy(c).to(DEV), mx, beta)
+        torch.cuda.synchronize()
+        assert got.cpu().numpy().tolist() == orc.sentence_core_neurons(c, beta).tolist(), (N, mx, beta)
+
+
+@pytest.mark.parametrize("G,K,N,gamma", [(1, 5, 40, 0.2), (12, 410, 1024, 0.2), (50, 6554, 16384, 0.4), (300, 100, 3000, 0.05)])
+def test_group_select_matches_oracle(lib, G, K, N, gamma):
+    _say("group select case", G, K, N, gamma)
+    rng = np.random.default_rng(G + K)
+    # sentences of one semantic group share most of their core neurons
+    base = rng.choice(N, size=K, replace=False)
+    sets = []
+    for _ in range(G):
+        s = base.copy()
+        swap = rng.random(K) < 0.3
+        s[swap] = rng.choice(N, size=int(swap.sum()), replace=False)
+        sets.append(np.unique(np.concatenate([s, rng.choice(N, size=K, replace=False)]))[:K])
+    sets_np = np.stack([np.sort(rng.permutation(s)) for s in sets]).astype(np.int32)
+    S, counts = lib.group_select(torch.from_numpy(sets_np).to(DEV), N, gamma)
+    torch.cuda.synchronize()
+    S_ref, c_ref = orc.group_core_neurons(sets_np, N, gamma)
+    assert counts.cpu().numpy().tolist() == c_ref.tolist()
+    assert S.cpu().numpy().tolist() == S_ref.tolist()
+
+
+def test_core_similarity_matches_oracle(lib):
+    rng = np.random.default_rng(17)
+    for N, Ka, Kb in ((100, 0, 0), (100, 10, 0), (16384, 6554, 6554), (36864, 14746, 9000), (50, 50, 50)):
+        a = np.sort(rng.choice(N, size=Ka, replace=False)).astype(np.int32)
+        b = np.sort(rng.choice(N, size=Kb, replace=False)).astype(np.int32)
+        out = lib.core_similarity(torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV))
+        torch.cuda.synchronize()
+        assert tuple(out.cpu().numpy().tolist()) == orc.core_similarity_counts(a, b), (N, Ka, Kb)
+
+
+def test_decode_graph_replays_match_eager(lib):
+    """The decode launches captured in a HIP graph give the eager result on every replay,
+    with other work and synchronisations in between."""
+    d, N, K = 1024, 3000, 1201
+    w = rand_weights(d, N, torch.float16, "relu", "out_major", seed=5, device=DEV)
+    S = np.sort(np.random.default_rng(1).choice(N, size=K, replace=False))
+    c = lib.compact(w["w_up"], None, w["b_up"], w["w_down"], "out_major", "relu",
+                    torch.from_numpy(S.astype(np.int32)).to(DEV))
+    desc = lib.make_weights(c["w_up_c"], None, c["b_up_c"], c["w_down_c"], w["b_down"])
+    x = torch.randn(1, d, generator=torch.Generator().manual_seed(2)).half().to(DEV)
+    y = torch.empty_like(x)
+    ws = torch.empty(lib.ffn_decode_workspace_size(1, K, d), dtype=torch.uint8, device=DEV)
+    lib.ffn_decode(x, desc, "relu", y=y, ws=ws)
+    torch.cuda.synchronize()
+    eager = y.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        lib.ffn_decode(x, desc, "relu", y=y, ws=ws)
+    for i in range(4):
+        y.zero_()
+        ws.fill_(0xFF)                               # stale scratch must not matter
+        (torch.randn(256, 256, device=DEV) @ torch.randn(256, 256, device=DEV)).sum().item()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager), f"replay {i}"
+    # new input through the same graph
+    x.copy_(torch.randn(1, d, generator=torch.Generator().manual_seed(3)).half())
+    g.replay()
+    torch.cuda.synchronize()
+    assert_close_rms(y[0], _oracle_ffn("relu", x[0], S, w, "out_major"), torch.float16, "graph, new input")
