@@ -28,6 +28,10 @@ What is here, and the passage each part follows:
   (Sec. 4.1): top-gamma of neurons by how many of the group's sentences have
   them in their core set.
 * ``count_tokens_into``     -- Eq. 3 as a running sum when a sentence grows.
+* ``union_rows``            -- batching several sentences that share resident
+  weights (the Sec. 5.3 large-model scenario): the neurons any sentence
+  needs, each tagged with the sentences that own it.  The decode result of a
+  batch is by definition each sentence's own ``ffn_relu`` / ``ffn_swiglu``.
 
 Readings taken where the paper is silent or ambiguous (each is also listed in
 the design document):
@@ -245,6 +249,22 @@ def group_core_neurons(core_sets, n_neurons: int, gamma: float):
             if 0 <= int(n) < n_neurons:
                 counts[int(n)] += 1
     return sentence_core_neurons(counts, gamma), counts
+
+
+def union_rows(core_sets, n_neurons: int):
+    """Rows of the weight matrices that a batch of sentences needs: U = the
+    union of the sentences' core sets (ascending) and, per row of U, a bit
+    mask whose bit s says that sentence s owns the row.  Indices outside
+    [0, n_neurons) name no neuron and are ignored.  At most 32 sentences."""
+    if len(core_sets) > 32:
+        raise ValueError("at most 32 sentences")
+    owners = np.zeros(int(n_neurons), dtype=np.uint32)
+    for s, S in enumerate(core_sets):
+        for n in S:
+            if 0 <= int(n) < n_neurons:
+                owners[int(n)] |= np.uint32(1 << s)
+    U = np.flatnonzero(owners).astype(np.int64)
+    return U, owners[U]
 
 
 def core_similarity_counts(S1, S2):

@@ -13,12 +13,11 @@
 // Kernel 2 (decode_reduce_kernel): sums the partials in a fixed order (so the
 // result is deterministic), adds b_down, converts to the element type.
 #include "common.hpp"
+#include "decode_common.hpp"
 
 namespace ci {
 
 namespace {
-
-constexpr int kSuper = 64;  // rows of a slice handled between two barriers (<= smallest workgroup)
 
 struct DecodeArgs {
   const void* x;
@@ -32,36 +31,6 @@ struct DecodeArgs {
   int nt_store;
 };
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-// 16-byte streaming load: the weights are read once per token and never
-// reused, so they are marked non-temporal.
-__device__ __forceinline__ uint4 ld16_stream(const void* p) {
-  const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-  return make_uint4(t[0], t[1], t[2], t[3]);
-}
-
-// Sums DEPTH per-lane values across the wave with a halving butterfly: after
-// the call every lane holds the wave-wide sum of value number
-// lane / (64 / DEPTH) -- for DEPTH = 8, 10 shuffles instead of 48.
-template <int N, int BIT>
-__device__ __forceinline__ void halve_rows(float* v, int lane) {
-  if constexpr (N > 1) {
-    const bool hi = (lane & BIT) != 0;
-#pragma unroll
-    for (int i = 0; i < N / 2; ++i) {
-      const float send = hi ? v[i] : v[i + N / 2];
-      const float keep = hi ? v[i + N / 2] : v[i];
-      v[i] = keep + __shfl_xor(send, BIT, kWave);
-    }
-    halve_rows<N / 2, BIT / 2>(v, lane);
-  } else {
-    float r = v[0];
-#pragma unroll
-    for (int bit = BIT; bit >= 1; bit >>= 1) r += __shfl_xor(r, bit, kWave);
-    v[0] = r;
-  }
-}
 template <int DEPTH>
 __device__ __forceinline__ float wave_sum_rows(float (&v)[DEPTH], int lane) {
   static_assert(DEPTH == 4 || DEPTH == 8 || DEPTH == 16, "ring depth");
@@ -345,6 +314,26 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
   }
 }
 
+template <class D>
+int launch_reduce_typed(const float* partial, const void* b_down, void* y, int n_wg, int d, int B,
+                        hipStream_t s) {
+  switch (params().reduce_cq) {
+    case 4:
+      hipLaunchKernelGGL((decode_reduce_kernel<D, 4>), dim3((d + 15) / 16, B), dim3(256), 0, s,
+                         partial, b_down, y, n_wg, d);
+      break;
+    case 16:
+      hipLaunchKernelGGL((decode_reduce_kernel<D, 16>), dim3((d + 63) / 64, B), dim3(256), 0, s,
+                         partial, b_down, y, n_wg, d);
+      break;
+    default:
+      hipLaunchKernelGGL((decode_reduce_kernel<D, 8>), dim3((d + 31) / 32, B), dim3(256), 0, s,
+                         partial, b_down, y, n_wg, d);
+  }
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
+
 template <class D, int NI, bool SWIGLU, bool GATHER>
 int launch_depth(const DecodeArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
   int depth = params().decode_depth;
@@ -377,21 +366,7 @@ int launch_typed(const DecodeArgs& a, int B, int nt, int ni, const void* b_down,
     if (rc != CI_OK) return rc;
   }
   if (params().decode_skip_reduce) return CI_OK;
-  switch (params().reduce_cq) {
-    case 4:
-      hipLaunchKernelGGL((decode_reduce_kernel<D, 4>), dim3((a.d + 15) / 16, B), dim3(256), 0, s,
-                         a.partial, b_down, y, a.n_wg, a.d);
-      break;
-    case 16:
-      hipLaunchKernelGGL((decode_reduce_kernel<D, 16>), dim3((a.d + 63) / 64, B), dim3(256), 0, s,
-                         a.partial, b_down, y, a.n_wg, a.d);
-      break;
-    default:
-      hipLaunchKernelGGL((decode_reduce_kernel<D, 8>), dim3((a.d + 31) / 32, B), dim3(256), 0, s,
-                         a.partial, b_down, y, a.n_wg, a.d);
-  }
-  CI_HIP_CHECK_LAUNCH();
-  return CI_OK;
+  return launch_reduce_typed<D>(a.partial, b_down, y, a.n_wg, a.d, B, s);
 }
 
 // Workgroup width for a row of `vecs` 16-byte vectors: NI loads per thread
@@ -439,6 +414,16 @@ int decode_splits(int64_t B, int64_t K) {
   if (n > K) n = K;
   if (n < 1) n = 1;
   return (int)n;
+}
+
+int launch_decode_reduce(const float* partial, const void* b_down, void* y, int n_wg, int d, int B,
+                         int dtype, hipStream_t s) {
+  switch (dtype) {
+    case CI_F32: return launch_reduce_typed<F32>(partial, b_down, y, n_wg, d, B, s);
+    case CI_F16: return launch_reduce_typed<F16>(partial, b_down, y, n_wg, d, B, s);
+    case CI_BF16: return launch_reduce_typed<BF16>(partial, b_down, y, n_wg, d, B, s);
+  }
+  return CI_ERR_BAD_DTYPE;
 }
 
 int launch_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,

@@ -372,3 +372,25 @@ def test_similarity_counts_hand_values():
     assert orc.core_similarity_counts([5], [5]) == (1, 1)
     i, u = orc.core_similarity_counts([1, 4, 9], [2, 4])
     assert (i, u) == (1, 4) and orc.core_similarity([1, 4, 9], [2, 4]) == 0.25
+
+
+def test_union_rows_hand_example_and_set_identities():
+    # three sentences over 8 neurons; 9 and -1 name no neuron
+    sets = [[0, 3, 5], [3, 4, 9], [-1, 5, 7]]
+    U, owners = orc.union_rows(sets, 8)
+    assert U.tolist() == [0, 3, 4, 5, 7]
+    assert owners.tolist() == [0b001, 0b011, 0b010, 0b101, 0b100]
+    # against Python set algebra on random sets: U is the sorted union, and the
+    # rows tagged with bit s are exactly sentence s's set
+    rng = np.random.default_rng(11)
+    sets = [rng.choice(50, size=12, replace=False) for _ in range(6)]
+    U, owners = orc.union_rows(sets, 50)
+    assert U.tolist() == sorted(set().union(*[set(map(int, S)) for S in sets]))
+    for s, S in enumerate(sets):
+        assert U[(owners >> np.uint32(s)) & np.uint32(1) == 1].tolist() == sorted(map(int, S))
+    assert sum(bin(int(m)).count("1") for m in owners) == 6 * 12
+    # one sentence: the union is its own set, every owner mask is 1
+    U, owners = orc.union_rows([[4, 2, 2, 6]], 8)
+    assert U.tolist() == [2, 4, 6] and owners.tolist() == [1, 1, 1]
+    U, owners = orc.union_rows([[], []], 8)
+    assert U.size == 0 and owners.size == 0
