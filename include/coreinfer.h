@@ -64,6 +64,7 @@ typedef enum { CI_DOWN_OUT_MAJOR = 0, CI_DOWN_NEURON_MAJOR = 1 } ci_down_layout;
 #define CI_MAX_TOKENS 65535     /* M: counts fit 16 bits                */
 #define CI_MAX_NEURONS 1048576  /* N                                   */
 #define CI_MAX_DMODEL 32768     /* d                                   */
+#define CI_MAX_UNION_SENTENCES 8 /* sentences of a union-batched decode */
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* coreinfer_strerror(int status);
@@ -215,6 +216,42 @@ int coreinfer_ffn_decode_workspace_size(int64_t B, int64_t K, int64_t d, size_t*
 int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w,
                          int dtype, int act, void* y,
                          void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Union-batched decode.  Several sentences, each with its own frozen core set
+ * (stability-guided prediction, Sec. 4.1), decode one token each against the
+ * same resident weights (the large-model scenario of Sec. 5.3).  Each row of
+ * the UNION of the core sets is read once and applied to the sentences that
+ * own it; per sentence the result is exactly the sparse FFN of Sec. 4.2 over
+ * its own set, i.e. what coreinfer_ffn_decode computes with core_idx = [B, K].
+ *
+ * coreinfer_union_build: core_idx [B, K] int32 (device; any order, entries
+ *   outside [0, N) are ignored, duplicates allowed), B <= CI_MAX_UNION_SENTENCES.
+ *   Out (device, caller-owned): union_idx [max_rows] int32, ascending, the
+ *   neurons in at least one set; union_mask [max_rows] uint32, bit s set iff
+ *   sentence s owns the row; union_count [1] int32, the number of rows.
+ *   max_rows >= min(N, B*K) (CI_ERR_INVALID_ARG otherwise).  Entries past
+ *   union_count are left untouched.  ws: coreinfer_union_workspace_size(N) bytes.
+ *
+ * coreinfer_ffn_decode_union: x [B, d], y [B, d] of `dtype`; w->w_up,
+ *   w->w_gate (SwiGLU), w->b_up, w->b_down as for the gathered decode: the full
+ *   resident matrices, w_up / w_gate [N, d], w_down NEURON-MAJOR [N, d];
+ *   w->core_idx and w->K are ignored.  union_idx / union_mask / union_count as
+ *   written by coreinfer_union_build with the same max_rows; the row count is
+ *   read on the device, so no host synchronisation is needed between the two
+ *   calls.  ws: coreinfer_ffn_decode_union_workspace_size bytes, 16-byte aligned.
+ *   Deterministic (fixed summation order).  Errors as for coreinfer_ffn_decode.
+ */
+int coreinfer_union_workspace_size(int64_t N, size_t* bytes);
+int coreinfer_union_build(const int32_t* core_idx, int64_t B, int64_t K, int64_t N, int64_t max_rows,
+                          int32_t* union_idx, uint32_t* union_mask, int32_t* union_count, void* ws,
+                          size_t ws_bytes, void* stream);
+int coreinfer_ffn_decode_union_workspace_size(int64_t B, int64_t max_rows, int64_t d, int dtype, int act,
+                                              size_t* bytes);
+int coreinfer_ffn_decode_union(const void* x, int64_t B, const ci_ffn_weights* w,
+                               const int32_t* union_idx, const uint32_t* union_mask,
+                               const int32_t* union_count, int64_t max_rows, int dtype, int act,
+                               void* y, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Dense FFN over all N neurons (Def. 1: the activation vector A(x) of every

@@ -63,6 +63,11 @@ _SIGNATURES = {
     "coreinfer_ffn_decode_workspace_size": (_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_ffn_decode": (_int, [_vp, _i64, ctypes.POINTER(ci_ffn_weights), _int, _int, _vp,
                                     _vp, _sz, _vp]),
+    "coreinfer_union_workspace_size": (_int, [_i64, ctypes.POINTER(_sz)]),
+    "coreinfer_union_build": (_int, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "coreinfer_ffn_decode_union_workspace_size": (_int, [_i64, _i64, _i64, _int, _int, ctypes.POINTER(_sz)]),
+    "coreinfer_ffn_decode_union": (_int, [_vp, _i64, ctypes.POINTER(ci_ffn_weights), _vp, _vp, _vp, _i64,
+                                          _int, _int, _vp, _vp, _sz, _vp]),
     "coreinfer_ffn_dense_workspace_size": (_int, [_i64, _i64, _i64, _int, ctypes.POINTER(_sz)]),
     "coreinfer_ffn_dense": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64,
                                    _vp, _vp, _vp, _sz, _vp]),
@@ -244,6 +249,50 @@ def ffn_decode(x: torch.Tensor, weights: ci_ffn_weights, act: str, y: Optional[t
                                      ACT_CODE[act], _ptr(y), _ptr(ws), ws.numel(), _stream(x)),
            "coreinfer_ffn_decode")
     return y if x.dim() == 2 else y.squeeze(0)
+
+
+def union_build(core_idx: torch.Tensor, N: int, max_rows: Optional[int] = None):
+    """coreinfer_union_build on core_idx [B, K] int32.  Returns (union_idx [max_rows] int32,
+    union_mask [max_rows] int32 holding the uint32 bits, union_count [1] int32), all on the device."""
+    B, K = core_idx.shape
+    if max_rows is None:
+        max_rows = max(1, min(N, B * K))
+    dev = core_idx.device
+    union_idx = torch.empty(max_rows, dtype=torch.int32, device=dev)
+    union_mask = torch.empty(max_rows, dtype=torch.int32, device=dev)
+    union_count = torch.empty(1, dtype=torch.int32, device=dev)
+    b = _sz(0)
+    _check(_lib.coreinfer_union_workspace_size(N, ctypes.byref(b)), "coreinfer_union_workspace_size")
+    ws = _workspace(b.value, core_idx)
+    _check(_lib.coreinfer_union_build(_ptr(core_idx), B, K, N, max_rows, _ptr(union_idx), _ptr(union_mask),
+                                      _ptr(union_count), _ptr(ws), ws.numel(), _stream(core_idx)),
+           "coreinfer_union_build")
+    return union_idx, union_mask, union_count
+
+
+def ffn_decode_union_workspace_size(B: int, max_rows: int, d: int, dtype: torch.dtype, act: str) -> int:
+    b = _sz(0)
+    _check(_lib.coreinfer_ffn_decode_union_workspace_size(B, max_rows, d, DTYPE_CODE[dtype], ACT_CODE[act],
+                                                          ctypes.byref(b)),
+           "coreinfer_ffn_decode_union_workspace_size")
+    return b.value
+
+
+def ffn_decode_union(x: torch.Tensor, weights: ci_ffn_weights, union_idx: torch.Tensor,
+                     union_mask: torch.Tensor, union_count: torch.Tensor, act: str,
+                     y: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """coreinfer_ffn_decode_union on x [B, d]; weights = the resident neuron-major matrices."""
+    B, d = x.shape
+    max_rows = union_idx.numel()
+    if y is None:
+        y = torch.empty_like(x)
+    if ws is None:
+        ws = _workspace(ffn_decode_union_workspace_size(B, max_rows, d, x.dtype, act), x)
+    _check(_lib.coreinfer_ffn_decode_union(_ptr(x), B, ctypes.byref(weights), _ptr(union_idx), _ptr(union_mask),
+                                           _ptr(union_count), max_rows, DTYPE_CODE[x.dtype], ACT_CODE[act],
+                                           _ptr(y), _ptr(ws), ws.numel(), _stream(x)),
+           "coreinfer_ffn_decode_union")
+    return y
 
 
 def ffn_dense_workspace_size(M: int, d: int, N: int, dtype: torch.dtype) -> int:

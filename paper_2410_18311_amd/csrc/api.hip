@@ -87,6 +87,10 @@ int coreinfer_set_param(const char* name, int value) {
   else if (!strcmp(name, "gemm_ring") && (value == 0 || value == 1)) p.gemm_ring = value;
   else if (!strcmp(name, "gemv_wgs_per_cu") && value >= 1 && value <= 32) p.gemv_wgs_per_cu = value;
   else if (!strcmp(name, "decode_skip_reduce") && (value == 0 || value == 1)) p.decode_skip_reduce = value;
+  else if (!strcmp(name, "union_depth") && (value == 8 || value == 16)) p.union_depth = value;
+  else if (!strcmp(name, "union_down_threads") && value >= 64 && value <= 512) p.union_down_threads = value;
+  else if (!strcmp(name, "union_up_wgs_per_cu") && value >= 1 && value <= 8) p.union_up_wgs_per_cu = value;
+  else if (!strcmp(name, "union_down_wgs_per_cu") && value >= 1 && value <= 16) p.union_down_wgs_per_cu = value;
   else return CI_ERR_INVALID_ARG;
   return CI_OK;
 }
@@ -226,6 +230,66 @@ int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int 
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
   return launch_ffn_decode(x, B, w, dtype, act, y, reinterpret_cast<float*>(ws), (hipStream_t)stream);
+}
+
+int coreinfer_union_workspace_size(int64_t N, size_t* bytes) {
+  if (!bytes || N < 1 || N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+  *bytes = round256((size_t)N * sizeof(uint32_t));
+  return CI_OK;
+}
+
+int coreinfer_union_build(const int32_t* core_idx, int64_t B, int64_t K, int64_t N, int64_t max_rows,
+                          int32_t* union_idx, uint32_t* union_mask, int32_t* union_count, void* ws,
+                          size_t ws_bytes, void* stream) {
+  size_t need = 0;
+  if (coreinfer_union_workspace_size(N, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (B < 1 || B > CI_MAX_UNION_SENTENCES || K < 0 || K > N) return CI_ERR_INVALID_ARG;
+  if ((K > 0 && !core_idx) || !union_idx || !union_mask || !union_count) return CI_ERR_INVALID_ARG;
+  const int64_t worst = B * K < N ? B * K : N;  // the union cannot have more rows than this
+  if (max_rows < 1 || max_rows < worst || max_rows > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(core_idx) & 3u) || (reinterpret_cast<uintptr_t>(union_idx) & 3u) ||
+      (reinterpret_cast<uintptr_t>(union_mask) & 3u) || (reinterpret_cast<uintptr_t>(union_count) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
+  return launch_union_build(core_idx, B, K, N, max_rows, union_idx, union_mask, union_count,
+                            reinterpret_cast<uint32_t*>(ws), (hipStream_t)stream);
+}
+
+int coreinfer_ffn_decode_union_workspace_size(int64_t B, int64_t max_rows, int64_t d, int dtype, int act,
+                                              size_t* bytes) {
+  if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  if (!bytes || B < 1 || B > CI_MAX_UNION_SENTENCES || max_rows < 1 || max_rows > CI_MAX_NEURONS ||
+      d < 1 || d > CI_MAX_DMODEL)
+    return CI_ERR_INVALID_ARG;
+  if (d % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
+  const int64_t chunks = union_up_chunks(d / vec_of(dtype));
+  const int64_t ndot = act == CI_ACT_SWIGLU ? 2 : 1;
+  // partial dots [chunks][ndot][max_rows][8] and partial sums [B][<= 256 slices][d], fp32
+  const size_t hp = ((size_t)chunks * ndot * (size_t)max_rows * 8 + 63) / 64 * 64;
+  *bytes = round256((hp + (size_t)B * 256 * (size_t)d) * sizeof(float)) + 256;
+  return CI_OK;
+}
+
+int coreinfer_ffn_decode_union(const void* x, int64_t B, const ci_ffn_weights* w,
+                               const int32_t* union_idx, const uint32_t* union_mask,
+                               const int32_t* union_count, int64_t max_rows, int dtype, int act,
+                               void* y, void* ws, size_t ws_bytes, void* stream) {
+  if (!w) return CI_ERR_INVALID_ARG;
+  size_t need = 0;
+  const int rc = coreinfer_ffn_decode_union_workspace_size(B, max_rows, w->d, dtype, act, &need);
+  if (rc != CI_OK) return rc;
+  if (!x || !y || !union_idx || !union_mask || !union_count) return CI_ERR_INVALID_ARG;
+  if (!w->w_up || !w->w_down || w->N < 1 || w->N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+  if ((act == CI_ACT_SWIGLU) != (w->w_gate != nullptr)) return CI_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(w->w_up) || !aligned16(w->w_gate) ||
+      !aligned16(w->w_down) || (reinterpret_cast<uintptr_t>(union_idx) & 3u) ||
+      (reinterpret_cast<uintptr_t>(union_mask) & 3u) || (reinterpret_cast<uintptr_t>(union_count) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
+  return launch_ffn_decode_union(x, B, w, union_idx, union_mask, union_count, max_rows, dtype, act, y,
+                                 reinterpret_cast<float*>(ws), (hipStream_t)stream);
 }
 
 int coreinfer_ffn_dense_workspace_size(int64_t M, int64_t d, int64_t N, int dtype, size_t* bytes) {

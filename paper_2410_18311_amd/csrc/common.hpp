@@ -120,6 +120,10 @@ struct Params {
   int reduce_cq = 8;        // column quads per reduce workgroup (4, 8, 16)
   int decode_nt_store = 1;  // non-temporal stores for the partial sums
   int decode_skip_reduce = 0;  // timing only: launch the slice kernel without the reduction
+  int union_depth = 8;            // union-batched decode: rows in flight per thread (8 or 16)
+  int union_down_threads = 128;   // threads (= 16-byte column vectors) per down-phase workgroup
+  int union_up_wgs_per_cu = 2;
+  int union_down_wgs_per_cu = 4;
 };
 Params& params();
 
@@ -145,6 +149,15 @@ int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const
 int decode_splits(int64_t B, int64_t K);
 int launch_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,
                       void* y, float* partial, hipStream_t s);
+int launch_decode_reduce(const float* partial, const void* b_down, void* y, int n_wg, int d, int B,
+                         int dtype, hipStream_t s);
+int union_up_chunks(int64_t vecs);
+int launch_union_build(const int32_t* core_idx, int64_t B, int64_t K, int64_t N, int64_t cap,
+                       int32_t* uidx, uint32_t* umask, int32_t* ucount, uint32_t* owners,
+                       hipStream_t s);
+int launch_ffn_decode_union(const void* x, int64_t B, const ci_ffn_weights* w, const int32_t* uidx,
+                            const uint32_t* umask, const int32_t* ucount, int64_t cap, int dtype,
+                            int act, void* y, float* ws, hipStream_t s);
 // h[M, N] fp32 = act(X w^T ...) and y = W h + b by row-dot GEMVs (small M).
 int launch_up_rows(const void* X, int64_t M, const void* w_up, const void* w_gate, const void* b_up,
                    int dtype, int act, int64_t d, int64_t N, float* H, float* A, hipStream_t s);

@@ -171,6 +171,55 @@ def test_next_row_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert r(F + 2, 4, F, 4, F, None) == lib.CI_ERR_BAD_LAYOUT
 
 
+def test_union_entry_points_reject_bad_arguments_without_a_gpu(lib):
+    F = FAKE
+    big = 1 << 30
+    r = lib.raw.coreinfer_union_build
+    # (core_idx, B, K, N, max_rows, union_idx, union_mask, union_count, ws, ws_bytes, stream)
+    assert r(None, 2, 8, 64, 16, F, F, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 9, 8, 64, 64, F, F, F, F, big, None) == lib.CI_ERR_INVALID_ARG      # more than 8 sentences
+    assert r(F, 0, 8, 64, 64, F, F, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 2, 80, 64, 64, F, F, F, F, big, None) == lib.CI_ERR_INVALID_ARG     # K > N
+    assert r(F, 2, 8, 64, 15, F, F, F, F, big, None) == lib.CI_ERR_INVALID_ARG      # max_rows < min(N, B*K)
+    assert r(F, 2, 8, 64, 16, None, F, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 2, 8, 64, 16, F, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F + 2, 2, 8, 64, 16, F, F, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 2, 8, 64, 16, F, F, F, None, big, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 2, 8, 64, 16, F, F, F, F, 64, None) == lib.CI_ERR_WORKSPACE
+    n = ctypes.c_size_t(0)
+    assert lib.raw.coreinfer_union_workspace_size(36864, ctypes.byref(n)) == lib.CI_OK and n.value >= 36864 * 4
+    assert lib.raw.coreinfer_union_workspace_size(0, ctypes.byref(n)) == lib.CI_ERR_INVALID_ARG
+
+    q = lib.raw.coreinfer_ffn_decode_union_workspace_size
+    assert q(8, 36864, 9216, 1, 0, ctypes.byref(n)) == lib.CI_OK
+    # partial dots [3 chunks][1][36864][8] + partial sums [8][256][9216], fp32
+    assert n.value >= (3 * 36864 * 8 + 8 * 256 * 9216) * 4
+    assert q(9, 64, 64, 1, 0, ctypes.byref(n)) == lib.CI_ERR_INVALID_ARG
+    assert q(8, 64, 60, 1, 0, ctypes.byref(n)) == lib.CI_ERR_BAD_LAYOUT
+    assert q(8, 64, 64, 7, 0, ctypes.byref(n)) == lib.CI_ERR_BAD_DTYPE
+
+    r = lib.raw.coreinfer_ffn_decode_union
+
+    def W(**kw):
+        base = dict(w_up=F, w_gate=None, b_up=None, w_down=F, b_down=None, core_idx=None, K=0, d=64, N=128)
+        base.update(kw)
+        return ctypes.byref(lib.ci_ffn_weights(**base))
+
+    # (x, B, w, union_idx, union_mask, union_count, max_rows, dtype, act, y, ws, ws_bytes, stream)
+    assert r(F, 2, None, F, F, F, 128, 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(None, 2, W(), F, F, F, 128, 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 2, W(), None, F, F, 128, 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 2, W(), F, F, None, 128, 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 9, W(), F, F, F, 128, 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 2, W(N=0), F, F, F, 128, 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 2, W(), F, F, F, 128, 1, 1, F, F, big, None) == lib.CI_ERR_INVALID_ARG   # SwiGLU without gate
+    assert r(F, 2, W(d=60), F, F, F, 128, 1, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 2, W(), F + 2, F, F, 128, 1, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 2, W(), F, F, F, 128, 4, 0, F, F, big, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, 2, W(), F, F, F, 128, 1, 0, F, None, big, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 2, W(), F, F, F, 128, 1, 0, F, F, 1024, None) == lib.CI_ERR_WORKSPACE
+
+
 def test_set_param_validation(lib):
     assert lib.raw.coreinfer_set_param(b"no_such_knob", 1) == lib.CI_ERR_INVALID_ARG
     assert lib.raw.coreinfer_set_param(b"decode_wgs_per_cu", 0) == lib.CI_ERR_INVALID_ARG

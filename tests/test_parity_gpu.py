@@ -379,7 +379,17 @@ def test_full_size_layer_gathered_eight_sentences(lib):
     x = torch.stack([wl.decode_hidden(cfg, 0, DEV, sentence=s, tokens=1)[0] for s in range(cfg.sentences)])
     desc = lib.make_weights(w["w_up"], None, w["b_up"], w["w_down"], w["b_down"], core_idx=idx)
     y = lib.ffn_decode(x, desc, "relu")
+    # the same batch through the union of the eight sets
+    uidx, umask, ucount = lib.union_build(idx, cfg.N)
+    yu = lib.ffn_decode_union(x, lib.make_weights(w["w_up"], None, w["b_up"], w["w_down"], w["b_down"]),
+                              uidx, umask, ucount, "relu")
     torch.cuda.synchronize()
+    U_ref, owners_ref = orc.union_rows([t.cpu().numpy() for t in sets], cfg.N)
+    n_rows = int(ucount.item())
+    assert n_rows == U_ref.size
+    assert uidx[:n_rows].cpu().numpy().tolist() == U_ref.tolist()
+    assert (umask[:n_rows].cpu().numpy().astype(np.int64) & 0xffffffff).tolist() == owners_ref.astype(np.int64).tolist()
+    _say(f"  union of 8 sets: {n_rows} of {cfg.N} neurons")
     for s in (0, 5):
         Sn = sets[s].cpu().numpy().astype(np.int64)
         up_rows = f64(w["w_up"][sets[s].long()])
@@ -389,6 +399,81 @@ def test_full_size_layer_gathered_eight_sentences(lib):
         y_ref = orc.ffn_relu(f64(x[s]), None, up_rows, f64(w["b_up"])[Sn], down_rows.T, f64(w["b_down"]))
         rel = assert_close_rms(y[s], y_ref, torch.float16, f"gathered sentence {s}")
         _say(f"  sentence {s}: max err / rms = {rel:.2e}")
+        rel = assert_close_rms(yu[s], y_ref, torch.float16, f"union-batched sentence {s}")
+        _say(f"  sentence {s}, union-batched: max err / rms = {rel:.2e}")
+
+
+# ------------------------------------------------ union-batched decode (next row)
+
+def _random_sets(rng, B, K, N, overlap):
+    """B index lists of length K; `overlap` in [0, 1] draws that share from a common pool."""
+    pool = rng.choice(N, size=min(N, max(K, 1)), replace=False)
+    out = []
+    for _ in range(B):
+        k_common = int(round(overlap * K))
+        a = rng.choice(pool, size=k_common, replace=False) if k_common else np.zeros(0, dtype=np.int64)
+        rest = np.setdiff1d(np.arange(N), a)
+        b = rng.choice(rest, size=K - k_common, replace=False)
+        S = np.concatenate([a, b])
+        rng.shuffle(S)
+        out.append(S)
+    return np.stack(out) if K else np.zeros((B, 0), dtype=np.int64)
+
+
+@pytest.mark.parametrize("B,K,N,overlap", [(1, 7, 40, 0.0), (3, 100, 300, 0.5), (8, 410, 1024, 0.0),
+                                           (8, 2000, 5000, 0.9), (5, 0, 64, 0.0), (2, 3000, 3000, 1.0)])
+def test_union_build_matches_oracle(lib, B, K, N, overlap):
+    _say("union build case", B, K, N, overlap)
+    S = _random_sets(np.random.default_rng(B * 31 + K), B, K, N, overlap)
+    if K >= 7:  # out-of-range entries and a duplicate are ignored / harmless
+        S[0, 1], S[B - 1, 2], S[0, 4] = -3, N + 5, S[0, 5]
+    idx = torch.from_numpy(S.astype(np.int32)).to(DEV)
+    uidx, umask, ucount = lib.union_build(idx, N)
+    torch.cuda.synchronize()
+    U_ref, owners_ref = orc.union_rows(list(S), N)
+    n_rows = int(ucount.item())
+    assert n_rows == U_ref.size
+    assert uidx[:n_rows].cpu().numpy().tolist() == U_ref.tolist()
+    assert (umask[:n_rows].cpu().numpy().astype(np.int64) & 0xffffffff).tolist() == owners_ref.astype(np.int64).tolist()
+
+
+@pytest.mark.parametrize("dt,act", [("f16", "relu"), ("bf16", "swiglu"), ("f32", "relu"), ("f32", "swiglu")])
+@pytest.mark.parametrize("d,N,K,B,overlap", [(512, 2000, 801, 4, 0.3), (9216, 1200, 480, 8, 0.0),
+                                             (4352, 900, 300, 5, 0.8), (64, 64, 64, 1, 0.0),
+                                             (1000, 700, 33, 8, 0.0), (256, 3000, 1500, 2, 1.0)])
+def test_decode_union_matches_oracle_and_gathered(lib, dt, act, d, N, K, B, overlap):
+    _say("decode union case", dt, act, d, N, K, B, overlap)
+    dtype = DTYPES[dt]
+    w = rand_weights(d, N, dtype, act, "neuron_major", seed=d + N + 1, device=DEV)
+    S = np.sort(_random_sets(np.random.default_rng(B * 100 + K + 7), B, K, N, overlap), axis=1)
+    idx = torch.from_numpy(S.astype(np.int32)).to(DEV)
+    x = torch.randn(B, d, generator=torch.Generator().manual_seed(K + 3)).to(dtype).to(DEV)
+    uidx, umask, ucount = lib.union_build(idx, N)
+    resident = lib.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"])
+    y = lib.ffn_decode_union(x, resident, uidx, umask, ucount, act)
+    y2 = lib.ffn_decode_union(x, resident, uidx, umask, ucount, act)
+    yg = lib.ffn_decode(x, lib.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"],
+                                            core_idx=idx), act)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2), "union-batched decode must be deterministic"
+    for b in range(B):
+        ref = _oracle_ffn(act, x[b], S[b], w, "neuron_major")
+        assert_close_rms(y[b], ref, dtype, f"union b={b}")
+        assert_close_rms(yg[b], ref, dtype, f"gathered b={b}")
+
+
+def test_decode_union_empty_sets_give_the_output_bias(lib):
+    d, N, B = 128, 256, 3
+    w = rand_weights(d, N, torch.float16, "relu", "neuron_major", seed=5, device=DEV)
+    idx = torch.full((B, 4), -1, dtype=torch.int32, device=DEV)   # no valid entry at all
+    uidx, umask, ucount = lib.union_build(idx, N)
+    x = torch.randn(B, d).half().to(DEV)
+    y = lib.ffn_decode_union(x, lib.make_weights(w["w_up"], None, w["b_up"], w["w_down"], w["b_down"]),
+                             uidx, umask, ucount, "relu")
+    torch.cuda.synchronize()
+    assert int(ucount.item()) == 0
+    for b in range(B):
+        assert torch.equal(y[b], w["b_down"])
 
 
 # --------------------------------- running counts, group sets, similarity (next rows)
