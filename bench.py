@@ -209,6 +209,46 @@ def main():
     dense_decode()
     dense_decode_ms = timed(dense_decode, reps=3)
 
+    # --------------------- several sentences: the same decode through the union of their core sets
+    # (a different algorithm from the gathered decode that `value` reports: every union row is read
+    # once for all its owners; reported beside it, never as `value`)
+    union = None
+    if gathered and B <= 8:
+        resident = [ci.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"]) for w in weights]
+        ubuild_ms = timed(lambda: [ci.union_build(core_idx[l], N) for l in range(L)]) / L
+        unions = [ci.union_build(core_idx[l], N) for l in range(L)]
+        u_ws = torch.empty(ci.ffn_decode_union_workspace_size(B, min(N, B * K), d, dtype, cfg.act),
+                           dtype=torch.uint8, device=dev)
+        y_union = torch.empty((L, B, d), dtype=dtype, device=dev)
+
+        def union_token_layers():
+            for l in range(L):
+                ci.ffn_decode_union(x_cur[l], resident[l], *unions[l], cfg.act, y=y_union[l], ws=u_ws)
+
+        x_cur.copy_(x_all[0])
+        union_token_layers()
+        decode_token_layers()
+        torch.cuda.synchronize()
+        rms = float(y_out.float().pow(2).mean().sqrt())
+        union_vs_gathered = float((y_union.float() - y_out.float()).abs().max()) / rms
+        ugraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(ugraph):
+            union_token_layers()
+        torch.cuda.synchronize()
+        ugraph.replay()
+        n_rep = max(1, min(T, 8))
+        union_ms = timed(ugraph.replay, reps=n_rep)
+        del ugraph
+        rows0 = int(unions[0][2].item())
+        union_bytes = rows0 * d * e * cfg.n_mat
+        union = {"tokens_per_s": B / (union_ms * 1e-3), "us_per_layer_step": union_ms * 1e3 / L,
+                 "union_rows_layer0": rows0, "algorithmic_bytes_per_layer_step": union_bytes,
+                 "gbps": union_bytes * L / (union_ms * 1e-3) / 1e9,
+                 "union_build_us_per_layer": ubuild_ms * 1e3,
+                 "max_abs_diff_vs_gathered_over_rms": union_vs_gathered,
+                 "note": "each row of the union of the sentences' core sets is read once; a different "
+                         "algorithm from the gathered decode, same result per sentence"}
+
     # ------------------------------- dominant kernel alone: HIP events around a graph of its launches
     ci.set_param("decode_skip_reduce", 1)
     try:
@@ -317,6 +357,7 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS,
                      "traffic": traffic, "bytes_per_launch": bytes_per_launch,
                      "us_per_launch": kernel_ms * 1e3},
+        "union_batched_decode": union,
         "cpu_baseline": cpu,
         "parity": parity,
     }

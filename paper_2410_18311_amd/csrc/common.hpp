@@ -121,9 +121,9 @@ struct Params {
   int decode_nt_store = 1;  // non-temporal stores for the partial sums
   int decode_skip_reduce = 0;  // timing only: launch the slice kernel without the reduction
   int union_depth = 8;            // union-batched decode: rows in flight per thread (8 or 16)
-  int union_down_threads = 128;   // threads (= 16-byte column vectors) per down-phase workgroup
-  int union_up_wgs_per_cu = 2;
-  int union_down_wgs_per_cu = 4;
+  int union_down_threads = 384;   // threads (= 16-byte column vectors) per down-phase workgroup
+  int union_up_wgs_per_cu = 1;
+  int union_down_wgs_per_cu = 2;
 };
 Params& params();
 

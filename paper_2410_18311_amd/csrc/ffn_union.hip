@@ -36,6 +36,7 @@ struct UnionArgs {
   float* hp;       // [c_up][NDOT][cap][SB]
   float* partial;  // [B][n_down][d]
   int B, d, N, cap, vecs;
+  int vc;  // up phase: 16-byte vectors of a row per column chunk
   int n_up, c_up, n_down, c_down;
 };
 
@@ -107,15 +108,46 @@ __device__ __forceinline__ void union_stage(const UnionArgs& a, int row0, int Rs
 }
 
 // ---- up phase ----------------------------------------------------------------
-// One thread owns one 16-byte column vector of its chunk and keeps the matching
-// x values of all sentences in registers.  DEPTH rows are in flight per thread;
-// every ring position issues its load (filler positions from x), so the
-// outstanding-load count is the same on every path.
-template <class T, bool SWIGLU>
-__device__ __forceinline__ uint4 union_up_issue(int pos, int Rs, int QB, const char* __restrict__ gate,
-                                                const char* __restrict__ up,
-                                                const char* __restrict__ filler, size_t rowbytes,
-                                                const int* sidx, uint32_t coff) {
+// dot of one 16-byte vector of weights with the matching 16 bytes of x, both in
+// the element type: two-element dot instructions with fp32 accumulation for the
+// 16-bit types (no conversions), plain FMAs for fp32.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+template <class D>
+__device__ __forceinline__ float dot16(const uint4& w, const uint4& x, float acc);
+template <>
+__device__ __forceinline__ float dot16<F32>(const uint4& w, const uint4& x, float acc) {
+  acc = fmaf(u2f(w.x), u2f(x.x), acc);
+  acc = fmaf(u2f(w.y), u2f(x.y), acc);
+  acc = fmaf(u2f(w.z), u2f(x.z), acc);
+  return fmaf(u2f(w.w), u2f(x.w), acc);
+}
+template <>
+__device__ __forceinline__ float dot16<F16>(const uint4& w, const uint4& x, float acc) {
+  acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w.x), __builtin_bit_cast(half2_t, x.x), acc, false);
+  acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w.y), __builtin_bit_cast(half2_t, x.y), acc, false);
+  acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w.z), __builtin_bit_cast(half2_t, x.z), acc, false);
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w.w), __builtin_bit_cast(half2_t, x.w), acc, false);
+}
+template <>
+__device__ __forceinline__ float dot16<BF16>(const uint4& w, const uint4& x, float acc) {
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x), __builtin_bit_cast(bf16x2_t, x.x), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y), __builtin_bit_cast(bf16x2_t, x.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z), __builtin_bit_cast(bf16x2_t, x.z), acc, false);
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w), __builtin_bit_cast(bf16x2_t, x.w), acc, false);
+}
+
+// One thread owns NI 16-byte column vectors of its chunk and keeps the matching
+// x values of all sentences in registers (element type, 4 registers per vector).
+// DEPTH rows are in flight per thread; every ring position issues its loads
+// (filler positions from x), so the outstanding-load count is the same on
+// every path.  One cross-lane reduction per row serves all NI vectors.
+template <class T, int NI, bool SWIGLU>
+__device__ __forceinline__ void union_up_issue(int pos, int Rs, int QB, const char* __restrict__ gate,
+                                               const char* __restrict__ up,
+                                               const char* __restrict__ filler, size_t rowbytes,
+                                               const int* sidx, const uint32_t (&coff)[NI],
+                                               uint4 (&dst)[NI]) {
   const bool valid = pos < QB;
   const bool second = SWIGLU && pos >= Rs;  // gate rows first, then up rows
   int r = second ? pos - Rs : pos;
@@ -123,13 +155,13 @@ __device__ __forceinline__ uint4 union_up_issue(int pos, int Rs, int QB, const c
   const char* base = (SWIGLU && !second) ? gate : up;
   const char* prow = base + (size_t)sidx[r] * rowbytes;
   prow = valid ? prow : filler;
-  return ld16_stream(prow + coff);
+#pragma unroll
+  for (int i = 0; i < NI; ++i) dst[i] = ld16_stream(prow + coff[i]);
 }
 
-template <class D, bool SWIGLU, int DEPTH>
+template <class D, int NI, bool SWIGLU, int DEPTH>
 __global__ __launch_bounds__(512) void union_up_kernel(UnionArgs a) {
   using T = typename D::T;
-  constexpr int VEC = D::VEC;
   constexpr int NDOT = SWIGLU ? 2 : 1;
 
   extern __shared__ float smem[];
@@ -150,19 +182,19 @@ __global__ __launch_bounds__(512) void union_up_kernel(UnionArgs a) {
   const char* gate = reinterpret_cast<const char*>(a.w_gate);
   const char* xbase = reinterpret_cast<const char*>(a.x);
 
-  const int vec = chunk * nt + tid;
-  const bool cv = vec < a.vecs;
-  // a column past the end re-reads column 0 with x = 0, so every load is unconditional
-  const uint32_t coff = cv ? (uint32_t)vec * 16u : 0u;
-
-  float xr[SB][VEC];
+  // vectors [chunk * vc, (chunk + 1) * vc) of a row belong to this chunk
+  uint32_t coff[NI];
+  uint4 xq[SB][NI];
 #pragma unroll
-  for (int t = 0; t < SB; ++t) {
-    if (t < a.B && cv) {
-      unpack<D>(ld16(xbase + (size_t)t * rowbytes + coff), xr[t]);
-    } else {
+  for (int i = 0; i < NI; ++i) {
+    const int local = i * nt + tid;
+    const int vec = chunk * a.vc + local;
+    const bool cv = local < a.vc && vec < a.vecs;
+    // a column past the end re-reads column 0 with x = 0, so every load is unconditional
+    coff[i] = cv ? (uint32_t)vec * 16u : 0u;
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) xr[t][v] = 0.f;
+    for (int t = 0; t < SB; ++t) {
+      xq[t][i] = (t < a.B && cv) ? ld16(xbase + (size_t)t * rowbytes + coff[i]) : make_uint4(0u, 0u, 0u, 0u);
     }
   }
 
@@ -174,11 +206,12 @@ __global__ __launch_bounds__(512) void union_up_kernel(UnionArgs a) {
     union_stage(a, r0 + s0, Rs, sidx, smask);
     __syncthreads();
 
-    uint4 buf[DEPTH];
-#define CI_UISSUE(pos) union_up_issue<T, SWIGLU>((pos), Rs, QB, gate, up, xbase, rowbytes, sidx, coff)
+    uint4 buf[DEPTH][NI];
+#define CI_UISSUE(pos, slot) \
+  union_up_issue<T, NI, SWIGLU>((pos), Rs, QB, gate, up, xbase, rowbytes, sidx, coff, buf[slot])
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) {
-      buf[s] = CI_UISSUE(s);
+      CI_UISSUE(s, s);
       __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -189,22 +222,20 @@ __global__ __launch_bounds__(512) void union_up_kernel(UnionArgs a) {
         int r = (SWIGLU && pos >= Rs) ? pos - Rs : pos;
         r = r > Rs - 1 ? Rs - 1 : r;
         const uint32_t m = __builtin_amdgcn_readfirstlane(pos < QB ? smask[r] : 0u);
-        float f[VEC];
-        unpack<D>(buf[s], f);
-        // refill the slot as soon as it has been consumed
-        __builtin_amdgcn_sched_barrier(0);
-        buf[s] = CI_UISSUE(pos + DEPTH);
-        __builtin_amdgcn_sched_barrier(0);
         float p[SB];
 #pragma unroll
         for (int t = 0; t < SB; ++t) {
           float sum = 0.f;
           if (m & (1u << t)) {  // uniform: only the owners' dots are computed
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) sum = fmaf(f[v], xr[t][v], sum);
+            for (int i = 0; i < NI; ++i) sum = dot16<D>(buf[s][i], xq[t][i], sum);
           }
           p[t] = sum;
         }
+        // refill the slot as soon as it has been consumed
+        __builtin_amdgcn_sched_barrier(0);
+        CI_UISSUE(pos + DEPTH, s);
+        __builtin_amdgcn_sched_barrier(0);
         halve_rows<SB, 32>(p, lane);  // lanes 8t .. 8t+7 now hold sentence t's wave sum
         if ((lane & 7) == 0 && pos < QB) red[((wave * NDOT * kSuper) + pos) * SB + (lane >> 3)] = p[0];
       }
@@ -339,27 +370,40 @@ __global__ __launch_bounds__(512) void union_down_kernel(UnionArgs a) {
   }
 }
 
-template <class D, bool SWIGLU>
-int launch_union_typed(const UnionArgs& a, int t_up, int t_down, hipStream_t s) {
+template <class D, int NI, bool SWIGLU>
+void launch_union_up(const UnionArgs& a, int t_up, hipStream_t s) {
   constexpr int NDOT = SWIGLU ? 2 : 1;
-  const size_t lds_up = (size_t)(t_up / 64) * NDOT * kSuper * SB * sizeof(float) + 2 * kSuper * sizeof(int);
-  const dim3 gu(a.n_up, a.c_up), gd(a.n_down, a.c_down);
-  if (params().union_depth == 16) {
-    hipLaunchKernelGGL((union_up_kernel<D, SWIGLU, 16>), gu, dim3(t_up), lds_up, s, a);
-    hipLaunchKernelGGL((union_down_kernel<D, SWIGLU, 16>), gd, dim3(t_down), 0, s, a);
-  } else {
-    hipLaunchKernelGGL((union_up_kernel<D, SWIGLU, 8>), gu, dim3(t_up), lds_up, s, a);
-    hipLaunchKernelGGL((union_down_kernel<D, SWIGLU, 8>), gd, dim3(t_down), 0, s, a);
+  const size_t lds = (size_t)(t_up / 64) * NDOT * kSuper * SB * sizeof(float) + 2 * kSuper * sizeof(int);
+  const dim3 g(a.n_up, a.c_up);
+  // about 16 loads in flight per thread
+  if constexpr (NI >= 3) hipLaunchKernelGGL((union_up_kernel<D, NI, SWIGLU, 4>), g, dim3(t_up), lds, s, a);
+  else if constexpr (NI == 2) hipLaunchKernelGGL((union_up_kernel<D, NI, SWIGLU, 8>), g, dim3(t_up), lds, s, a);
+  else hipLaunchKernelGGL((union_up_kernel<D, NI, SWIGLU, 16>), g, dim3(t_up), lds, s, a);
+}
+
+template <class D, bool SWIGLU>
+int launch_union_typed(const UnionArgs& a, int ni, int t_up, int t_down, hipStream_t s) {
+  switch (ni) {
+    case 1: launch_union_up<D, 1, SWIGLU>(a, t_up, s); break;
+    case 2: launch_union_up<D, 2, SWIGLU>(a, t_up, s); break;
+    case 3: launch_union_up<D, 3, SWIGLU>(a, t_up, s); break;
+    case 4: launch_union_up<D, 4, SWIGLU>(a, t_up, s); break;
+    default: return CI_ERR_UNSUPPORTED;
   }
+  const dim3 gd(a.n_down, a.c_down);
+  if (params().union_depth == 16)
+    hipLaunchKernelGGL((union_down_kernel<D, SWIGLU, 16>), gd, dim3(t_down), 0, s, a);
+  else
+    hipLaunchKernelGGL((union_down_kernel<D, SWIGLU, 8>), gd, dim3(t_down), 0, s, a);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
 
 }  // namespace
 
-// Column chunks of the up phase for a row of `vecs` 16-byte vectors (at most
-// 512 threads per workgroup); part of the workspace layout.
-int union_up_chunks(int64_t vecs) { return (int)((vecs + 511) / 512); }
+// Column chunks of the up phase for a row of `vecs` 16-byte vectors (a
+// workgroup covers at most 512 threads x 4 vectors); part of the workspace layout.
+int union_up_chunks(int64_t vecs) { return (int)((vecs + 2047) / 2048); }
 
 int launch_union_build(const int32_t* core_idx, int64_t B, int64_t K, int64_t N, int64_t cap,
                        int32_t* uidx, uint32_t* umask, int32_t* ucount, uint32_t* owners,
@@ -398,11 +442,21 @@ int launch_ffn_decode_union(const void* x, int64_t B, const ci_ffn_weights* w, c
   int cus = 256;
   if (device_info(&di) == CI_OK) cus = di.cus;
   a.c_up = union_up_chunks(a.vecs);
-  const int t_up = ((a.vecs + a.c_up - 1) / a.c_up + 63) / 64 * 64;
-  int t_down = params().union_down_threads / 64 * 64;
-  if (t_down < 64) t_down = 64;
-  if (t_down > 512) t_down = 512;
-  if (t_down > (a.vecs + 63) / 64 * 64) t_down = (a.vecs + 63) / 64 * 64;
+  a.vc = (a.vecs + a.c_up - 1) / a.c_up;
+  // vectors per thread: the choice that pads the chunk least, the larger one on ties (one
+  // cross-lane reduction per row serves all of a thread's vectors)
+  int ni = 1, t_up = 512, waste = 1 << 30;
+  for (int n = 4; n >= 1; --n) {
+    const int t = ((a.vc + n - 1) / n + 63) / 64 * 64;
+    if (t > 512) continue;
+    if (t * n - a.vc < waste) { waste = t * n - a.vc; ni = n; t_up = t; }
+  }
+  // down phase: column chunks of about union_down_threads vectors, evenly sized
+  int want = params().union_down_threads;
+  if (want < 64) want = 64;
+  if (want > 512) want = 512;
+  a.c_down = (a.vecs + want - 1) / want;
+  const int t_down = ((a.vecs + a.c_down - 1) / a.c_down + 63) / 64 * 64;
   a.c_down = (a.vecs + t_down - 1) / t_down;
   a.n_up = cus * params().union_up_wgs_per_cu / a.c_up;
   a.n_down = cus * params().union_down_wgs_per_cu / a.c_down;
@@ -420,9 +474,9 @@ int launch_ffn_decode_union(const void* x, int64_t B, const ci_ffn_weights* w, c
   int rc;
   const bool sw = act == CI_ACT_SWIGLU;
   switch (dtype) {
-    case CI_F32: rc = sw ? launch_union_typed<F32, true>(a, t_up, t_down, s) : launch_union_typed<F32, false>(a, t_up, t_down, s); break;
-    case CI_F16: rc = sw ? launch_union_typed<F16, true>(a, t_up, t_down, s) : launch_union_typed<F16, false>(a, t_up, t_down, s); break;
-    case CI_BF16: rc = sw ? launch_union_typed<BF16, true>(a, t_up, t_down, s) : launch_union_typed<BF16, false>(a, t_up, t_down, s); break;
+    case CI_F32: rc = sw ? launch_union_typed<F32, true>(a, ni, t_up, t_down, s) : launch_union_typed<F32, false>(a, ni, t_up, t_down, s); break;
+    case CI_F16: rc = sw ? launch_union_typed<F16, true>(a, ni, t_up, t_down, s) : launch_union_typed<F16, false>(a, ni, t_up, t_down, s); break;
+    case CI_BF16: rc = sw ? launch_union_typed<BF16, true>(a, ni, t_up, t_down, s) : launch_union_typed<BF16, false>(a, ni, t_up, t_down, s); break;
     default: return CI_ERR_BAD_DTYPE;
   }
   if (rc != CI_OK) return rc;
