@@ -85,6 +85,7 @@ int coreinfer_set_param(const char* name, int value) {
   else if (!strcmp(name, "select_debug") && value >= 0 && value <= 3) p.select_debug = value;
   else if (!strcmp(name, "select_wgs_per_cu") && value >= 1 && value <= 8) p.select_wgs_per_cu = value;
   else if (!strcmp(name, "gemm_ring") && (value == 0 || value == 1)) p.gemm_ring = value;
+  else if (!strcmp(name, "gemm_big") && value >= 0 && value <= 2) p.gemm_big = value;
   else if (!strcmp(name, "gemv_wgs_per_cu") && value >= 1 && value <= 32) p.gemv_wgs_per_cu = value;
   else if (!strcmp(name, "decode_skip_reduce") && (value == 0 || value == 1)) p.decode_skip_reduce = value;
   else if (!strcmp(name, "union_depth") && (value == 8 || value == 16)) p.union_depth = value;
@@ -302,7 +303,7 @@ int coreinfer_ffn_dense_workspace_size(int64_t M, int64_t d, int64_t N, int dtyp
   if (M <= 4) {
     b += round256((size_t)M * (size_t)(N < kMaxSplits ? N : kMaxSplits) * (size_t)d * sizeof(float));
   } else {
-    const int splits = gemm_down_splits(M, d, N, dtype);  // split-K partial products of Y
+    const int splits = gemm_down_splits_max(M, d, N, dtype);  // split-K partial products of Y
     if (splits > 1) b += round256((size_t)splits * (size_t)M * (size_t)d * sizeof(float));
   }
   *bytes = b + 256;

@@ -117,6 +117,7 @@ struct Params {
   int select_debug = 0;
   int gemv_wgs_per_cu = 4;
   int gemm_ring = 1;         // register-ring GEMM kernel where it applies
+  int gemm_big = 1;          // 256 x 256 tiles: 0 never, 1 when there are enough of them, 2 whenever the shape divides
   int reduce_cq = 8;        // column quads per reduce workgroup (4, 8, 16)
   int decode_nt_store = 1;  // non-temporal stores for the partial sums
   int decode_skip_reduce = 0;  // timing only: launch the slice kernel without the reduction
@@ -166,6 +167,7 @@ int launch_down_rows(const float* H, int64_t M, const void* w_down, const void* 
 int launch_gemm_up(const void* X, int64_t M, const void* w_up, const void* w_gate, const void* b_up,
                    int dtype, int act, int64_t d, int64_t N, void* H, float* A, hipStream_t s);
 int gemm_down_splits(int64_t M, int64_t d, int64_t N, int dtype);
+int gemm_down_splits_max(int64_t M, int64_t d, int64_t N, int dtype);  // what the workspace is sized for
 int launch_gemm_down(const void* H, int64_t M, const void* w_down, const void* b_down,
                      int down_layout, int dtype, int64_t d, int64_t N, void* Y, float* partial,
                      hipStream_t s);

@@ -302,38 +302,52 @@ __global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
     CI_GEMM_ISSUE(r, r);
     __builtin_amdgcn_sched_barrier(0);  // oldest tile first: the waits below count on this order
   }
+  // tile 0: registers -> LDS stage 0, slot 0 refilled with tile RD
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    *reinterpret_cast<uint4*>(smem + lds_off[i]) = ra[0][i];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) *reinterpret_cast<uint4*>(smem + TILE * (1 + q) + lds_off[i]) = rb[0][q][i];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  CI_GEMM_ISSUE(0, RD);
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
 
+  // Software pipeline: while tile kt is multiplied out of one LDS stage, tile kt + 1 moves from its
+  // register slot into the other stage and the slot is refilled with tile kt + 1 + RD -- one
+  // quarter of the stores and loads per MFMA k-step, so that the memory pipeline, the LDS and the
+  // matrix cores work at the same time instead of in turn.
   for (int kt0 = 0; kt0 < nk; kt0 += RD) {
 #pragma unroll
     for (int r = 0; r < RD; ++r) {
       const int kt = kt0 + r;
-      T* sA = smem + (kt & 1) * STAGE;
-      // tile kt: registers -> LDS (this buffer was last read two iterations ago, before the
-      // previous barrier), then the slot is refilled with tile kt + RD
+      constexpr int kNextSlotOf[3] = {1 % RD, 2 % RD, 0};
+      const int rn = kNextSlotOf[r];  // slot of tile kt + 1
+      const T* sA = smem + (kt & 1) * STAGE;
+      T* sN = smem + ((kt + 1) & 1) * STAGE;  // last read while tile kt - 1 was multiplied, before the previous barrier
+      const int kk_next = min(kt + 1 + RD, nk - 1) * BK;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<uint4*>(sA + lds_off[i]) = ra[r][i];
+      for (int s = 0; s < BK / 16; ++s) {
+        const int koff = s * 16 + (lane >> 5) * 8;
+        uint4 fa[2], fb[NB][2];
 #pragma unroll
-        for (int q = 0; q < NB; ++q) *reinterpret_cast<uint4*>(sA + TILE * (1 + q) + lds_off[i]) = rb[r][q][i];
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      CI_GEMM_ISSUE(r, kt + RD);
-      __builtin_amdgcn_sched_barrier(0);
-      __syncthreads();
-      if (kt < nk) {  // padding iterations (nk not a multiple of RD) skip the arithmetic only
+        for (int i = 0; i < 2; ++i)
+          fa[i] = *reinterpret_cast<const uint4*>(sA + (wm * 64 + i * 32 + (lane & 31)) * LDK + koff);
 #pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-          const int koff = s * 16 + (lane >> 5) * 8;
-          uint4 fa[2], fb[NB][2];
+        for (int q = 0; q < NB; ++q)
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
-            fa[i] = *reinterpret_cast<const uint4*>(sA + (wm * 64 + i * 32 + (lane & 31)) * LDK + koff);
+          for (int j = 0; j < 2; ++j)
+            fb[q][j] = *reinterpret_cast<const uint4*>(sA + TILE * (1 + q) +
+                                                       (wn * 64 + j * 32 + (lane & 31)) * LDK + koff);
+        // quarter s of tile kt + 1: registers -> LDS, then the registers are refilled
+        *reinterpret_cast<uint4*>(sN + lds_off[s]) = ra[rn][s];
 #pragma unroll
-          for (int q = 0; q < NB; ++q)
+        for (int q = 0; q < NB; ++q) *reinterpret_cast<uint4*>(sN + TILE * (1 + q) + lds_off[s]) = rb[rn][q][s];
+        ra[rn][s] = ld16(pa[s] + kk_next);
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-              fb[q][j] = *reinterpret_cast<const uint4*>(sA + TILE * (1 + q) +
-                                                         (wn * 64 + j * 32 + (lane & 31)) * LDK + koff);
+        for (int q = 0; q < NB; ++q) rb[rn][q][s] = ld16(pb[q][s] + kk_next);
+        if (kt < nk) {  // padding iterations (nk not a multiple of RD) skip the arithmetic only
 #pragma unroll
           for (int q = 0; q < NB; ++q)
 #pragma unroll
@@ -341,12 +355,203 @@ __global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
 #pragma unroll
               for (int j = 0; j < 2; ++j) acc[q][i][j] = mfma32<D>(fa[i], fb[q][j], acc[q][i][j]);
         }
+        __builtin_amdgcn_sched_barrier(0);  // keeps the quarters (and with them the load order) apart
       }
+      __syncthreads();
     }
   }
 #undef CI_GEMM_ISSUE
 
   gemm_epilogue<D, EPI>(g, acc, m0, n0, wm, wn, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Large-tile kernel for shapes that divide evenly: 256 x 256 outputs per
+// workgroup (SwiGLU: 256 rows x 128 gate + the same 128 up columns), eight waves
+// of 128 x 64 with 8 accumulator tiles each (two waves per SIMD: a single wave
+// does not overlap its LDS fragment reads with its own MFMAs).  A compute unit can keep only a
+// limited number of cache lines in flight, which caps what it can pull from L2
+// at roughly 20-25 bytes per clock; a 128 x 128 tile needs 64 bytes per clock to
+// keep its matrix cores busy, a 256 x 256 tile 32.  Two k-tiles ahead live in
+// registers (an L2 miss takes longer than one k-tile of MFMAs); a third of the next one moves to the other LDS stage (and is re-requested
+// for the tile after) between the MFMAs of each k-step; the one barrier per
+// k-tile sits before the last k-step, whose MFMAs cover the first fragment reads
+// of the next tile.
+constexpr int GM = 256;
+constexpr int kBigMinWorkgroups = 160;  // below this the 128 x 128 kernel fills the chip better
+
+template <class D, int EPI>
+__device__ __forceinline__ void big_store_block(const GemmArgs& g, const f32x16& c0, const f32x16& c1,
+                                                int row0, int col, int lane) {
+  using T = typename D::T;
+  if (g.partial) {
+    float* part = g.partial + (size_t)blockIdx.y * g.M * g.Nn;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = row0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      part[(size_t)row * g.Nn + col] = c0[v];
+    }
+    return;
+  }
+  const T* bias = reinterpret_cast<const T*>(g.bias);
+  const float bv = bias ? to_float<D>(bias[col]) : 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int row = row0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    float h, score;
+    if (EPI == EPI_SWIGLU) {
+      h = silu(c0[v]) * c1[v];
+      score = fabsf(h);
+    } else if (EPI == EPI_RELU) {
+      h = fmaxf(c0[v] + bv, 0.f);
+      score = h;
+    } else {
+      h = c0[v] + bv;
+      score = h;
+    }
+    const size_t o = (size_t)row * g.ldo + col;
+    if (g.out_f) g.out_f[o] = score;
+    if (g.out_e) reinterpret_cast<T*>(g.out_e)[o] = from_float<D>(h);
+  }
+}
+
+template <class D, int EPI>
+__global__ __launch_bounds__(512) void gemm_mfma_big_kernel(GemmArgs g) {
+  using T = typename D::T;
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  constexpr int BNO = DUAL ? 128 : 256;  // output columns per workgroup
+  constexpr int TILE = GM * LDK;         // one operand tile in LDS (elements)
+  constexpr int STAGE = 2 * TILE;        // A rows, then 256 B rows (SwiGLU: 128 gate, 128 up)
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* smem = reinterpret_cast<T*>(smem_raw);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;  // 2 x 4 waves of 128 x 64 outputs
+  const int tiles_m = g.M / GM;
+  const int t = xcd_swizzle(blockIdx.x, gridDim.x);
+  const int m0 = (t % tiles_m) * GM, n0 = (t / tiles_m) * BNO;
+  const int k_begin = blockIdx.y * g.k_chunk;
+  const int k_end = min(g.Kk, k_begin + g.k_chunk);
+  const int nk = (k_end - k_begin) / BK;
+
+  // staging: 8 16-byte pieces per thread and k-tile; piece i < 4 is A row srow + 64 i, piece
+  // 4 + j is row srow + 64 j of the 256-row B image.  Uniform bases + 32-bit per-thread byte
+  // offsets (an operand spans far less than 4 GB)
+  const int srow = tid >> 3, kc = (tid & 7) * 8;
+  const char* Ab = reinterpret_cast<const char*>(g.A) + ((size_t)m0 * g.lda + k_begin) * sizeof(T);
+  const char* B0b = reinterpret_cast<const char*>(g.B0) + ((size_t)n0 * g.ldb + k_begin) * sizeof(T);
+  const char* B1b = DUAL ? reinterpret_cast<const char*>(g.B1) + ((size_t)n0 * g.ldb + k_begin) * sizeof(T) : B0b;
+  const uint32_t offA = (uint32_t)(((size_t)srow * g.lda + kc) * sizeof(T));
+  const uint32_t offB = (uint32_t)(((size_t)srow * g.ldb + kc) * sizeof(T));
+  const uint32_t sa = (uint32_t)(64 * g.lda * sizeof(T)), sb = (uint32_t)(64 * g.ldb * sizeof(T));
+  const int soff = srow * LDK + kc;
+
+  constexpr int RD = 1;  // k-tiles held in registers ahead of the one being multiplied (2 does not fit 128 VGPRs)
+  uint4 r[RD][8];
+#define CI_BIG_ISSUE(slot, i, kk)                                                                  \
+  do {                                                                                             \
+    const uint32_t kb_ = (uint32_t)(kk) * (uint32_t)sizeof(T);                                     \
+    if ((i) < 4) r[slot][i] = ld16(Ab + (offA + (uint32_t)(i) * sa + kb_));                          \
+    else if (!DUAL || (i) < 6) r[slot][i] = ld16(B0b + (offB + (uint32_t)((i) - 4) * sb + kb_));     \
+    else r[slot][i] = ld16(B1b + (offB + (uint32_t)((i) - 6) * sb + kb_));                           \
+  } while (0)
+#define CI_BIG_STORE(slot, i, base) \
+  *reinterpret_cast<uint4*>((base) + ((i) < 4 ? 0 : TILE) + soff + 64 * ((i) & 3) * LDK) = r[slot][i]
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // fragment rows of this wave: A rows wm*128 + 32 i; B image rows wn*64 + 32 j, or for SwiGLU the
+  // gate rows wn*32 (j = 0) and the up rows 128 + wn*32 (j = 1) of the same output columns
+  const int l31 = lane & 31, khalf = (lane >> 5) * 8;
+  const int brow0 = DUAL ? wn * 32 + l31 : wn * 64 + l31;
+  const int brow1 = DUAL ? 128 + wn * 32 + l31 : wn * 64 + 32 + l31;
+  uint4 fa[2][4], fb[2][2];
+#define CI_BIG_FRAGS(buf, base, s)                                                                 \
+  do {                                                                                             \
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                               \
+      fa[buf][i_] = *reinterpret_cast<const uint4*>((base) + (wm * 128 + i_ * 32 + l31) * LDK + (s) * 16 + khalf); \
+    fb[buf][0] = *reinterpret_cast<const uint4*>((base) + TILE + brow0 * LDK + (s) * 16 + khalf);  \
+    fb[buf][1] = *reinterpret_cast<const uint4*>((base) + TILE + brow1 * LDK + (s) * 16 + khalf);  \
+  } while (0)
+
+  // prologue: tiles 0 .. RD-1 requested, tile 0 -> LDS stage 0, its slot re-requested with tile RD
+#pragma unroll
+  for (int q = 0; q < RD; ++q) {
+    const int kkq = min(q, nk - 1) * BK;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) CI_BIG_ISSUE(q, i, kkq);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) CI_BIG_STORE(0, i, smem);
+  __builtin_amdgcn_sched_barrier(0);
+  {
+    const int kkq = min(RD, nk - 1) * BK;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) CI_BIG_ISSUE(0, i, kkq);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
+  CI_BIG_FRAGS(0, smem, 0);
+
+  for (int kt0 = 0; kt0 < nk; kt0 += 2) {
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int kt = kt0 + par;              // stage par holds tile kt
+      constexpr int kNext[2] = {1 % RD, 0};
+      const int slot = kNext[par];           // slot of tile kt + 1 (RD = 2: its parity; RD = 1: slot 0)
+      const T* sA = smem + par * STAGE;
+      T* sN = smem + (1 - par) * STAGE;
+      const int kk_next = min(kt + 1 + RD, nk - 1) * BK;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (s == 3) {
+          // every wave has read all of this tile's fragments and written its share of the next tile
+          __syncthreads();
+          CI_BIG_FRAGS(0, sN, 0);
+        } else {
+          CI_BIG_FRAGS((s + 1) & 1, sA, s + 1);
+          // a third of tile kt + 1: registers -> the other stage, then re-requested with tile kt + 1 + RD
+          constexpr int lo[4] = {0, 3, 6, 8};
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            if (i >= lo[s] && i < lo[s + 1]) {
+              CI_BIG_STORE(slot, i, sN);
+              CI_BIG_ISSUE(slot, i, kk_next);
+            }
+          }
+        }
+        if (kt < nk) {  // the padding iteration of an odd tile count skips the arithmetic only
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<D>(fa[s & 1][i], fb[s & 1][j], acc[i][j]);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keeps the k-steps (and with them the load order) apart
+      }
+    }
+  }
+#undef CI_BIG_ISSUE
+#undef CI_BIG_STORE
+#undef CI_BIG_FRAGS
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row0 = m0 + wm * 128 + i * 32;
+    if (DUAL) {
+      big_store_block<D, EPI>(g, acc[i][0], acc[i][1], row0, n0 + wn * 32 + l31, lane);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        big_store_block<D, EPI>(g, acc[i][j], acc[i][j], row0, n0 + wn * 64 + j * 32 + l31, lane);
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -484,7 +689,21 @@ int launch_mfma(const GemmArgs& g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.Nn + BN - 1) / BN);
   const int splits = g.partial ? (g.Kk + g.k_chunk - 1) / g.k_chunk : 1;
   const bool ring = !BNN && g.Kk % BK == 0 && g.k_chunk % BK == 0 && params().gemm_ring;
-  if (ring) {
+  constexpr int BNO = (EPI == EPI_SWIGLU) ? 128 : 256;
+  const int big_tiles = (g.M / GM) * (g.Nn / BNO);
+  const bool big = ring && g.M % GM == 0 && g.Nn % BNO == 0 && g.Kk / BK >= 2 &&
+                   (params().gemm_big == 2 || (params().gemm_big == 1 && big_tiles * splits >= kBigMinWorkgroups));
+  if (big) {
+    const size_t lds_big = (size_t)2 * 2 * GM * LDK * sizeof(typename D::T);
+    static bool big_attr_done = false;
+    if (!big_attr_done) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_big_kernel<D, EPI>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_big) != hipSuccess)
+        return CI_ERR_HIP;
+      big_attr_done = true;
+    }
+    hipLaunchKernelGGL((gemm_mfma_big_kernel<D, EPI>), dim3(big_tiles, splits), dim3(512), lds_big, s, g);
+  } else if (ring) {
     static bool ring_attr_done = false;
     if (lds > 48 * 1024 && !ring_attr_done) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_ring_kernel<D, EPI>),
@@ -553,16 +772,41 @@ int launch_gemm_up(const void* X, int64_t M, const void* w_up, const void* w_gat
 }
 
 // Number of k splits of the down projection: few output tiles (small M) would
-// leave most CUs idle, so the long reduction over N is cut into chunks.  A
-// pure function of the shape, so the workspace query can use it.
-int gemm_down_splits(int64_t M, int64_t d, int64_t N, int dtype) {
-  if (dtype == CI_F32) return 1;
+// leave most CUs idle, so the long reduction over N is cut into chunks.  Pure
+// functions of the shape; the workspace is sized for the larger of the two.
+static int down_splits_small(int64_t M, int64_t d, int64_t N) {
   const int64_t tiles = ((M + BM - 1) / BM) * ((d + BN - 1) / BN);
   int64_t s = (512 + tiles - 1) / tiles;
   const int64_t max_by_k = (N + 4 * BK - 1) / (4 * BK);  // at least four k tiles per split
   if (s > max_by_k) s = max_by_k;
   if (s > 8) s = 8;
   return s < 1 ? 1 : (int)s;
+}
+// Large tiles: as many k splits as bring the grid to about one workgroup per CU;
+// 0 when the large-tile kernel does not apply.
+static int down_splits_big(int64_t M, int64_t d, int64_t N) {
+  if (M % GM != 0 || d % 256 != 0 || N % BK != 0) return 0;
+  const int64_t tb = (M / GM) * (d / 256);
+  if (tb >= kBigMinWorkgroups) return 1;
+  if (tb < 32) return 0;
+  int64_t sb = (256 + tb / 2) / tb;
+  const int64_t max_k = N / (8 * BK);  // at least eight k tiles per split
+  if (sb > max_k) sb = max_k;
+  if (sb > 8) sb = 8;
+  return (sb >= 1 && tb * sb >= kBigMinWorkgroups) ? (int)sb : 0;
+}
+int gemm_down_splits(int64_t M, int64_t d, int64_t N, int dtype) {
+  if (dtype == CI_F32) return 1;
+  if (params().gemm_big == 1) {
+    const int sb = down_splits_big(M, d, N);
+    if (sb > 0) return sb;
+  }
+  return down_splits_small(M, d, N);
+}
+int gemm_down_splits_max(int64_t M, int64_t d, int64_t N, int dtype) {
+  if (dtype == CI_F32) return 1;
+  const int a = down_splits_small(M, d, N), b = down_splits_big(M, d, N);
+  return a > b ? a : b;
 }
 
 int launch_gemm_down(const void* H, int64_t M, const void* w_down, const void* b_down,

@@ -246,6 +246,32 @@ def test_dense_matches_oracle(lib, dt, act, layout, M, d, N):
     assert torch.equal(A, A2)
 
 
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("act", ["relu", "swiglu"])
+@pytest.mark.parametrize("M,d,N", [(256, 128, 256), (512, 1024, 768), (256, 576, 1280), (768, 256, 512)])
+def test_dense_large_tile_kernel_matches_oracle(lib, dt, act, M, d, N):
+    """The 256 x 256 tile kernel, forced for shapes it divides (normally chosen only for large
+    grids): up projection with both epilogues and the down projection, split over k or not."""
+    _say("dense large-tile case", dt, act, M, d, N)
+    dtype = DTYPES[dt]
+    w = rand_weights(d, N, dtype, act, "out_major", seed=M + d + N + 9, device=DEV)
+    X = torch.randn(M, d, generator=torch.Generator().manual_seed(M + 1)).to(dtype).to(DEV)
+    lib.set_param("gemm_big", 2)
+    try:
+        Y, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], "out_major", act,
+                             want_y=True, want_a=True)
+        torch.cuda.synchronize()
+    finally:
+        lib.set_param("gemm_big", 1)
+    if act == "relu":
+        A_ref = orc.score_relu(f64(X), f64(w["w_up"]), f64(w["b_up"]))
+    else:
+        A_ref = orc.score_swiglu(f64(X), f64(w["w_gate"]), f64(w["w_up"]))
+    rms = np.sqrt(np.mean(A_ref ** 2))
+    assert np.max(np.abs(f64(A) - A_ref)) <= 1e-4 * rms
+    assert_close_rms(Y, _oracle_ffn(act, X, None, w, "out_major"), dtype, "dense Y, large tiles")
+
+
 # ------------------------------------------------------------- whole small path
 
 def test_tiny_fp32_configuration_end_to_end(lib):
