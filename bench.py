@@ -87,15 +87,18 @@ def main():
 
     # ------------------------------------------------------------------ inputs (untimed)
     weights = [wl.layer_weights(cfg, l, dev) for l in range(L)]
-    X = [[wl.prefill_hidden(cfg, l, dev, sentence=s) for s in range(B)] for l in range(L)]
+    # the sentences of a batch share the layer's weights: their prompts go through the dense prefill
+    # FFN as one [B * M, d] matrix (one pass over the weights), selection then runs per sentence
+    X = [torch.cat([wl.prefill_hidden(cfg, l, dev, sentence=s) for s in range(B)], dim=0).contiguous()
+         for l in range(L)]
     # decode inputs: x_all[t] is [L, B, d], one fresh hidden state per layer, sentence and step
     x_all = torch.stack([torch.stack([wl.decode_hidden(cfg, l, dev, sentence=s) for s in range(B)], dim=1)
                          for l in range(L)], dim=1).contiguous()          # [T, L, B, d]
     x_cur = torch.empty((L, B, d), dtype=dtype, device=dev)
     y_out = torch.empty((L, B, d), dtype=dtype, device=dev)
-    A_buf = torch.empty((M, N), dtype=torch.float32, device=dev)
-    Y_buf = torch.empty((M, d), dtype=dtype, device=dev)
-    dense_ws = torch.empty(ci.ffn_dense_workspace_size(M, d, N, dtype), dtype=torch.uint8, device=dev)
+    A_buf = torch.empty((B * M, N), dtype=torch.float32, device=dev)
+    Y_buf = torch.empty((B * M, d), dtype=dtype, device=dev)
+    dense_ws = torch.empty(ci.ffn_dense_workspace_size(B * M, d, N, dtype), dtype=torch.uint8, device=dev)
     sel_ws = torch.empty(ci.select_workspace_size(M, N), dtype=torch.uint8, device=dev)
     counts = torch.empty(N, dtype=torch.int32, device=dev)
     core_idx = torch.empty((L, B, K), dtype=torch.int32, device=dev)
@@ -115,10 +118,10 @@ def main():
 
     def prefill_layer(l):
         w = weights[l]
+        ci.ffn_dense(X[l], w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], cfg.down_layout,
+                     cfg.act, want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
         for s in range(B):
-            ci.ffn_dense(X[l][s], w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], cfg.down_layout,
-                         cfg.act, want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
-            ci.select(A_buf, cfg.alpha, beta, core_idx=core_idx[l, s], counts=counts, ws=sel_ws)
+            ci.select(A_buf[s * M:(s + 1) * M], cfg.alpha, beta, core_idx=core_idx[l, s], counts=counts, ws=sel_ws)
         if not gathered:
             ci.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act,
                        core_idx[l, 0], out=cbuf[l])
@@ -185,12 +188,12 @@ def main():
         return a.elapsed_time(b) / reps
 
     w0 = weights[0]
-    dense_ms = timed(lambda: [ci.ffn_dense(X[l][0], weights[l]["w_up"], weights[l]["w_gate"], weights[l]["b_up"],
+    dense_ms = timed(lambda: [ci.ffn_dense(X[l], weights[l]["w_up"], weights[l]["w_gate"], weights[l]["b_up"],
                                            weights[l]["w_down"], weights[l]["b_down"], cfg.down_layout, cfg.act,
                                            want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
-                              for l in range(L)]) / L
+                              for l in range(L)]) / L   # per layer, all B sentences together
     scratch_idx = torch.empty(K, dtype=torch.int32, device=dev)   # keeps the real core sets intact
-    select_ms = timed(lambda: [ci.select(A_buf, cfg.alpha, beta, core_idx=scratch_idx, counts=counts, ws=sel_ws)
+    select_ms = timed(lambda: [ci.select(A_buf[:M], cfg.alpha, beta, core_idx=scratch_idx, counts=counts, ws=sel_ws)
                                for l in range(L)]) / L
     compact_ms = None
     if not gathered:
@@ -283,10 +286,10 @@ def main():
             threads = os.cpu_count() or 1
         f64 = lambda t: None if t is None else t.detach().cpu().to(torch.float64).numpy()
         # fresh prefill of layer 0, sentence 0 on the GPU, its activations handed to the oracle
-        ci.ffn_dense(X[0][0], w0["w_up"], w0["w_gate"], w0["b_up"], w0["w_down"], w0["b_down"], cfg.down_layout,
+        ci.ffn_dense(X[0], w0["w_up"], w0["w_gate"], w0["b_up"], w0["w_down"], w0["b_down"], cfg.down_layout,
                      cfg.act, want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
         torch.cuda.synchronize()
-        A_host = A_buf.cpu().numpy()
+        A_host = A_buf[:M].cpu().numpy()
         ts = time.perf_counter()
         S_ref, _ = orc.select(A_host, cfg.alpha, beta)
         select_cpu_ms = (time.perf_counter() - ts) * 1e3
@@ -350,8 +353,8 @@ def main():
         "select_us_per_layer": select_ms * 1e3,
         "compact_us_per_layer": None if compact_ms is None else compact_ms * 1e3,
         "dense_prefill_ms_per_layer": dense_ms,
-        "dense_prefill_tflops": 2.0 * M * d * N * n_mat / (dense_ms * 1e-3) / 1e12,
-        "dense_prefill_mfma_frac": 2.0 * M * d * N * n_mat / (dense_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype],
+        "dense_prefill_tflops": 2.0 * B * M * d * N * n_mat / (dense_ms * 1e-3) / 1e12,
+        "dense_prefill_mfma_frac": 2.0 * B * M * d * N * n_mat / (dense_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype],
         "dense_decode_tokens_per_s": B / (dense_decode_ms * 1e-3),
         "roofline": {"kernel": "ffn_decode_kernel", "bound": "hbm", "achieved": achieved_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS,

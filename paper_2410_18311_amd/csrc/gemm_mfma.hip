@@ -378,6 +378,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
 // k-tile sits before the last k-step, whose MFMAs cover the first fragment reads
 // of the next tile.
 constexpr int GM = 256;
+constexpr int LDN = 256 + 32;  // LDS row pitch of a k-major B tile (576 bytes: rows alternate bank halves)
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 constexpr int kBigMinWorkgroups = 160;  // below this the 128 x 128 kernel fills the chip better
 
 template <class D, int EPI>
@@ -415,7 +419,7 @@ __device__ __forceinline__ void big_store_block(const GemmArgs& g, const f32x16&
   }
 }
 
-template <class D, int EPI>
+template <class D, int EPI, bool BNN>
 __global__ __launch_bounds__(512) void gemm_mfma_big_kernel(GemmArgs g) {
   using T = typename D::T;
   constexpr bool DUAL = (EPI == EPI_SWIGLU);
@@ -439,24 +443,38 @@ __global__ __launch_bounds__(512) void gemm_mfma_big_kernel(GemmArgs g) {
   // offsets (an operand spans far less than 4 GB)
   const int srow = tid >> 3, kc = (tid & 7) * 8;
   const char* Ab = reinterpret_cast<const char*>(g.A) + ((size_t)m0 * g.lda + k_begin) * sizeof(T);
-  const char* B0b = reinterpret_cast<const char*>(g.B0) + ((size_t)n0 * g.ldb + k_begin) * sizeof(T);
+  // B given k-major ([Kk, Nn], a neuron-major down matrix): its tile is staged as it lies in
+  // memory, [64 k][256 n] with row pitch LDN, piece j of a thread = k row tid/32 + 16 j, columns
+  // 8 (tid % 32) .. + 8; the fragments then come out of LDS through transposing reads.
+  static_assert(!(BNN && DUAL), "k-major B is only needed for the down projection");
+  const char* B0b = BNN ? reinterpret_cast<const char*>(g.B0) + ((size_t)k_begin * g.ldb + n0) * sizeof(T)
+                        : reinterpret_cast<const char*>(g.B0) + ((size_t)n0 * g.ldb + k_begin) * sizeof(T);
   const char* B1b = DUAL ? reinterpret_cast<const char*>(g.B1) + ((size_t)n0 * g.ldb + k_begin) * sizeof(T) : B0b;
   const uint32_t offA = (uint32_t)(((size_t)srow * g.lda + kc) * sizeof(T));
-  const uint32_t offB = (uint32_t)(((size_t)srow * g.ldb + kc) * sizeof(T));
-  const uint32_t sa = (uint32_t)(64 * g.lda * sizeof(T)), sb = (uint32_t)(64 * g.ldb * sizeof(T));
+  const uint32_t offB = BNN ? (uint32_t)(((size_t)(tid >> 5) * g.ldb + (tid & 31) * 8) * sizeof(T))
+                            : (uint32_t)(((size_t)srow * g.ldb + kc) * sizeof(T));
+  const uint32_t sa = (uint32_t)(64 * g.lda * sizeof(T));
+  const uint32_t sb = (uint32_t)((BNN ? 16 : 64) * g.ldb * sizeof(T));
+  const uint32_t kstepB = BNN ? (uint32_t)(g.ldb * sizeof(T)) : (uint32_t)sizeof(T);  // bytes per unit of k
   const int soff = srow * LDK + kc;
+  const int soffB = BNN ? (tid >> 5) * LDN + (tid & 31) * 8 : soff;
 
   constexpr int RD = 1;  // k-tiles held in registers ahead of the one being multiplied (2 does not fit 128 VGPRs)
   uint4 r[RD][8];
 #define CI_BIG_ISSUE(slot, i, kk)                                                                  \
   do {                                                                                             \
     const uint32_t kb_ = (uint32_t)(kk) * (uint32_t)sizeof(T);                                     \
+    const uint32_t kbB_ = (uint32_t)(kk) * kstepB;                                                 \
     if ((i) < 4) r[slot][i] = ld16(Ab + (offA + (uint32_t)(i) * sa + kb_));                          \
-    else if (!DUAL || (i) < 6) r[slot][i] = ld16(B0b + (offB + (uint32_t)((i) - 4) * sb + kb_));     \
-    else r[slot][i] = ld16(B1b + (offB + (uint32_t)((i) - 6) * sb + kb_));                           \
+    else if (!DUAL || (i) < 6) r[slot][i] = ld16(B0b + (offB + (uint32_t)((i) - 4) * sb + kbB_));    \
+    else r[slot][i] = ld16(B1b + (offB + (uint32_t)((i) - 6) * sb + kbB_));                          \
   } while (0)
-#define CI_BIG_STORE(slot, i, base) \
-  *reinterpret_cast<uint4*>((base) + ((i) < 4 ? 0 : TILE) + soff + 64 * ((i) & 3) * LDK) = r[slot][i]
+#define CI_BIG_STORE(slot, i, base)                                                                \
+  do {                                                                                             \
+    if ((i) < 4) *reinterpret_cast<uint4*>((base) + soff + 64 * (i) * LDK) = r[slot][i];             \
+    else if (BNN) *reinterpret_cast<uint4*>((base) + TILE + soffB + 16 * ((i) - 4) * LDN) = r[slot][i]; \
+    else *reinterpret_cast<uint4*>((base) + TILE + soffB + 64 * ((i) - 4) * LDK) = r[slot][i];        \
+  } while (0)
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -471,13 +489,30 @@ __global__ __launch_bounds__(512) void gemm_mfma_big_kernel(GemmArgs g) {
   const int l31 = lane & 31, khalf = (lane >> 5) * 8;
   const int brow0 = DUAL ? wn * 32 + l31 : wn * 64 + l31;
   const int brow1 = DUAL ? 128 + wn * 32 + l31 : wn * 64 + 32 + l31;
+  // k-major B: a transposing 64-bit LDS read hands lane 4a + b of a 16-lane group element b of the
+  // 8-byte pieces that lanes a, a + 4, a + 8, a + 12 of the group point at.  With lane s of a group
+  // pointing at k row s / 4, columns 4 (s % 4) .. + 4, lane L of the group receives four consecutive
+  // k of column L: two such reads give the eight k of one MFMA operand (k chunk lane / 32, column
+  // lane % 32).
+  const int trow = 8 * (lane >> 5) + ((lane & 15) >> 2);
+  const int tcol = wn * 64 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   uint4 fa[2][4], fb[2][2];
 #define CI_BIG_FRAGS(buf, base, s)                                                                 \
   do {                                                                                             \
     _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                               \
       fa[buf][i_] = *reinterpret_cast<const uint4*>((base) + (wm * 128 + i_ * 32 + l31) * LDK + (s) * 16 + khalf); \
-    fb[buf][0] = *reinterpret_cast<const uint4*>((base) + TILE + brow0 * LDK + (s) * 16 + khalf);  \
-    fb[buf][1] = *reinterpret_cast<const uint4*>((base) + TILE + brow1 * LDK + (s) * 16 + khalf);  \
+    if (BNN) {                                                                                     \
+      _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) {                                           \
+        const T* p_ = (base) + TILE + ((s) * 16 + trow) * LDN + tcol + j_ * 32;                    \
+        const s16x4 lo_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p_));               \
+        const s16x4 hi_ = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p_ + 4 * LDN));     \
+        const s16x8 both_ = __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7);             \
+        fb[buf][j_] = __builtin_bit_cast(uint4, both_);                                            \
+      }                                                                                            \
+    } else {                                                                                       \
+      fb[buf][0] = *reinterpret_cast<const uint4*>((base) + TILE + brow0 * LDK + (s) * 16 + khalf); \
+      fb[buf][1] = *reinterpret_cast<const uint4*>((base) + TILE + brow1 * LDK + (s) * 16 + khalf); \
+    }                                                                                              \
   } while (0)
 
   // prologue: tiles 0 .. RD-1 requested, tile 0 -> LDS stage 0, its slot re-requested with tile RD
@@ -691,18 +726,19 @@ int launch_mfma(const GemmArgs& g, hipStream_t s) {
   const bool ring = !BNN && g.Kk % BK == 0 && g.k_chunk % BK == 0 && params().gemm_ring;
   constexpr int BNO = (EPI == EPI_SWIGLU) ? 128 : 256;
   const int big_tiles = (g.M / GM) * (g.Nn / BNO);
-  const bool big = ring && g.M % GM == 0 && g.Nn % BNO == 0 && g.Kk / BK >= 2 &&
+  const bool ring_shape = g.Kk % BK == 0 && g.k_chunk % BK == 0 && params().gemm_ring;
+  const bool big = ring_shape && (EPI == EPI_LINEAR || !BNN) && g.M % GM == 0 && g.Nn % BNO == 0 && g.Kk / BK >= 2 &&
                    (params().gemm_big == 2 || (params().gemm_big == 1 && big_tiles * splits >= kBigMinWorkgroups));
   if (big) {
     const size_t lds_big = (size_t)2 * 2 * GM * LDK * sizeof(typename D::T);
     static bool big_attr_done = false;
     if (!big_attr_done) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_big_kernel<D, EPI>),
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_big_kernel<D, EPI, BNN && EPI == EPI_LINEAR>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_big) != hipSuccess)
         return CI_ERR_HIP;
       big_attr_done = true;
     }
-    hipLaunchKernelGGL((gemm_mfma_big_kernel<D, EPI>), dim3(big_tiles, splits), dim3(512), lds_big, s, g);
+    hipLaunchKernelGGL((gemm_mfma_big_kernel<D, EPI, BNN && EPI == EPI_LINEAR>), dim3(big_tiles, splits), dim3(512), lds_big, s, g);
   } else if (ring) {
     static bool ring_attr_done = false;
     if (lds > 48 * 1024 && !ring_attr_done) {

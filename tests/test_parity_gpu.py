@@ -248,17 +248,18 @@ def test_dense_matches_oracle(lib, dt, act, layout, M, d, N):
 
 @pytest.mark.parametrize("dt", ["f16", "bf16"])
 @pytest.mark.parametrize("act", ["relu", "swiglu"])
+@pytest.mark.parametrize("layout", ["out_major", "neuron_major"])
 @pytest.mark.parametrize("M,d,N", [(256, 128, 256), (512, 1024, 768), (256, 576, 1280), (768, 256, 512)])
-def test_dense_large_tile_kernel_matches_oracle(lib, dt, act, M, d, N):
+def test_dense_large_tile_kernel_matches_oracle(lib, dt, act, layout, M, d, N):
     """The 256 x 256 tile kernel, forced for shapes it divides (normally chosen only for large
     grids): up projection with both epilogues and the down projection, split over k or not."""
-    _say("dense large-tile case", dt, act, M, d, N)
+    _say("dense large-tile case", dt, act, layout, M, d, N)
     dtype = DTYPES[dt]
-    w = rand_weights(d, N, dtype, act, "out_major", seed=M + d + N + 9, device=DEV)
+    w = rand_weights(d, N, dtype, act, layout, seed=M + d + N + 9, device=DEV)
     X = torch.randn(M, d, generator=torch.Generator().manual_seed(M + 1)).to(dtype).to(DEV)
     lib.set_param("gemm_big", 2)
     try:
-        Y, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], "out_major", act,
+        Y, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], layout, act,
                              want_y=True, want_a=True)
         torch.cuda.synchronize()
     finally:
@@ -269,7 +270,7 @@ def test_dense_large_tile_kernel_matches_oracle(lib, dt, act, M, d, N):
         A_ref = orc.score_swiglu(f64(X), f64(w["w_gate"]), f64(w["w_up"]))
     rms = np.sqrt(np.mean(A_ref ** 2))
     assert np.max(np.abs(f64(A) - A_ref)) <= 1e-4 * rms
-    assert_close_rms(Y, _oracle_ffn(act, X, None, w, "out_major"), dtype, "dense Y, large tiles")
+    assert_close_rms(Y, _oracle_ffn(act, X, None, w, layout), dtype, "dense Y, large tiles")
 
 
 # ------------------------------------------------------------- whole small path
