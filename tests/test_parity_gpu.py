@@ -503,6 +503,43 @@ def test_decode_union_empty_sets_give_the_output_bias(lib):
         assert torch.equal(y[b], w["b_down"])
 
 
+# ------------------------------------------------------------ the documented size limits
+
+def test_select_at_the_size_limits(lib):
+    """N = CI_MAX_NEURONS with two tokens, and M = CI_MAX_TOKENS (counts up to 65535) on a narrow layer."""
+    A = wl.activation_like(2, 1 << 20, seed=77, kind="relu", levels=0)
+    _select_case(lib, A, 0.2, 0.4, "N at its limit")
+    A = wl.activation_like(65535, 48, seed=78, kind="relu", levels=4)
+    _select_case(lib, A, 0.25, 0.5, "M at its limit")
+
+
+@pytest.mark.parametrize("dt,act", [("f16", "relu"), ("bf16", "swiglu")])
+def test_decode_and_dense_at_the_model_width_limit(lib, dt, act):
+    """d = CI_MAX_DMODEL: four 16-byte vectors per thread in the decode kernels."""
+    d, N, K = 32768, 200, 71
+    dtype = DTYPES[dt]
+    _say("width limit", dt, act, d, N, K)
+    w = rand_weights(d, N, dtype, act, "neuron_major", seed=3, device=DEV)
+    S = np.stack([np.sort(np.random.default_rng(5 + b).choice(N, size=K, replace=False)) for b in range(2)])
+    idx = torch.from_numpy(S.astype(np.int32)).to(DEV)
+    x = (torch.randn(2, d, generator=torch.Generator().manual_seed(2)) * 0.05).to(dtype).to(DEV)
+    yg = lib.ffn_decode(x, lib.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"],
+                                            core_idx=idx), act)
+    c = lib.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], "neuron_major", act, idx[0].contiguous())
+    yc = lib.ffn_decode(x[:1], lib.make_weights(c["w_up_c"], c["w_gate_c"], c["b_up_c"], c["w_down_c"], w["b_down"]), act)
+    uidx, umask, ucount = lib.union_build(idx, N)
+    yu = lib.ffn_decode_union(x, lib.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"]),
+                              uidx, umask, ucount, act)
+    Yd, _ = lib.ffn_dense(x, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], "neuron_major", act)
+    torch.cuda.synchronize()
+    for b in range(2):
+        ref = _oracle_ffn(act, x[b], S[b], w, "neuron_major")
+        assert_close_rms(yg[b], ref, dtype, f"gathered, widest model, b={b}")
+        assert_close_rms(yu[b], ref, dtype, f"union-batched, widest model, b={b}")
+        assert_close_rms(Yd[b], _oracle_ffn(act, x[b], None, w, "neuron_major"), dtype, f"dense, widest model, b={b}")
+    assert_close_rms(yc[0], _oracle_ffn(act, x[0], S[0], w, "neuron_major"), dtype, "compacted, widest model")
+
+
 # --------------------------------- running counts, group sets, similarity (next rows)
 
 def test_running_counts_and_count_select_match_oracle(lib):
