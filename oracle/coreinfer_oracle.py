@@ -27,6 +27,10 @@ What is here, and the passage each part follows:
 * ``group_core_neurons``    -- similarity-guided prediction, group step
   (Sec. 4.1): top-gamma of neurons by how many of the group's sentences have
   them in their core set.
+* ``assign_group``          -- similarity-guided prediction, choosing the group
+  (Sec. 4.1 says only "once the input sentence's group is determined"): the
+  group whose core set is most similar to the prompt's own under Insight-2's
+  metric.
 * ``count_tokens_into``     -- Eq. 3 as a running sum when a sentence grows.
 * ``union_rows``            -- batching several sentences that share resident
   weights (the Sec. 5.3 large-model scenario): the neurons any sentence
@@ -271,6 +275,23 @@ def core_similarity_counts(S1, S2):
     """(identical neurons, neurons involved) of Insight-2's similarity."""
     a, b = set(int(v) for v in S1), set(int(v) for v in S2)
     return len(a & b), len(a | b)
+
+
+def assign_group(prompt_set, group_sets):
+    """Similarity-guided prediction, group choice (Sec. 4.1; the rule is a
+    reading, the paper leaves it open): the group whose core set has the
+    largest Insight-2 similarity (identical / involved neurons) with the
+    prompt's own core set; equal similarities go to the lower group index;
+    two empty sets count as similarity 1.  Returns (group, [(identical,
+    involved) per group]).  Compared as exact fractions."""
+    from fractions import Fraction
+    pairs = [core_similarity_counts(prompt_set, G) for G in group_sets]
+    best, best_sim = -1, None
+    for g, (i, u) in enumerate(pairs):
+        sim = Fraction(1) if u == 0 else Fraction(i, u)
+        if best_sim is None or sim > best_sim:
+            best, best_sim = g, sim
+    return best, pairs
 
 
 def core_similarity(S1, S2) -> float:

@@ -394,3 +394,27 @@ def test_union_rows_hand_example_and_set_identities():
     assert U.tolist() == [2, 4, 6] and owners.tolist() == [1, 1, 1]
     U, owners = orc.union_rows([[], []], 8)
     assert U.size == 0 and owners.size == 0
+
+
+def test_assign_group_hand_example_and_identities():
+    prompt = [1, 2, 3, 4]
+    groups = [[1, 2, 9, 10], [2, 3, 4, 8], [5, 6, 7, 11]]
+    # identical / involved: 2/6, 3/5, 0/8 -> group 1
+    g, pairs = orc.assign_group(prompt, groups)
+    assert g == 1 and pairs == [(2, 6), (3, 5), (0, 8)]
+    # a group equal to the prompt's set has similarity 1 and wins; ties go to the lower index
+    g, _ = orc.assign_group(prompt, [[7, 8, 9, 10], [1, 2, 3, 4], [1, 2, 3, 4]])
+    assert g == 1
+    g, _ = orc.assign_group(prompt, [[1, 2, 5, 6], [3, 4, 7, 8]])     # both 2/6
+    assert g == 0
+    # reordering the groups moves the answer with them
+    rng = np.random.default_rng(3)
+    groups = [np.sort(rng.choice(200, size=40, replace=False)) for _ in range(7)]
+    prompt = np.sort(rng.choice(200, size=40, replace=False))
+    g, pairs = orc.assign_group(prompt, groups)
+    sims = [orc.core_similarity(prompt, G) for G in groups]
+    assert g == int(np.argmax(sims)) and sims.count(max(sims)) == 1
+    perm = rng.permutation(7)
+    g2, _ = orc.assign_group(prompt, [groups[i] for i in perm])
+    assert perm[g2] == g
+    assert orc.assign_group([], [[], [1]])[0] == 0
