@@ -166,6 +166,19 @@ int coreinfer_core_similarity(const int32_t* set_a, int64_t Ka, const int32_t* s
                               int32_t* out, void* stream);
 
 /*
+ * Similarity-guided prediction, choosing the group (Sec. 4.1 says only "once
+ * the input sentence's group is determined"; the rule here is a reading): the
+ * group whose core set is most similar to the prompt's own core set under the
+ * metric above.  set [K] and every row of group_sets [G, Kg]: ascending,
+ * duplicate free.  Out (device): inter_union [G, 2] int32 as for
+ * coreinfer_core_similarity, best [1] int32 = the group with the largest
+ * identical / involved ratio, compared exactly; equal ratios go to the lower
+ * index; two empty sets count as ratio 1.  G <= CI_MAX_TOKENS.
+ */
+int coreinfer_assign_group(const int32_t* set, int64_t K, const int32_t* group_sets, int64_t G, int64_t Kg,
+                           int32_t* best, int32_t* inter_union, void* stream);
+
+/*
  * Deploy the core neurons (Sec. 5.3): gather rows S of w_up (and w_gate),
  * entries S of b_up and columns S of w_down into contiguous, neuron-major
  * buffers:

@@ -58,6 +58,7 @@ _SIGNATURES = {
     "coreinfer_count_select": (_int, [_vp, _i64, _i64, _dbl, _vp, _vp, _sz, _vp]),
     "coreinfer_group_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_core_similarity": (_int, [_vp, _i64, _vp, _i64, _vp, _vp]),
+    "coreinfer_assign_group": (_int, [_vp, _i64, _vp, _i64, _i64, _vp, _vp, _vp]),
     "coreinfer_compact": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64,
                                  _vp, _vp, _vp, _vp, _vp, _vp]),
     "coreinfer_ffn_decode_workspace_size": (_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
@@ -194,6 +195,16 @@ def core_similarity(set_a: torch.Tensor, set_b: torch.Tensor, out: Optional[torc
     _check(_lib.coreinfer_core_similarity(_ptr(set_a), set_a.numel(), _ptr(set_b), set_b.numel(), _ptr(out),
                                           _stream(set_a)), "coreinfer_core_similarity")
     return out
+
+
+def assign_group(prompt_set: torch.Tensor, group_sets: torch.Tensor):
+    """coreinfer_assign_group.  Returns (best [1] int32, inter_union [G, 2] int32) on the device."""
+    G, Kg = group_sets.shape
+    best = torch.empty(1, dtype=torch.int32, device=group_sets.device)
+    iu = torch.empty((G, 2), dtype=torch.int32, device=group_sets.device)
+    _check(_lib.coreinfer_assign_group(_ptr(prompt_set), prompt_set.numel(), _ptr(group_sets), G, Kg,
+                                       _ptr(best), _ptr(iu), _stream(group_sets)), "coreinfer_assign_group")
+    return best, iu
 
 
 def compact(w_up, w_gate, b_up, w_down, down_layout: str, act: str, core_idx: torch.Tensor,

@@ -187,6 +187,18 @@ int coreinfer_core_similarity(const int32_t* set_a, int64_t Ka, const int32_t* s
   return launch_similarity(set_a, Ka, set_b, Kb, out, (hipStream_t)stream);
 }
 
+int coreinfer_assign_group(const int32_t* set, int64_t K, const int32_t* group_sets, int64_t G, int64_t Kg,
+                           int32_t* best, int32_t* inter_union, void* stream) {
+  if (!best || !inter_union || G < 1 || G > CI_MAX_TOKENS || K < 0 || Kg < 0 || K > CI_MAX_NEURONS ||
+      Kg > CI_MAX_NEURONS)
+    return CI_ERR_INVALID_ARG;
+  if ((K > 0 && !set) || (Kg > 0 && !group_sets)) return CI_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(set) & 3u) || (reinterpret_cast<uintptr_t>(group_sets) & 3u) ||
+      (reinterpret_cast<uintptr_t>(best) & 3u) || (reinterpret_cast<uintptr_t>(inter_union) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  return launch_assign_group(set, K, group_sets, G, Kg, best, inter_union, (hipStream_t)stream);
+}
+
 int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                       int down_layout, int dtype, int act, int64_t d, int64_t N,
                       const int32_t* core_idx, int64_t K, void* w_up_c, void* w_gate_c,

@@ -406,12 +406,15 @@ __global__ void scatter_count_kernel(const int32_t* __restrict__ idx, int64_t n_
 }
 
 // out[0] = |a ∩ b|, out[1] = |a ∪ b| for two ascending duplicate-free index
-// lists (Insight-2's similarity is out[0] / out[1]).  One workgroup; every
+// lists (Insight-2's similarity is out[0] / out[1]).  One workgroup per list a
+// (blockIdx.x picks row a + blockIdx.x * Ka and out + 2 * blockIdx.x); every
 // element of a is looked up in b by binary search.
 __global__ __launch_bounds__(1024) void similarity_kernel(const int32_t* __restrict__ a, int Ka,
                                                           const int32_t* __restrict__ b, int Kb,
                                                           int32_t* out) {
   __shared__ uint32_t wsum[kMaxWaves];
+  a += (size_t)blockIdx.x * Ka;
+  out += 2 * blockIdx.x;
   uint32_t hits = 0;
   for (int i = threadIdx.x; i < Ka; i += blockDim.x) {
     const int v = a[i];
@@ -431,6 +434,35 @@ __global__ __launch_bounds__(1024) void similarity_kernel(const int32_t* __restr
     out[0] = (int32_t)t;
     out[1] = Ka + Kb - (int32_t)t;
   }
+}
+
+// best[0] = the group with the largest identical / involved ratio (compared
+// exactly by cross-multiplication; 0 / 0 counts as 1; ties to the lower index).
+__global__ __launch_bounds__(1024) void best_group_kernel(const int32_t* __restrict__ iu, int G,
+                                                          int32_t* __restrict__ best) {
+  __shared__ int64_t si[1024], su[1024];
+  __shared__ int sg[1024];
+  int64_t bi = -1, bu = 1;
+  int bg = 0x7fffffff;
+  for (int g = threadIdx.x; g < G; g += blockDim.x) {
+    int64_t i = iu[2 * g], u = iu[2 * g + 1];
+    if (u == 0) { i = 1; u = 1; }
+    if (i * bu > bi * u) { bi = i; bu = u; bg = g; }  // strictly better only: keeps the lowest index
+  }
+  si[threadIdx.x] = bi; su[threadIdx.x] = bu; sg[threadIdx.x] = bg;
+  __syncthreads();
+  for (int half = 512; half >= 1; half >>= 1) {
+    if ((int)threadIdx.x < half) {
+      const int64_t i2 = si[threadIdx.x + half], u2 = su[threadIdx.x + half];
+      const int g2 = sg[threadIdx.x + half];
+      const int64_t l = i2 * su[threadIdx.x], r = si[threadIdx.x] * u2;
+      if (l > r || (l == r && g2 < sg[threadIdx.x])) {
+        si[threadIdx.x] = i2; su[threadIdx.x] = u2; sg[threadIdx.x] = g2;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) best[0] = sg[0];
 }
 
 template <int ITEMS>
@@ -504,6 +536,14 @@ int launch_scatter_count(const int32_t* idx, int64_t n_idx, int64_t N, int32_t* 
 
 int launch_similarity(const int32_t* a, int64_t Ka, const int32_t* b, int64_t Kb, int32_t* out, hipStream_t s) {
   hipLaunchKernelGGL(similarity_kernel, dim3(1), dim3(1024), 0, s, a, (int)Ka, b, (int)Kb, out);
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
+
+int launch_assign_group(const int32_t* set, int64_t K, const int32_t* groups, int64_t G, int64_t Kg,
+                        int32_t* best, int32_t* iu, hipStream_t s) {
+  hipLaunchKernelGGL(similarity_kernel, dim3((unsigned)G), dim3(1024), 0, s, groups, (int)Kg, set, (int)K, iu);
+  hipLaunchKernelGGL(best_group_kernel, dim3(1), dim3(1024), 0, s, iu, (int)G, best);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }

@@ -164,6 +164,12 @@ def test_next_row_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert r(F, 3, 80, 64, 0.2, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 3, 8, 64, 2.0, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 3, 8, 64, 0.2, F, None, F, 16, None) == lib.CI_ERR_WORKSPACE
+    r = lib.raw.coreinfer_assign_group
+    assert r(F, 4, F, 0, 4, F, F, None) == lib.CI_ERR_INVALID_ARG
+    assert r(None, 4, F, 3, 4, F, F, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, None, 3, 4, F, F, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, F, 3, 4, None, F, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, F, 3, 4, F, F + 2, None) == lib.CI_ERR_BAD_LAYOUT
     r = lib.raw.coreinfer_core_similarity
     assert r(F, 4, F, 4, None, None) == lib.CI_ERR_INVALID_ARG
     assert r(None, 4, F, 4, F, None) == lib.CI_ERR_INVALID_ARG

@@ -596,6 +596,21 @@ def test_core_similarity_matches_oracle(lib):
         assert tuple(out.cpu().numpy().tolist()) == orc.core_similarity_counts(a, b), (N, Ka, Kb)
 
 
+@pytest.mark.parametrize("G,K,Kg,N", [(1, 5, 5, 40), (4, 410, 410, 1024), (37, 6554, 3277, 16384), (1500, 20, 30, 300)])
+def test_assign_group_matches_oracle(lib, G, K, Kg, N):
+    rng = np.random.default_rng(G * 7 + K)
+    prompt = np.sort(rng.choice(N, size=K, replace=False))
+    groups = np.stack([np.sort(rng.choice(N, size=Kg, replace=False)) for _ in range(G)])
+    if G >= 4:                       # two groups with exactly the same similarity: the lower index wins
+        groups[G - 1] = groups[1]
+    best, iu = lib.assign_group(torch.from_numpy(prompt.astype(np.int32)).to(DEV),
+                                torch.from_numpy(groups.astype(np.int32)).to(DEV))
+    torch.cuda.synchronize()
+    g_ref, pairs = orc.assign_group(prompt, list(groups))
+    assert iu.cpu().numpy().tolist() == [list(p) for p in pairs]
+    assert int(best.item()) == g_ref
+
+
 def test_decode_graph_replays_match_eager(lib):
     """The decode launches captured in a HIP graph give the eager result on every replay,
     with other work and synchronisations in between."""
