@@ -38,17 +38,23 @@ def parse_args():
     return p.parse_args()
 
 
-def read_traffic_note(workload: str):
+def read_traffic_note(workload: str, algorithmic_bytes: int):
     """HBM bytes per launch of the dominant kernel measured with rocprofv3
-    --pmc (FETCH_SIZE / WRITE_SIZE), if a summary has been committed."""
+    --pmc (FETCH_SIZE / WRITE_SIZE), if a summary has been committed for this
+    workload at the same launch size (same keep fraction)."""
     path = os.path.join(ROOT, "profiles", f"pmc_ffn_decode_{workload}.txt")
+    traffic, alg = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                traffic = float(line.split(":", 1)[1])
+            if line.startswith("algorithmic_bytes_per_launch:"):
+                alg = int(line.split(":", 1)[1])
     except OSError:
-        pass
-    return None
+        return None
+    if alg is None or abs(alg - algorithmic_bytes) > 0.001 * algorithmic_bytes:
+        return None
+    return traffic
 
 
 def main():
@@ -272,7 +278,7 @@ def main():
         bytes_per_launch += B * K * 4
     achieved_gbps = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
     e2e_gbps = bytes_per_launch * L * T / (decode_ms * 1e-3) / 1e9
-    traffic = read_traffic_note(cfg.name)
+    traffic = read_traffic_note(cfg.name, bytes_per_launch)
 
     # ------------------------------------------------------------- CPU oracle baseline + parity
     cpu = None
