@@ -32,6 +32,9 @@ What is here, and the passage each part follows:
   group whose core set is most similar to the prompt's own under Insight-2's
   metric.
 * ``count_tokens_into``     -- Eq. 3 as a running sum when a sentence grows.
+* ``compact_update_slots``  -- re-deploying after the core set changed
+  (Fig. 1 "stability estimation ... how to update"; the paper gives no rule):
+  only the rows whose neuron left the set are rewritten.
 * ``union_rows``            -- batching several sentences that share resident
   weights (the Sec. 5.3 large-model scenario): the neurons any sentence
   needs, each tagged with the sentences that own it.  The decode result of a
@@ -253,6 +256,31 @@ def group_core_neurons(core_sets, n_neurons: int, gamma: float):
             if 0 <= int(n) < n_neurons:
                 counts[int(n)] += 1
     return sentence_core_neurons(counts, gamma), counts
+
+
+def compact_update_slots(slot_idx, new_set):
+    """Updating deployed neurons in place when the core set changes (the paper
+    names the update in Fig. 1 but gives no rule; this one rewrites as little
+    as possible).  ``slot_idx[j]`` is the neuron held by row j of the compact
+    buffers.  Neurons that stay keep their row; the rows of neurons that left
+    (ascending row) take the neurons that entered (ascending neuron).
+    Returns (new slot_idx, number of rows rewritten)."""
+    slot_idx = [int(v) for v in slot_idx]
+    new = sorted(set(int(v) for v in new_set))
+    if len(new) != len(slot_idx):
+        raise ValueError("the core set keeps its size")
+    newset = set(new)
+    seen, free = set(), []
+    for j, n in enumerate(slot_idx):
+        if n in newset and n not in seen:
+            seen.add(n)
+        else:
+            free.append(j)
+    entering = [n for n in new if n not in seen]
+    out = list(slot_idx)
+    for j, n in zip(free, entering):
+        out[j] = n
+    return np.asarray(out, dtype=np.int64), len(free)
 
 
 def union_rows(core_sets, n_neurons: int):

@@ -418,3 +418,28 @@ def test_assign_group_hand_example_and_identities():
     g2, _ = orc.assign_group(prompt, [groups[i] for i in perm])
     assert perm[g2] == g
     assert orc.assign_group([], [[], [1]])[0] == 0
+
+
+def test_compact_update_slots_hand_example_and_invariants():
+    # rows hold neurons 2 5 7 9; new set 2 3 9 11: 5 and 7 leave (rows 1, 2), 3 and 11 enter
+    out, changed = orc.compact_update_slots([2, 5, 7, 9], [2, 3, 9, 11])
+    assert out.tolist() == [2, 3, 11, 9] and changed == 2
+    out, changed = orc.compact_update_slots([2, 5, 7, 9], [9, 7, 5, 2])
+    assert out.tolist() == [2, 5, 7, 9] and changed == 0
+    rng = np.random.default_rng(8)
+    slots = rng.permutation(300)[:120]
+    for _ in range(5):           # a chain of updates
+        new = np.sort(rng.choice(300, size=120, replace=False))
+        out, changed = orc.compact_update_slots(slots, new)
+        assert sorted(out.tolist()) == new.tolist()                      # exactly the new set, once each
+        stay = np.isin(slots, new)
+        assert (out[stay] == slots[stay]).all()                          # who stays keeps the row
+        assert changed == int((~stay).sum()) == len(set(new) - set(slots))
+        # the FFN over the rows in slot order is the FFN over the new set (a sum over neurons)
+        slots = out
+    d, N = 16, 300
+    W1, W2, x = rng.standard_normal((N, d)), rng.standard_normal((d, N)), rng.standard_normal(d)
+    b1 = rng.standard_normal(N)
+    y_slots = orc.ffn_relu(x, slots, W1, b1, W2)
+    y_sorted = orc.ffn_relu(x, np.sort(slots), W1, b1, W2)
+    assert np.allclose(y_slots, y_sorted, rtol=1e-12, atol=1e-12)
