@@ -198,6 +198,28 @@ int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up,
                       int32_t* status, void* stream);
 
 /*
+ * Re-deploying after the core set changed (Fig. 1 names a stability estimation
+ * that decides "how to update" the set but gives no rule; this call rewrites
+ * as little as possible).  The compact buffers written by coreinfer_compact
+ * (or by an earlier update) are changed in place so that they hold exactly the
+ * neurons of new_idx: a neuron that stays keeps its row; the rows of neurons
+ * that left, in ascending row order, take the neurons that entered, in
+ * ascending neuron order.  Only those rows are copied.
+ *   new_idx [K] int32 ascending, duplicate free, the new core set (same K as
+ *   the buffers).  slot_idx [K] int32, in/out: the neuron held by each row;
+ *   after coreinfer_compact it equals that call's core_idx.  The decode entry
+ *   point does not care about the order of the rows.  changed [1] int32
+ *   (device, may be NULL): number of rows rewritten.  Weights, layouts and
+ *   dtypes as for coreinfer_compact.  ws: coreinfer_compact_update_workspace_size.
+ */
+int coreinfer_compact_update_workspace_size(int64_t N, int64_t K, size_t* bytes);
+int coreinfer_compact_update(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
+                             int down_layout, int dtype, int act, int64_t d, int64_t N,
+                             const int32_t* new_idx, int64_t K, int32_t* slot_idx, void* w_up_c,
+                             void* w_gate_c, void* b_up_c, void* w_down_c, int32_t* changed, void* ws,
+                             size_t ws_bytes, void* stream);
+
+/*
  * Weights of one FFN layer as the decode kernel reads them.
  *   core_idx == NULL: compacted -- the buffers written by coreinfer_compact;
  *                     K rows each, shared by all B inputs.

@@ -61,6 +61,9 @@ _SIGNATURES = {
     "coreinfer_assign_group": (_int, [_vp, _i64, _vp, _i64, _i64, _vp, _vp, _vp]),
     "coreinfer_compact": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64,
                                  _vp, _vp, _vp, _vp, _vp, _vp]),
+    "coreinfer_compact_update_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
+    "coreinfer_compact_update": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64, _vp,
+                                        _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_ffn_decode_workspace_size": (_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_ffn_decode": (_int, [_vp, _i64, ctypes.POINTER(ci_ffn_weights), _int, _int, _vp,
                                     _vp, _sz, _vp]),
@@ -226,6 +229,27 @@ def compact(w_up, w_gate, b_up, w_down, down_layout: str, act: str, core_idx: to
                                   _ptr(out["b_up_c"]), _ptr(out["w_down_c"]), _ptr(status), _stream(w_up)),
            "coreinfer_compact")
     return out
+
+
+def compact_update(w_up, w_gate, b_up, w_down, down_layout: str, act: str, new_idx: torch.Tensor,
+                   slot_idx: torch.Tensor, bufs: dict, changed: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """coreinfer_compact_update: `bufs` (from compact) and `slot_idx` are changed in place.
+    Returns the device int32 [1] holding the number of rows rewritten."""
+    N, d = w_up.shape
+    K = new_idx.numel()
+    if changed is None:
+        changed = torch.zeros(1, dtype=torch.int32, device=w_up.device)
+    b = _sz(0)
+    _check(_lib.coreinfer_compact_update_workspace_size(N, K, ctypes.byref(b)),
+           "coreinfer_compact_update_workspace_size")
+    ws = _workspace(b.value, w_up)
+    _check(_lib.coreinfer_compact_update(_ptr(w_up), _ptr(w_gate), _ptr(b_up), _ptr(w_down),
+                                         LAYOUT_CODE[down_layout], DTYPE_CODE[w_up.dtype], ACT_CODE[act],
+                                         d, N, _ptr(new_idx), K, _ptr(slot_idx), _ptr(bufs["w_up_c"]),
+                                         _ptr(bufs["w_gate_c"]), _ptr(bufs["b_up_c"]), _ptr(bufs["w_down_c"]),
+                                         _ptr(changed), _ptr(ws), ws.numel(), _stream(w_up)),
+           "coreinfer_compact_update")
+    return changed
 
 
 def ffn_decode_workspace_size(B: int, K: int, d: int) -> int:

@@ -218,6 +218,38 @@ int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up, co
                         w_gate_c, b_up_c, w_down_c, status, (hipStream_t)stream);
 }
 
+int coreinfer_compact_update_workspace_size(int64_t N, int64_t K, size_t* bytes) {
+  if (!bytes || N < 1 || N > CI_MAX_NEURONS || K < 0 || K > N) return CI_ERR_INVALID_ARG;
+  *bytes = round256(((size_t)N + 3 * (size_t)K + 64) * sizeof(uint32_t));
+  return CI_OK;
+}
+
+int coreinfer_compact_update(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
+                             int down_layout, int dtype, int act, int64_t d, int64_t N,
+                             const int32_t* new_idx, int64_t K, int32_t* slot_idx, void* w_up_c,
+                             void* w_gate_c, void* b_up_c, void* w_down_c, int32_t* changed, void* ws,
+                             size_t ws_bytes, void* stream) {
+  if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  if (!layout_ok(down_layout)) return CI_ERR_BAD_LAYOUT;
+  if (d < 1 || d > CI_MAX_DMODEL) return CI_ERR_INVALID_ARG;
+  size_t need = 0;
+  if (coreinfer_compact_update_workspace_size(N, K, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!w_up || !w_down || !w_up_c || !w_down_c || (K > 0 && (!new_idx || !slot_idx))) return CI_ERR_INVALID_ARG;
+  if ((act == CI_ACT_SWIGLU) != (w_gate != nullptr) || (w_gate != nullptr) != (w_gate_c != nullptr))
+    return CI_ERR_INVALID_ARG;
+  if ((b_up != nullptr) != (b_up_c != nullptr)) return CI_ERR_INVALID_ARG;
+  if (d % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
+  if (!aligned16(w_up) || !aligned16(w_gate) || !aligned16(w_down) || !aligned16(w_up_c) ||
+      !aligned16(w_gate_c) || !aligned16(w_down_c) || (reinterpret_cast<uintptr_t>(new_idx) & 3u) ||
+      (reinterpret_cast<uintptr_t>(slot_idx) & 3u) || (reinterpret_cast<uintptr_t>(changed) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
+  return launch_compact_update(w_up, w_gate, b_up, w_down, down_layout, dtype, d, N, new_idx, K, slot_idx,
+                               w_up_c, w_gate_c, b_up_c, w_down_c, changed, reinterpret_cast<uint32_t*>(ws),
+                               (hipStream_t)stream);
+}
+
 int coreinfer_ffn_decode_workspace_size(int64_t B, int64_t K, int64_t d, size_t* bytes) {
   if (!bytes || B < 1 || B > 65535 || K < 0 || K > CI_MAX_NEURONS || d < 1 || d > CI_MAX_DMODEL)
     return CI_ERR_INVALID_ARG;

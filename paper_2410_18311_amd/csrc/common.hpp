@@ -149,6 +149,10 @@ int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const
                    int down_layout, int dtype, int64_t d, int64_t N, const int32_t* core_idx,
                    int64_t K, void* w_up_c, void* w_gate_c, void* b_up_c, void* w_down_c,
                    int32_t* status, hipStream_t s);
+int launch_compact_update(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
+                          int down_layout, int dtype, int64_t d, int64_t N, const int32_t* new_idx,
+                          int64_t K, int32_t* slot_idx, void* w_up_c, void* w_gate_c, void* b_up_c,
+                          void* w_down_c, int32_t* changed, uint32_t* ws, hipStream_t s);
 int decode_splits(int64_t B, int64_t K);
 int launch_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,
                       void* y, float* partial, hipStream_t s);

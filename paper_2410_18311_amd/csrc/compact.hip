@@ -78,7 +78,167 @@ __global__ __launch_bounds__(256) void gather_cols_t_kernel(const E* __restrict_
   }
 }
 
+// ---- in-place update after the core set changed ------------------------------
+// flags[n]: 0 not in the new set, 1 in the new set and not yet deployed, 2 in
+// the new set and already held by a row.
+__global__ void delta_zero_kernel(uint32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+__global__ void delta_mark_new_kernel(const int32_t* __restrict__ new_idx, int K, int N, uint32_t* flags) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= K) return;
+  const int n = new_idx[j];
+  if (n >= 0 && n < N) flags[n] = 1u;
+}
+// keep[j] = 1 when row j's neuron stays (first row to claim it), else the row is free
+__global__ void delta_mark_kept_kernel(const int32_t* __restrict__ slot_idx, int K, int N, uint32_t* flags,
+                                       uint32_t* keep) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= K) return;
+  const int n = slot_idx[j];
+  uint32_t k = 0;
+  if (n >= 0 && n < N) k = atomicCAS(&flags[n], 1u, 2u) == 1u ? 1u : 0u;
+  keep[j] = k;
+}
+// Ordered lists of the free rows (ascending row) and of the entering neurons
+// (ascending neuron); count[0] = number of pairs.  One workgroup.
+__global__ __launch_bounds__(1024) void delta_pair_kernel(const int32_t* __restrict__ new_idx,
+                                                          const uint32_t* __restrict__ flags,
+                                                          const uint32_t* __restrict__ keep, int K, int N,
+                                                          int32_t* free_list, int32_t* enter_list,
+                                                          int32_t* count, int32_t* changed) {
+  __shared__ int wf[16], we[16];
+  __shared__ int base_f, base_e;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) { base_f = 0; base_e = 0; }
+  __syncthreads();
+  for (int j0 = 0; j0 < K; j0 += 1024) {
+    const int j = j0 + tid;
+    const bool is_free = j < K && keep[j] == 0u;
+    int n = -1;
+    if (j < K) n = new_idx[j];
+    // entering: in the new set, not held by any row; a duplicate in new_idx counts once (its first place)
+    const bool enters = j < K && n >= 0 && n < N && flags[n] == 1u && (j == 0 || new_idx[j - 1] != n);
+    const uint64_t bf = __ballot(is_free), be = __ballot(enters);
+    if (lane == 0) { wf[wave] = __popcll(bf); we[wave] = __popcll(be); }
+    __syncthreads();
+    int of = base_f, oe = base_e;
+    for (int w = 0; w < wave; ++w) { of += wf[w]; oe += we[w]; }
+    if (is_free) free_list[of + __popcll(bf & lanemask_lt())] = j;
+    if (enters) enter_list[oe + __popcll(be & lanemask_lt())] = n;
+    __syncthreads();
+    if (tid == 0) {
+      int tf = 0, te = 0;
+      for (int w = 0; w < 16; ++w) { tf += wf[w]; te += we[w]; }
+      base_f += tf; base_e += te;
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const int c = base_f < base_e ? base_f : base_e;
+    count[0] = c;
+    if (changed) changed[0] = c;
+  }
+}
+// Row t of the pair list: the entering neuron's weights go to the free row.
+__global__ __launch_bounds__(256) void delta_rows_kernel(RowGather g, const int32_t* __restrict__ free_list,
+                                                         const int32_t* __restrict__ enter_list,
+                                                         const int32_t* __restrict__ count,
+                                                         int32_t* slot_idx, int vecs_per_row) {
+  const int t = blockIdx.x, mat = blockIdx.y;
+  if (t >= count[0]) return;
+  const size_t dst = (size_t)free_list[t], src = (size_t)enter_list[t];
+  const uint4* in = reinterpret_cast<const uint4*>(g.in[mat]) + src * vecs_per_row;
+  uint4* out = reinterpret_cast<uint4*>(g.out[mat]) + dst * vecs_per_row;
+  for (int v = threadIdx.x; v < vecs_per_row; v += blockDim.x) out[v] = in[v];
+  if (mat == 0 && threadIdx.x == 0) {
+    slot_idx[dst] = (int32_t)src;
+    if (g.b_in) {
+      if (g.elem == 2) reinterpret_cast<uint16_t*>(g.b_out)[dst] = reinterpret_cast<const uint16_t*>(g.b_in)[src];
+      else reinterpret_cast<uint32_t*>(g.b_out)[dst] = reinterpret_cast<const uint32_t*>(g.b_in)[src];
+    }
+  }
+}
+// nn.Linear [d, N] down matrix: out[free_list[t], j] = in[j, enter_list[t]], 64 pairs x 64 j per workgroup.
+template <class E>
+__global__ __launch_bounds__(256) void delta_cols_t_kernel(const E* __restrict__ in, E* __restrict__ out,
+                                                           const int32_t* __restrict__ free_list,
+                                                           const int32_t* __restrict__ enter_list,
+                                                           const int32_t* __restrict__ count, int N, int d) {
+  __shared__ E tile[64][65];
+  __shared__ int sdst[64];
+  const int c = count[0];
+  const int t0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  if (t0 >= c) return;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int t = t0 + tx;
+  const bool ok = t < c;
+  const size_t n = ok ? (size_t)enter_list[t] : 0;
+  if (ty == 0) sdst[tx] = ok ? free_list[t] : 0;
+  for (int jj = ty; jj < 64; jj += 4) {
+    const int j = j0 + jj;
+    E v = 0;
+    if (ok && j < d) v = in[(size_t)j * N + n];
+    tile[jj][tx] = v;
+  }
+  __syncthreads();
+  const int j = j0 + tx;
+  for (int kk = ty; kk < 64; kk += 4) {
+    if (t0 + kk < c && j < d) out[(size_t)sdst[kk] * d + j] = tile[tx][kk];
+  }
+}
+
 }  // namespace
+
+int launch_compact_update(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
+                          int down_layout, int dtype, int64_t d, int64_t N, const int32_t* new_idx,
+                          int64_t K, int32_t* slot_idx, void* w_up_c, void* w_gate_c, void* b_up_c,
+                          void* w_down_c, int32_t* changed, uint32_t* ws, hipStream_t s) {
+  // workspace: flags [N], keep [K], free_list [K], enter_list [K], count [1]
+  uint32_t* flags = ws;
+  uint32_t* keep = flags + N;
+  int32_t* free_list = reinterpret_cast<int32_t*>(keep + K);
+  int32_t* enter_list = free_list + K;
+  int32_t* count = enter_list + K;
+  const unsigned gk = (unsigned)((K + 255) / 256);
+  hipLaunchKernelGGL(delta_zero_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, flags, N);
+  if (K > 0) {
+    hipLaunchKernelGGL(delta_mark_new_kernel, dim3(gk), dim3(256), 0, s, new_idx, (int)K, (int)N, flags);
+    hipLaunchKernelGGL(delta_mark_kept_kernel, dim3(gk), dim3(256), 0, s, slot_idx, (int)K, (int)N, flags, keep);
+  }
+  hipLaunchKernelGGL(delta_pair_kernel, dim3(1), dim3(1024), 0, s, new_idx, flags, keep, (int)K, (int)N,
+                     free_list, enter_list, count, changed);
+  CI_HIP_CHECK_LAUNCH();
+  if (K == 0) return CI_OK;
+  const int e = elem_bytes(dtype);
+  RowGather g;
+  g.n_mat = 0;
+  g.in[g.n_mat] = w_up; g.out[g.n_mat++] = w_up_c;
+  if (w_gate) { g.in[g.n_mat] = w_gate; g.out[g.n_mat++] = w_gate_c; }
+  if (down_layout == CI_DOWN_NEURON_MAJOR) { g.in[g.n_mat] = w_down; g.out[g.n_mat++] = w_down_c; }
+  for (int i = g.n_mat; i < 3; ++i) { g.in[i] = nullptr; g.out[i] = nullptr; }
+  g.b_in = b_up;
+  g.b_out = b_up_c;
+  g.elem = e;
+  // the down columns first: the row kernel rewrites slot_idx, which nothing below reads
+  if (down_layout == CI_DOWN_OUT_MAJOR) {
+    dim3 grid((unsigned)((K + 63) / 64), (unsigned)((d + 63) / 64));
+    if (e == 2)
+      hipLaunchKernelGGL((delta_cols_t_kernel<uint16_t>), grid, dim3(256), 0, s,
+                         reinterpret_cast<const uint16_t*>(w_down), reinterpret_cast<uint16_t*>(w_down_c),
+                         free_list, enter_list, count, (int)N, (int)d);
+    else
+      hipLaunchKernelGGL((delta_cols_t_kernel<uint32_t>), grid, dim3(256), 0, s,
+                         reinterpret_cast<const uint32_t*>(w_down), reinterpret_cast<uint32_t*>(w_down_c),
+                         free_list, enter_list, count, (int)N, (int)d);
+    CI_HIP_CHECK_LAUNCH();
+  }
+  hipLaunchKernelGGL(delta_rows_kernel, dim3((unsigned)K, g.n_mat), dim3(256), 0, s, g, free_list, enter_list,
+                     count, slot_idx, (int)(d * e / 16));
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
 
 int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                    int down_layout, int dtype, int64_t d, int64_t N, const int32_t* core_idx,

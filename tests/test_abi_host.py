@@ -101,6 +101,29 @@ def test_compact_rejects_bad_arguments_without_a_gpu(lib):
     assert r(F + 8, None, None, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_LAYOUT
 
 
+def test_compact_update_rejects_bad_arguments_without_a_gpu(lib):
+    r = lib.raw.coreinfer_compact_update
+    F = FAKE
+    big = 1 << 24
+    # (w_up, w_gate, b_up, w_down, layout, dtype, act, d, N, new_idx, K, slot_idx, w_up_c, w_gate_c, b_up_c,
+    #  w_down_c, changed, ws, ws_bytes, stream)
+    assert r(F, None, None, F, 0, 6, 0, 64, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, None, None, F, 3, 1, 0, 64, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, None, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, None, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 200, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 1, 64, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, F, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 60, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F + 2, F, None, None, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, None, None, big, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, None, F, 100, None) == lib.CI_ERR_WORKSPACE
+    n = ctypes.c_size_t(0)
+    assert lib.raw.coreinfer_compact_update_workspace_size(128, 8, ctypes.byref(n)) == lib.CI_OK
+    assert n.value >= (128 + 3 * 8 + 1) * 4
+    assert lib.raw.coreinfer_compact_update_workspace_size(128, 129, ctypes.byref(n)) == lib.CI_ERR_INVALID_ARG
+
+
 def test_ffn_decode_rejects_bad_arguments_without_a_gpu(lib):
     r = lib.raw.coreinfer_ffn_decode
     F = FAKE

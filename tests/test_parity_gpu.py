@@ -126,6 +126,43 @@ def test_compact_matches_oracle(lib, dt, act, layout, d, N, K):
         assert np.array_equal(f64(out["b_up_c"]), ref["b_up_c"])
 
 
+@pytest.mark.parametrize("dt,act,layout", [("f16", "relu", "out_major"), ("bf16", "swiglu", "out_major"),
+                                           ("f32", "relu", "neuron_major"), ("f16", "swiglu", "neuron_major")])
+@pytest.mark.parametrize("d,N,K,turnover", [(64, 200, 77, 0.3), (1024, 3000, 1201, 0.1), (256, 500, 500, 0.0),
+                                            (512, 4000, 1500, 1.0), (8, 5, 1, 1.0)])
+def test_compact_update_matches_oracle(lib, dt, act, layout, d, N, K, turnover):
+    """Two updates in a row: slot map and buffers bit-exact against the oracle's rule, decode over
+    the updated buffers against the oracle FFN of the new set."""
+    _say("compact update case", dt, act, layout, d, N, K, turnover)
+    dtype = DTYPES[dt]
+    w = rand_weights(d, N, dtype, act, layout, seed=d + N + K, device=DEV)
+    rng = np.random.default_rng(K * 3 + d)
+    S = np.sort(rng.choice(N, size=K, replace=False))
+    slot = torch.from_numpy(S.astype(np.int32)).to(DEV)
+    bufs = lib.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], layout, act, slot)
+    slot_ref = S.copy()
+    x = torch.randn(1, d, generator=torch.Generator().manual_seed(K)).to(dtype).to(DEV)
+    for step in range(2):
+        n_new = min(int(round(turnover * K)), N - K)
+        stay = rng.choice(slot_ref, size=K - n_new, replace=False)
+        fresh = rng.choice(np.setdiff1d(np.arange(N), slot_ref), size=n_new, replace=False)
+        S_new = np.sort(np.concatenate([stay, fresh]))
+        changed = lib.compact_update(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], layout, act,
+                                     torch.from_numpy(S_new.astype(np.int32)).to(DEV), slot, bufs)
+        torch.cuda.synchronize()
+        slot_ref, changed_ref = orc.compact_update_slots(slot_ref, S_new)
+        assert int(changed.item()) == changed_ref == n_new
+        assert slot.cpu().numpy().astype(np.int64).tolist() == slot_ref.tolist()
+        ref = orc.compact(slot_ref, f64(w["w_up"]), down_out_major64(w, layout), f64(w["w_gate"]), f64(w["b_up"]))
+        for key, t in bufs.items():
+            if t is not None:
+                assert np.array_equal(f64(t), ref[key]), f"{key} after update {step}"
+        desc = lib.make_weights(bufs["w_up_c"], bufs["w_gate_c"], bufs["b_up_c"], bufs["w_down_c"], w["b_down"])
+        y = lib.ffn_decode(x, desc, act)
+        torch.cuda.synchronize()
+        assert_close_rms(y[0], _oracle_ffn(act, x[0], np.sort(slot_ref), w, layout), dtype, f"decode after update {step}")
+
+
 def test_compact_flags_bad_indices_without_faulting(lib):
     d, N = 64, 100
     w = rand_weights(d, N, torch.float16, "relu", "out_major", seed=1, device=DEV)
