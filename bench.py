@@ -107,6 +107,7 @@ def main():
     dense_ws = torch.empty(ci.ffn_dense_workspace_size(B * M, d, N, dtype), dtype=torch.uint8, device=dev)
     sel_ws = torch.empty(ci.select_workspace_size(M, N), dtype=torch.uint8, device=dev)
     counts = torch.empty(N, dtype=torch.int32, device=dev)
+    counts_all = torch.empty((L, N), dtype=torch.int32, device=dev) if (B == 1 and len(cfg.betas) > 1) else None
     core_idx = torch.empty((L, B, K), dtype=torch.int32, device=dev)
     dec_ws = torch.empty(ci.ffn_decode_workspace_size(B, K, d), dtype=torch.uint8, device=dev)
     if gathered:
@@ -127,7 +128,8 @@ def main():
         ci.ffn_dense(X[l], w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], cfg.down_layout,
                      cfg.act, want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
         for s in range(B):
-            ci.select(A_buf[s * M:(s + 1) * M], cfg.alpha, beta, core_idx=core_idx[l, s], counts=counts, ws=sel_ws)
+            ci.select(A_buf[s * M:(s + 1) * M], cfg.alpha, beta, core_idx=core_idx[l, s],
+                      counts=counts if counts_all is None else counts_all[l], ws=sel_ws)
         if not gathered:
             ci.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act,
                        core_idx[l, 0], out=cbuf[l])
@@ -217,6 +219,54 @@ def main():
                              cfg.down_layout, cfg.act, want_y=True, want_a=False, Y=Yd[s:s + 1], ws=dws)
     dense_decode()
     dense_decode_ms = timed(dense_decode, reps=3)
+
+    # ------------- keep-fraction sweep: one prefill and one count set, Def. 2 + deployment + decode per beta
+    sweep = None
+    if counts_all is not None and args.beta is None:
+        sweep = []
+        cs_ws = torch.empty(256, dtype=torch.uint8, device=dev)
+        n_tok = max(1, min(T, 64))
+        for b2 in cfg.betas[1:]:
+            K2 = ci.keep_count(b2, N)
+            idx2 = torch.empty((L, K2), dtype=torch.int32, device=dev)
+            bufs2 = [{"w_up_c": torch.empty((K2, d), dtype=dtype, device=dev),
+                      "w_gate_c": torch.empty((K2, d), dtype=dtype, device=dev) if cfg.act == "swiglu" else None,
+                      "b_up_c": torch.empty((K2,), dtype=dtype, device=dev) if cfg.b_up is not None else None,
+                      "w_down_c": torch.empty((K2, d), dtype=dtype, device=dev)} for _ in range(L)]
+
+            def redeploy():
+                for l in range(L):
+                    w = weights[l]
+                    ci.count_select(counts_all[l], M, b2, core_idx=idx2[l], ws=cs_ws)
+                    ci.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act, idx2[l],
+                               out=bufs2[l])
+            redeploy()
+            redeploy_ms = timed(redeploy) / L
+            descs2 = [ci.make_weights(c["w_up_c"], c["w_gate_c"], c["b_up_c"], c["w_down_c"], w["b_down"])
+                      for c, w in zip(bufs2, weights)]
+            ws2 = torch.empty(ci.ffn_decode_workspace_size(1, K2, d), dtype=torch.uint8, device=dev)
+
+            def layers2():
+                for l in range(L):
+                    ci.ffn_decode(x_cur[l], descs2[l], cfg.act, y=y_out[l], ws=ws2)
+            layers2()
+            torch.cuda.synchronize()
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                layers2()
+            torch.cuda.synchronize()
+
+            def tokens2():
+                for t in range(n_tok):
+                    x_cur.copy_(x_all[t])
+                    g2.replay()
+            tokens2()
+            tok_ms = timed(tokens2) / n_tok
+            bytes2 = cfg.n_mat * K2 * d * e + (K2 * e if cfg.b_up is not None else 0) + 2 * d * e
+            sweep.append({"beta": b2, "core_neurons": K2, "tokens_per_s": 1.0 / (tok_ms * 1e-3),
+                          "decode_hbm_gbps_whole_phase": bytes2 * L / (tok_ms * 1e-3) / 1e9,
+                          "count_select_plus_compact_us_per_layer": redeploy_ms * 1e3, "decode_tokens_timed": n_tok})
+            del g2, bufs2, descs2, idx2, ws2
 
     # --------------------- several sentences: the same decode through the union of their core sets
     # (a different algorithm from the gathered decode that `value` reports: every union row is read
@@ -366,6 +416,7 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS,
                      "traffic": traffic, "bytes_per_launch": bytes_per_launch,
                      "us_per_launch": kernel_ms * 1e3},
+        "beta_sweep": sweep,
         "union_batched_decode": union,
         "cpu_baseline": cpu,
         "parity": parity,
