@@ -74,18 +74,24 @@ int coreinfer_version(void);
 
 /*
  * Development knob for tuning sweeps, never needed for correct use: overrides
- * a launch-shape parameter process-wide.  Names: "decode_wgs_per_cu" (1..16), "decode_wgs" (0 = use the per-CU rule,
- * else the number of neuron slices per sentence, up to 1024),
- * "decode_threads" (0 = derive from d, else a multiple of 64 up to 1024),
- * "decode_depth" (4, 8 or 16 weight rows in flight per thread), "reduce_cq"
- * (4, 8, 16 column quads per reduction workgroup), "decode_nt_store" (0/1),
- * "select_wgs_per_cu" (1..8), "select_debug" (timing only: 1 stops after the
- * per-token phase, 2 after the ticket; core_idx is then NOT written),
- * "gemv_wgs_per_cu" (1..32), "gemm_ring" (0/1), "decode_skip_reduce"
- * (0/1; 1 launches only the first decode kernel so that it can be timed
- * alone -- y is then NOT written).  Unknown name or value out of range:
- * CI_ERR_INVALID_ARG.  Not thread-safe against running
- * calls.
+ * a launch-shape parameter process-wide.  Names:
+ *   "decode_wgs_per_cu" (1..16), "decode_wgs" (0 = use the per-CU rule, else
+ *   the number of neuron slices per sentence, up to 1024), "decode_threads"
+ *   (0 = derive from d, else a multiple of 64 up to 1024), "decode_depth" (4, 8
+ *   or 16 weight rows in flight per thread), "reduce_cq" (4, 8, 16 column quads
+ *   per reduction workgroup), "decode_nt_store" (0/1), "decode_skip_reduce"
+ *   (0/1; 1 launches only the first decode kernel so that it can be timed
+ *   alone -- y is then NOT written);
+ *   "select_wgs_per_cu" (1..8), "select_debug" (timing only: 1 stops after the
+ *   per-token phase, 2 after the ticket; core_idx is then NOT written);
+ *   "gemv_wgs_per_cu" (1..32), "gemm_ring" (0/1: register-ring GEMM kernels),
+ *   "gemm_big" (0 never, 1 when the grid is large enough, 2 whenever the shape
+ *   divides: the 256 x 256-tile GEMM kernel);
+ *   "union_depth" (8, 16), "union_down_threads" (64..512), "union_up_wgs_per_cu"
+ *   (1..8), "union_down_wgs_per_cu" (1..16): union-batched decode.
+ * Unknown name or value out of range: CI_ERR_INVALID_ARG.  Not thread-safe
+ * against running calls; a workspace size must be queried under the setting
+ * the call will run with.
  */
 int coreinfer_set_param(const char* name, int value);
 
