@@ -282,7 +282,7 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   if (c < d) {
     const float* p = partial + (size_t)b * n_wg * d + c;
-#pragma unroll 4
+#pragma unroll 8
     for (int w = ty; w < n_wg; w += G) {
       const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + (size_t)w * d));
       s.x += u2f(t[0]); s.y += u2f(t[1]); s.z += u2f(t[2]); s.w += u2f(t[3]);
