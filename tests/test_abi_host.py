@@ -269,3 +269,24 @@ def test_workloads_module_has_the_five_configurations():
     assert w["w_up"].shape == (128, 64) and w["w_down"].shape == (64, 128) and w["w_gate"] is None
     again = wl.layer_weights(small, 0)
     assert (w["w_up"] == again["w_up"]).all()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_bench_line_fields_are_built_from_the_documented_pieces():
+    """The traffic note is only used for the launch size it was measured at."""
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    assert bench.read_traffic_note("opt6.7b_relu_f16", 107410228) is not None
+    assert bench.read_traffic_note("opt6.7b_relu_f16", 2 * 107410228) is None
+    assert bench.read_traffic_note("no_such_workload", 1) is None
