@@ -136,15 +136,16 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld,
  * that decides how the set is updated but does not specify it; Eq. 3 is a sum
  * over tokens, so counts of new tokens simply add to the old ones):
  *   coreinfer_count_tokens  steps 1-2 of coreinfer_select over the M rows of
- *                           act; counts [N] is cleared first unless
- *                           accumulate != 0, in which case it is added to.
+ *                           act; counts [N] is overwritten unless
+ *                           accumulate != 0, in which case it is added to;
+ *                           ws: coreinfer_select_workspace_size(M, N) bytes.
  *   coreinfer_count_select  step 3 on given counts (every value must lie in
  *                           [0, max_count], max_count <= CI_MAX_TOKENS);
  *                           core_idx [keep_count(beta, N)] ascending;
  *                           ws: at least 256 bytes.
  */
 int coreinfer_count_tokens(const float* act, int64_t M, int64_t N, int64_t ld, double alpha,
-                           int32_t* counts, int accumulate, void* stream);
+                           int32_t* counts, int accumulate, void* ws, size_t ws_bytes, void* stream);
 int coreinfer_count_select(const int32_t* counts, int64_t N, int64_t max_count, double beta,
                            int32_t* core_idx, void* ws, size_t ws_bytes, void* stream);
 

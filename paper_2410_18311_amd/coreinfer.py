@@ -54,7 +54,7 @@ _SIGNATURES = {
     "coreinfer_keep_count": (_int, [_dbl, _i64, ctypes.POINTER(_i64)]),
     "coreinfer_select_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
-    "coreinfer_count_tokens": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _int, _vp]),
+    "coreinfer_count_tokens": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _int, _vp, _sz, _vp]),
     "coreinfer_count_select": (_int, [_vp, _i64, _i64, _dbl, _vp, _vp, _sz, _vp]),
     "coreinfer_group_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_core_similarity": (_int, [_vp, _i64, _vp, _i64, _vp, _vp]),
@@ -150,15 +150,18 @@ def select(act: torch.Tensor, alpha: float, beta: float, core_idx: Optional[torc
 
 
 def count_tokens(act: torch.Tensor, alpha: float, counts: Optional[torch.Tensor] = None,
-                 accumulate: bool = False) -> torch.Tensor:
+                 accumulate: bool = False, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
     """coreinfer_count_tokens: Eq. 3 over the rows of act, optionally added to existing counts."""
     assert act.dim() == 2 and act.dtype == torch.float32 and act.stride(1) == 1
     M, N = act.shape
     if counts is None:
         assert not accumulate
         counts = torch.empty(N, dtype=torch.int32, device=act.device)
+    if ws is None:
+        ws = _workspace(select_workspace_size(M, N), act)
     _check(_lib.coreinfer_count_tokens(_ptr(act), M, N, act.stride(0), float(alpha), _ptr(counts),
-                                       1 if accumulate else 0, _stream(act)), "coreinfer_count_tokens")
+                                       1 if accumulate else 0, _ptr(ws), ws.numel(), _stream(act)),
+           "coreinfer_count_tokens")
     return counts
 
 

@@ -106,9 +106,20 @@ int coreinfer_keep_count(double frac, int64_t n, int64_t* k) {
 
 int coreinfer_select_workspace_size(int64_t M, int64_t N, size_t* bytes) {
   if (!bytes || M < 1 || M > CI_MAX_TOKENS || N < 1 || N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
-  *bytes = round256((size_t)N * sizeof(int32_t)) + 256;
+  SelectWs w;
+  select_ws_layout(M, N, &w);
+  *bytes = w.total;
   return CI_OK;
 }
+
+namespace {
+// counters inside the workspace, for callers that pass none
+int32_t* ws_counts(void* ws, int64_t M, int64_t N) {
+  SelectWs w;
+  select_ws_layout(M, N, &w);
+  return reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + w.off_counts);
+}
+}  // namespace
 
 int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld, double alpha, double beta,
                      int32_t* core_idx, int32_t* counts, void* ws, size_t ws_bytes, void* stream) {
@@ -123,22 +134,24 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld, double 
     return CI_ERR_BAD_LAYOUT;
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
-  // workspace: [N] counters (used when the caller passes none), then the ticket word
-  int32_t* cnt = counts ? counts : reinterpret_cast<int32_t*>(ws);
-  uint32_t* ticket = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(ws) + round256((size_t)N * sizeof(int32_t)));
-  return launch_select(act, M, N, ld, qa, keep(qb, N), M, core_idx, cnt, ticket,
-                       kSelZero | kSelTokens | kSelFinal, (hipStream_t)stream);
+  int32_t* cnt = counts ? counts : ws_counts(ws, M, N);
+  return launch_select(act, M, N, ld, qa, keep(qb, N), M, core_idx, cnt, ws, kSelTokens | kSelFinal,
+                       (hipStream_t)stream);
 }
 
 int coreinfer_count_tokens(const float* act, int64_t M, int64_t N, int64_t ld, double alpha,
-                           int32_t* counts, int accumulate, void* stream) {
-  if (!act || !counts || M < 1 || M > CI_MAX_TOKENS || N < 1 || N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+                           int32_t* counts, int accumulate, void* ws, size_t ws_bytes, void* stream) {
+  size_t need = 0;
+  if (coreinfer_select_workspace_size(M, N, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!act || !counts) return CI_ERR_INVALID_ARG;
   const int64_t qa = fraction_ppm(alpha);
   if (qa == 0) return CI_ERR_INVALID_ARG;
   if (ld < N) return CI_ERR_BAD_LAYOUT;
   if ((reinterpret_cast<uintptr_t>(act) & 3u) || (reinterpret_cast<uintptr_t>(counts) & 3u)) return CI_ERR_BAD_LAYOUT;
-  return launch_select(act, M, N, ld, qa, 1, M, nullptr, counts, nullptr,
-                       (accumulate ? 0 : kSelZero) | kSelTokens, (hipStream_t)stream);
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
+  return launch_select(act, M, N, ld, qa, 1, M, nullptr, counts, ws,
+                       kSelTokens | (accumulate ? kSelAccumulate : 0), (hipStream_t)stream);
 }
 
 int coreinfer_count_select(const int32_t* counts, int64_t N, int64_t max_count, double beta,
@@ -150,8 +163,9 @@ int coreinfer_count_select(const int32_t* counts, int64_t N, int64_t max_count, 
   if ((reinterpret_cast<uintptr_t>(counts) & 3u) || (reinterpret_cast<uintptr_t>(core_idx) & 3u)) return CI_ERR_BAD_LAYOUT;
   if (!ws || ws_bytes < 256) return CI_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
+  // Def. 2 alone runs in one workgroup and needs no scratch
   return launch_select(nullptr, 0, N, N, 1, keep(qb, N), max_count, core_idx, const_cast<int32_t*>(counts),
-                       reinterpret_cast<uint32_t*>(ws), kSelFinal, (hipStream_t)stream);
+                       nullptr, kSelFinal, (hipStream_t)stream);
 }
 
 int coreinfer_group_select(const int32_t* core_sets, int64_t G, int64_t K, int64_t N, double gamma,
@@ -166,15 +180,14 @@ int coreinfer_group_select(const int32_t* core_sets, int64_t G, int64_t K, int64
     return CI_ERR_BAD_LAYOUT;
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
-  int32_t* cnt = counts ? counts : reinterpret_cast<int32_t*>(ws);
-  uint32_t* ticket = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(ws) + round256((size_t)N * sizeof(int32_t)));
+  int32_t* cnt = counts ? counts : ws_counts(ws, G, N);
   hipStream_t s = (hipStream_t)stream;
   // clear the counters, count the groups' members, then Def. 2 with gamma on the counters
-  int rc = launch_select(nullptr, 0, N, N, 1, 1, G, nullptr, cnt, ticket, kSelZero, s);
+  int rc = launch_select(nullptr, 0, N, N, 1, 1, G, nullptr, cnt, nullptr, kSelZero, s);
   if (rc != CI_OK) return rc;
   rc = launch_scatter_count(core_sets, G * K, N, cnt, s);
   if (rc != CI_OK) return rc;
-  return launch_select(nullptr, 0, N, N, 1, keep(qg, N), G, core_idx, cnt, ticket, kSelFinal, s);
+  return launch_select(nullptr, 0, N, N, 1, keep(qg, N), G, core_idx, cnt, nullptr, kSelFinal, s);
 }
 
 int coreinfer_core_similarity(const int32_t* set_a, int64_t Ka, const int32_t* set_b, int64_t Kb,

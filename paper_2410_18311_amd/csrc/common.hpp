@@ -137,9 +137,14 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
   } while (0)
 
 // ---- launchers (one per translation unit) ----------------------------------
-enum { kSelZero = 1, kSelTokens = 2, kSelFinal = 4 };
+enum { kSelZero = 1, kSelTokens = 2, kSelFinal = 4, kSelAccumulate = 8 };
+struct SelectWs {
+  size_t off_thr, off_ticket, off_counts, total;
+};
+void select_ws_layout(int64_t M, int64_t N, SelectWs* w);
+// ws: laid out by select_ws_layout (may be null when only kSelZero is asked for)
 int launch_select(const float* act, int64_t M, int64_t N, int64_t ld, int64_t q_alpha, int64_t K,
-                  int64_t max_count, int32_t* core_idx, int32_t* counts, uint32_t* ticket, int what,
+                  int64_t max_count, int32_t* core_idx, int32_t* counts, void* ws, int what,
                   hipStream_t s);
 int launch_scatter_count(const int32_t* idx, int64_t n_idx, int64_t N, int32_t* counts, hipStream_t s);
 int launch_similarity(const int32_t* a, int64_t Ka, const int32_t* b, int64_t Kb, int32_t* out, hipStream_t s);

@@ -1,27 +1,30 @@
-// Sentence-wise core neuron selection (Sec. 3.1 of arXiv 2410.18311).
+// Sentence-wise core neuron selection (Sec. 3.1 of arXiv 2410.18311), two
+// launches per sentence and layer, no floating-point or counter atomics:
 //
-// select_kernel, one launch per sentence and layer:
-//   * Def. 1 / Eq. 1 and Eq. 3.  One workgroup per prompt token (looping when
-//     M exceeds the grid).  The token's N activations become integer keys
-//     (the IEEE bits of a positive float are monotone in its value;
-//     everything that is not > 0 becomes key 0), loaded once and kept in
+// token_threshold_kernel -- Def. 1 / Eq. 1.  One workgroup per prompt token
+//     (looping when M exceeds the grid).  The token's N activations become
+//     integer keys (the IEEE bits of a positive float are monotone in its
+//     value; everything that is not > 0 becomes key 0), loaded once and kept in
 //     registers.  A three-pass most-significant-digit radix select (11 + 11 +
 //     9 bits) over LDS histograms finds the value T of the k-th largest key,
 //     k being the share alpha of the positive keys.  The histograms are
 //     replicated eight times by lane so that activations sharing an exponent
 //     do not serialise on one LDS address.  Keys > T are token-wise core
-//     neurons; of the keys == T the lowest indices fill the remaining places
-//     (ordered ballot / popcount prefix; skipped when all of them are taken).
-//     Each chosen neuron's counter is incremented: in an LDS-private
-//     packed-u16 histogram when the workgroup sees several tokens (flushed
-//     once with integer atomics), else directly in global memory.  Integer
-//     adds commute, so the counts do not depend on scheduling.
-//   * Def. 2 / Eq. 2.  The workgroup that finishes last (a ticket taken after a
-//     device-scope fence) selects the K neurons first in the order (count
-//     descending, index ascending): threshold count by a two-pass radix select
-//     over the counts (<= 65535), then a ballot-based ordered compaction that
+//     neurons; of the keys == T the lowest indices fill the remaining places:
+//     an ordered ballot / popcount prefix finds the index `cut` of the last tie
+//     that is taken (skipped when all of them are).  The token's result is the
+//     pair (T, cut): neuron n is in its core set iff key > T or (key == T and
+//     n <= cut).
+// count_final_kernel -- Eq. 3 and Def. 2.  Counting is a second pass over the
+//     activations by neuron: a workgroup owns 256 neurons and a share of the
+//     tokens, compares every activation with its token's (T, cut) and keeps the
+//     tallies in registers -- no atomics on the counters, and the counts are
+//     the same whatever the scheduling.  Partial tallies go to the workspace;
+//     the workgroup that finishes last (a ticket taken after a device-scope
+//     fence) adds them up, writes the counts, and selects the K neurons first
+//     in the order (count descending, index ascending): threshold count by a
+//     radix select over the counts (<= 65535), then an ordered compaction that
 //     writes S ascending: position = #greater before + min(#equal before, need).
-// zero_i32_kernel clears the counters and the ticket beforehand.
 #include "common.hpp"
 
 namespace ci {
@@ -142,41 +145,40 @@ __device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, 
 }
 
 template <int ITEMS>
-__global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ act, int M, int N,
-                                                      int64_t ld, int64_t q_alpha, int K,
-                                                      int32_t* counts, int32_t* core_idx,
-                                                      uint32_t* ticket, int privatise, int max_count,
-                                                      int debug) {
+__global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __restrict__ act, int M, int N,
+                                                               int64_t ld, int64_t q_alpha,
+                                                               uint32_t* __restrict__ thr,
+                                                               uint32_t* ticket) {
   __shared__ SelShared sh;
-  extern __shared__ uint32_t dyn[];  // [kHistWords] histograms, then [ceil(N/2)] packed u16 counters
+  __shared__ uint32_t cut_s;
+  extern __shared__ uint32_t dyn[];  // [kHistWords] histograms
   uint32_t* hist = dyn;
-  uint32_t* lcount = dyn + kHistWords;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int n_iter = (N + nt - 1) / nt;
-  const int npair = (N + 1) / 2;
+  if (ticket && blockIdx.x == 0 && tid == 0) *ticket = 0u;  // for the counting launch that follows
 
-  if (privatise) {
-    for (int j = tid; j < npair; j += nt) lcount[j] = 0;
-    __syncthreads();
-  }
-
-  // ------------------------------------------------ Def. 1 / Eq. 1, Eq. 3 ----
   for (int m = blockIdx.x; m < M; m += gridDim.x) {
     const float* row = act + (size_t)m * ld;
     uint32_t kc[ITEMS > 0 ? ITEMS : 1];
     uint32_t npos = 0;
     if (ITEMS > 0) {
-      float av[ITEMS > 0 ? ITEMS : 1];
+      // branch-free loads, issued back to back in batches (a batch bounds the registers that hold
+      // values not yet turned into keys)
+      constexpr int BATCH = ITEMS > 16 ? 8 : (ITEMS > 0 ? ITEMS : 1);
 #pragma unroll
-      for (int i = 0; i < ITEMS; ++i) {  // branch-free: all loads are issued back to back
-        const int e = i * nt + tid;
-        av[i] = row[e < N ? e : N - 1];
-      }
+      for (int i0 = 0; i0 < ITEMS; i0 += BATCH) {
+        float av[BATCH];
 #pragma unroll
-      for (int i = 0; i < ITEMS; ++i) {
-        const int e = i * nt + tid;
-        kc[i] = (e < N && av[i] > 0.f) ? f2u(av[i]) : 0u;
+        for (int j = 0; j < BATCH; ++j) {
+          const int e = (i0 + j) * nt + tid;
+          av[j] = row[e < N ? e : N - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) {
+          const int e = (i0 + j) * nt + tid;
+          kc[i0 + j] = (e < N && av[j] > 0.f) ? f2u(av[j]) : 0u;
+        }
       }
 #pragma unroll
       for (int i = 0; i < ITEMS; ++i) npos += wave_count(kc[i] != 0);
@@ -195,7 +197,6 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
       return (a > 0.f) ? f2u(a) : 0u;
     };
     // for the histogram passes a zero key must match no prefix: map it to all-ones
-    // (bit 31 set, which no prefix mask ever covers with a zero prefix... see radix_pass use)
     auto key_sel = [&](int i) -> uint32_t {
       const uint32_t key = key_at(i);
       return key != 0 ? key : 0xffffffffu;
@@ -203,7 +204,10 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
 
     const uint32_t P = block_sum_waves(npos, &sh);
     const uint32_t k = (uint32_t)((q_alpha * (int64_t)P + 999999) / 1000000);  // share of the positives
-    if (k == 0) continue;  // uniform: no positive activation
+    if (k == 0) {  // uniform: no positive activation, nothing is selected (no key exceeds all-ones)
+      if (tid == 0) { thr[2 * m] = 0xffffffffu; thr[2 * m + 1] = 0u; }
+      continue;
+    }
 
     // 31-bit keys: digits of 11, 11 and 9 bits.  Bit 31 is part of the mask from the start,
     // so the all-ones stand-in of a zero key never matches.
@@ -213,72 +217,137 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
     radix_pass<ITEMS>(key_sel, n_iter, 0, 512, hist, &sh, prefix, prefix_mask, need, n_eq);
     const uint32_t T = prefix;  // the k-th largest key; `need` of the n_eq keys == T are in the top k
 
-    auto bump = [&](int e) {
-      if (privatise) atomicAdd(&lcount[e >> 1], 1u << (16 * (e & 1)));
-      else atomicAdd(&counts[e], 1);
-    };
-
-    const bool all_ties = (need == n_eq);  // uniform
-    uint32_t base = 0;                      // ties seen in earlier iterations
-    for_items<ITEMS>(n_iter, [&](int i) {
-      const uint32_t key = key_at(i);  // T >= 1, so elements past the end (key 0) never match
-      const int e = i * nt + tid;
-      if (key > T) bump(e);
-      if (all_ties) {
-        if (key == T) bump(e);
-      } else if (base < need) {  // uniform condition
-        // index order = iteration, then wave, then lane
-        const bool tie = key == T;
-        const uint64_t bal = __ballot(tie);
-        __syncthreads();
-        if (lane == 0) sh.wave_tot[wave] = (uint32_t)__popcll(bal);
-        __syncthreads();
-        uint32_t before = base, tot = 0;
-        for (int w = 0; w < nw; ++w) {
-          const uint32_t c = sh.wave_tot[w];
-          if (w < wave) before += c;
-          tot += c;
+    // index of the last tie that is taken; ties in index order = iteration, then wave, then lane
+    if (tid == 0) cut_s = 0x7fffffffu;  // all ties taken (the usual case: need == n_eq)
+    if (need != n_eq) {                 // uniform
+      uint32_t base = 0;                // ties seen in earlier iterations
+      for_items<ITEMS>(n_iter, [&](int i) {
+        if (base < need) {  // uniform condition
+          const bool tie = key_at(i) == T;  // T >= 1, so elements past the end (key 0) never match
+          const uint64_t bal = __ballot(tie);
+          __syncthreads();
+          if (lane == 0) sh.wave_tot[wave] = (uint32_t)__popcll(bal);
+          __syncthreads();
+          uint32_t before = base, tot = 0;
+          for (int w = 0; w < nw; ++w) {
+            const uint32_t c = sh.wave_tot[w];
+            if (w < wave) before += c;
+            tot += c;
+          }
+          const uint32_t rank = before + (uint32_t)__popcll(bal & lanemask_lt());
+          if (tie && rank == need - 1) cut_s = (uint32_t)(i * nt + tid);
+          base += tot;
         }
-        const uint32_t rank = before + (uint32_t)__popcll(bal & lanemask_lt());
-        if (tie && rank < need) bump(e);
-        base += tot;
-      }
-    });
+      });
+    }
     __syncthreads();
+    if (tid == 0) { thr[2 * m] = T; thr[2 * m + 1] = cut_s; }
+    __syncthreads();  // cut_s and the histograms are reused by the next token
   }
+}
 
-  if (privatise) {
+// Tallies of one lane's four neurons n0 .. n0+3 over the tokens wave, wave + nw, ... (UN at a time
+// in flight: the pass is latency-bound, it has few workgroups).  VEC: one 16-byte load per token,
+// else four clamped 4-byte loads (unaligned rows or the last neurons of the layer).
+template <bool VEC>
+__device__ __forceinline__ void count_tokens_of_lane(const float* __restrict__ act, int64_t ld,
+                                                     const uint32_t* __restrict__ thr, int M, int N,
+                                                     int n0, int wave, int nw, uint32_t (&cnt)[4]) {
+  constexpr int UN = 8;
+  for (int m0 = wave * UN; m0 < M; m0 += nw * UN) {
+    float v[UN][4];
+    uint32_t T[UN], cut[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int m = min(m0 + u, M - 1);  // clamped: a repeated token is masked below
+      const float* p = act + (size_t)m * ld;
+      if (VEC) {
+        const float4 q = *reinterpret_cast<const float4*>(p + n0);
+        v[u][0] = q.x; v[u][1] = q.y; v[u][2] = q.z; v[u][3] = q.w;
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[u][c] = p[min(n0 + c, N - 1)];
+      }
+      T[u] = thr[2 * m];
+      cut[u] = thr[2 * m + 1];
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      if (m0 + u < M) {  // uniform per wave
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const uint32_t key = (n0 + c < N && v[u][c] > 0.f) ? f2u(v[u][c]) : 0u;
+          cnt[c] += (key > T[u] || (key == T[u] && (uint32_t)(n0 + c) <= cut[u])) ? 1u : 0u;
+        }
+      }
+    }
+  }
+}
+
+// What count_final_kernel does, individually switchable.
+enum { kDoCount = 1, kDoFinal = 2, kAccumulate = 4 };
+
+template <int ITEMS>
+__global__ __launch_bounds__(1024) void count_final_kernel(const float* __restrict__ act, int M, int N,
+                                                           int64_t ld, const uint32_t* __restrict__ thr,
+                                                           int vec_ok, int32_t* counts, int K,
+                                                           int32_t* core_idx, uint32_t* ticket,
+                                                           int max_count, int what, int debug) {
+  __shared__ SelShared sh;
+  extern __shared__ uint32_t dyn[];  // counting: [1024] block tallies; Def. 2: [kHistWords] histograms
+  uint32_t* hist = dyn;
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+  const int n_iter = (N + nt - 1) / nt;
+
+  // ------------------------------------------------ Eq. 3 ---------------------
+  if (what & kDoCount) {
+    const int nb = blockIdx.x;
+    const int n0 = nb * 256 + lane * 4;  // this lane's four neurons
+    for (int j = tid; j < 256; j += nt) dyn[j] = 0;
     __syncthreads();
-    for (int j = tid; j < npair; j += nt) {
-      const uint32_t v = lcount[j];
-      if (v & 0xffffu) atomicAdd(&counts[2 * j], (int)(v & 0xffffu));
-      if (v >> 16) atomicAdd(&counts[2 * j + 1], (int)(v >> 16));
+    uint32_t cnt[4] = {0, 0, 0, 0};
+    if (vec_ok && n0 + 3 < N) count_tokens_of_lane<true>(act, ld, thr, M, N, n0, wave, nw, cnt);
+    else count_tokens_of_lane<false>(act, ld, thr, M, N, n0, wave, nw, cnt);
+    // block tallies: integer adds in LDS (commutative), then one plain store per neuron
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (cnt[c]) atomicAdd(&dyn[lane * 4 + c], cnt[c]);
+    __syncthreads();
+    const bool acc = (what & kAccumulate) != 0;
+    for (int j = tid; j < 256; j += nt) {
+      const int n = nb * 256 + j;
+      if (n < N) counts[n] = (int32_t)dyn[j] + (acc ? counts[n] : 0);
     }
   }
 
   // ------------------------------------------------ Def. 2 / Eq. 2 -----------
-  // The last workgroup to arrive sees every counter update: each workgroup's
-  // atomics are complete (device-scope fence) before it takes its ticket.
+  // The workgroup that finishes last sees every count: each workgroup's stores are complete
+  // (per-wave wait, barrier, one device-scope fence) before it takes its ticket.  Same-address
+  // tickets cost about 25-50 ns each, one reason why the counting pass uses few, wide workgroups.
   if (debug & 1) return;
-  // Every wave first waits until its own counter updates have been performed (vmcnt(0)); the
-  // barrier orders them before thread 0, whose single device-scope fence then publishes the
-  // workgroup's updates before the ticket is taken.  (A fence in every wave costs far more.)
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-  __syncthreads();
-  if (tid == 0) {
+  if (what & kDoCount) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (tid == 0) {
+      __threadfence();
+      sh.ticket = atomicAdd(ticket, 1u);
+    }
+    __syncthreads();
+    if (sh.ticket != gridDim.x - 1) return;
     __threadfence();
-    sh.ticket = atomicAdd(ticket, 1u);
   }
-  __syncthreads();
-  if (sh.ticket != gridDim.x - 1) return;
-  __threadfence();
   if (debug & 2) return;
+  if (!(what & kDoFinal)) return;  // counts only (running form of Eq. 3)
+
+  // Plain loads: the fence above (acquire at device scope) has dropped this CU's stale lines, and
+  // plain loads can all be in flight at once.
+  auto total_count = [&](int e) -> uint32_t { return (uint32_t)counts[e]; };
 
   uint32_t cc[ITEMS > 0 ? ITEMS : 1];
   auto load_count = [&](int i) -> uint32_t {  // past the end: element N-1, masked by the callers
     const int e = i * nt + tid;
-    return (uint32_t)__hip_atomic_load(&counts[e < N ? e : N - 1], __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+    return total_count(e < N ? e : N - 1);
   };
   if (ITEMS > 0) {
 #pragma unroll
@@ -294,32 +363,37 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
     return valid ? c : 0xffffffffu;
   };
 
-  // counts are <= max_count <= 65535: two 8-bit digits; the high one is skipped below 256
+  // counts are <= max_count <= 65535: one digit of 8 or 11 bits when they stay below 256 or 2048
+  // (every prompt length of the workloads), else an 8-bit digit on top of an 8-bit one
   uint32_t prefix = 0, prefix_mask = 0xffff0000u, need = (uint32_t)K, n_eq = 0;
-  if (max_count >= 256) radix_pass<ITEMS>(ckey_sel, n_iter, 8, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
-  else prefix_mask |= 0xff00u;
-  radix_pass<ITEMS>(ckey_sel, n_iter, 0, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
+  if (max_count < 256) {
+    prefix_mask |= 0xff00u;
+    radix_pass<ITEMS>(ckey_sel, n_iter, 0, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
+  } else if (max_count < 2048) {
+    prefix_mask |= 0xf800u;
+    radix_pass<ITEMS>(ckey_sel, n_iter, 0, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
+  } else {
+    radix_pass<ITEMS>(ckey_sel, n_iter, 8, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
+    radix_pass<ITEMS>(ckey_sel, n_iter, 0, 256, hist, &sh, prefix, prefix_mask, need, n_eq);
+  }
   const uint32_t T = prefix;
 
   // ordered compaction.  pos = (#greater before) + min(#equal before, need), "before" in index
   // order = iteration, then wave, then lane.
   if constexpr (ITEMS > 0) {
-    // tallies per (iteration, wave) go to a table, one wave scans it, then every thread
-    // places its elements: three barriers in all
+    // tallies per (iteration, wave) go to a table, one wave scans it, then every thread places its
+    // elements (the ballots are taken again rather than kept): three barriers in all
     uint32_t* tab = hist;  // [n_iter * nw], (#greater << 16) | #equal, each <= 64 before the scan
-    uint64_t bgs[ITEMS], bes[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
       bool valid;
       const uint32_t key = ckey_valid(i, valid);
-      bgs[i] = __ballot(valid && key > T);
-      bes[i] = __ballot(valid && key == T);
-      if (lane == 0 && i < n_iter) tab[i * nw + wave] = ((uint32_t)__popcll(bgs[i]) << 16) | (uint32_t)__popcll(bes[i]);
+      const uint64_t bg = __ballot(valid && key > T), be = __ballot(valid && key == T);
+      if (lane == 0 && i < n_iter) tab[i * nw + wave] = ((uint32_t)__popcll(bg) << 16) | (uint32_t)__popcll(be);
     }
     __syncthreads();
     if (wave == 0) {
-      // exclusive scan of the n_iter * nw entries; the two 16-bit fields cannot overflow into
-      // each other because N <= 16 * 1024 here (#equal < 65536 is needed: it is <= N)
+      // exclusive scan of the n_iter * nw entries (the running sums are kept in full 32 bits)
       const int n_ent = n_iter * nw;
       const int per = (n_ent + 63) / 64;
       uint32_t g_sum = 0, e_sum = 0;
@@ -334,7 +408,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
         if (lane >= off) { g_inc += og; e_inc += oe; }
       }
       uint32_t g_run = g_inc - g_sum, e_run = e_inc - e_sum;
-      uint32_t* gtab = tab + n_ent;  // exclusive #greater / #equal prefixes, full 32 bits each
+      uint32_t* gtab = tab + n_ent;  // exclusive #greater / #equal prefixes
       uint32_t* etab = gtab + n_ent;
       for (int j = 0; j < per; ++j) {
         const int idx = lane * per + j;
@@ -353,9 +427,12 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
       if (i < n_iter) {
-        const bool isg = (bgs[i] >> lane) & 1, ise = (bes[i] >> lane) & 1;
-        const uint32_t g_before = gtab[i * nw + wave] + (uint32_t)__popcll(bgs[i] & lanemask_lt());
-        const uint32_t e_before = etab[i * nw + wave] + (uint32_t)__popcll(bes[i] & lanemask_lt());
+        bool valid;
+        const uint32_t key = ckey_valid(i, valid);
+        const bool isg = valid && key > T, ise = valid && key == T;
+        const uint64_t bg = __ballot(isg), be = __ballot(ise);
+        const uint32_t g_before = gtab[i * nw + wave] + (uint32_t)__popcll(bg & lanemask_lt());
+        const uint32_t e_before = etab[i * nw + wave] + (uint32_t)__popcll(be & lanemask_lt());
         const uint32_t pos = g_before + (e_before < need ? e_before : need);
         if (isg || (ise && e_before < need)) core_idx[pos] = i * nt + tid;
       }
@@ -466,64 +543,107 @@ __global__ __launch_bounds__(1024) void best_group_kernel(const int32_t* __restr
 }
 
 template <int ITEMS>
-int launch_sel(const float* act, int M, int N, int64_t ld, int64_t q_alpha, int K, int32_t* counts,
-               int32_t* core_idx, uint32_t* ticket, int grid, int nt, int privatise, size_t lds,
-               int max_count, int stop, hipStream_t s) {
+int launch_threshold(const float* act, int M, int N, int64_t ld, int64_t q_alpha, uint32_t* thr,
+                     uint32_t* ticket, int grid, int nt, hipStream_t s) {
   static bool attr_done = false;  // raise the dynamic-LDS ceiling once (64 KB by default)
   if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<ITEMS>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024) != hipSuccess)
       return CI_ERR_HIP;
     attr_done = true;
   }
-  hipLaunchKernelGGL((select_kernel<ITEMS>), dim3(grid), dim3(nt), lds, s, act, M, N, ld, q_alpha, K,
-                     counts, core_idx, ticket, privatise, max_count, stop);
+  hipLaunchKernelGGL((token_threshold_kernel<ITEMS>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act, M,
+                     N, ld, q_alpha, thr, ticket);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
 
+template <int ITEMS>
+int launch_count_final(const float* act, int M, int N, int64_t ld, const uint32_t* thr, int vec_ok,
+                       int32_t* counts, int K, int32_t* core_idx, uint32_t* ticket, int max_count, int what,
+                       int debug, int grid, int nt, hipStream_t s) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&count_final_kernel<ITEMS>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024) != hipSuccess)
+      return CI_ERR_HIP;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((count_final_kernel<ITEMS>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act, M, N,
+                     ld, thr, vec_ok, counts, K, core_idx, ticket, max_count, what, debug);
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
+
+size_t round256z(size_t n) { return (n + 255) / 256 * 256; }
+
 }  // namespace
 
-// The three stages of the selection, individually switchable:
-//   kSelZero   clear the counters (else they are accumulated into: Eq. 3 is a sum over tokens)
-//   kSelTokens Def. 1 + Eq. 3 over the M rows of act
-//   kSelFinal  Def. 2 on the counters (values <= max_count)
+// Workspace of one selection: per-token (T, cut) pairs, the ticket word, and
+// counters for callers that pass none.
+void select_ws_layout(int64_t M, int64_t N, SelectWs* w) {
+  w->off_thr = 0;
+  w->off_ticket = round256z((size_t)(M > 0 ? M : 1) * 2 * sizeof(uint32_t));
+  w->off_counts = w->off_ticket + 256;
+  w->total = w->off_counts + round256z((size_t)N * sizeof(int32_t));
+}
+
+// The stages of the selection, individually switchable:
+//   kSelZero       clear the counters (before members are scattered into them)
+//   kSelTokens     Def. 1 over the M rows of act, then Eq. 3 (kSelAccumulate: added to the counters)
+//   kSelFinal      Def. 2 on the counters (values <= max_count)
 int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_t q_alpha,
-                  int64_t K64, int64_t max_count, int32_t* core_idx, int32_t* counts,
-                  uint32_t* ticket, int what, hipStream_t s) {
+                  int64_t K64, int64_t max_count, int32_t* core_idx, int32_t* counts, void* ws,
+                  int what, hipStream_t s) {
   const int M = (what & kSelTokens) ? (int)M64 : 0, N = (int)N64, K = (int)K64;
   DeviceInfo di;
   int rc = device_info(&di);
   if (rc != CI_OK) return rc;
 
-  if ((what & kSelZero) || (what & kSelFinal)) {
-    const int nz = (what & kSelZero) ? N : 0;
-    hipLaunchKernelGGL(zero_i32_kernel, dim3(nz > 0 ? (nz + 255) / 256 : 1), dim3(256), 0, s, counts, nz, ticket);
+  if (what & kSelZero) {
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((N + 255) / 256), dim3(256), 0, s, counts, N, (uint32_t*)nullptr);
     CI_HIP_CHECK_LAUNCH();
   }
   if (!(what & (kSelTokens | kSelFinal))) return CI_OK;
 
+  SelectWs w;
+  select_ws_layout(M, N, &w);
+  char* base = reinterpret_cast<char*>(ws);
+  uint32_t* thr = ws ? reinterpret_cast<uint32_t*>(base + w.off_thr) : nullptr;
+  uint32_t* ticket = ws ? reinterpret_cast<uint32_t*>(base + w.off_ticket) : nullptr;
+
   const int nt = N >= 4096 ? 1024 : 256;
   const int items = (N + nt - 1) / nt;
-  int grid = di.cus * params().select_wgs_per_cu;
-  if (grid > M) grid = M;
-  if (grid < 1) grid = 1;
-  const int tokens_per_wg = (M + grid - 1) / grid;
-  // private u16 counters pay off only when a workgroup sees several tokens
-  // and they fit LDS next to the digit histograms
-  const size_t hist_bytes = (size_t)kHistWords * 4;
-  const size_t priv_bytes = (size_t)((N + 1) / 2) * 4;
-  const int privatise = (tokens_per_wg >= 2 && priv_bytes <= 88 * 1024) ? 1 : 0;
-  const size_t lds = hist_bytes + (privatise ? priv_bytes : 0);
-  const int stop = (what & kSelFinal) ? params().select_debug : 1;  // 1: return before the ticket
   const int mc = (int)max_count;
-
-#define CI_SEL(I) launch_sel<I>(act, M, N, ld, q_alpha, K, counts, core_idx, ticket, grid, nt, privatise, lds, mc, stop, s)
-  if (items <= 4) return CI_SEL(4);
-  if (items <= 8) return CI_SEL(8);
-  if (items <= 16) return CI_SEL(16);
-  return CI_SEL(0);
-#undef CI_SEL
+  const int debug = (what & kSelFinal) ? params().select_debug : 0;
+  int kwhat = 0;
+  int grid_b = 1;
+  if (what & kSelTokens) {
+    int grid = di.cus * params().select_wgs_per_cu;
+    if (grid > M) grid = M;
+    if (grid < 1) grid = 1;
+#define CI_THR(I) launch_threshold<I>(act, M, N, ld, q_alpha, thr, ticket, grid, nt, s)
+    if (items <= 4) rc = CI_THR(4);
+    else if (items <= 8) rc = CI_THR(8);
+    else if (items <= 16) rc = CI_THR(16);
+    else if (items <= 40) rc = CI_THR(40);
+    else rc = CI_THR(0);
+#undef CI_THR
+    if (rc != CI_OK) return rc;
+    grid_b = (N + 255) / 256;
+    kwhat |= kDoCount;
+    if (what & kSelAccumulate) kwhat |= kAccumulate;
+  }
+  if (what & kSelFinal) kwhat |= kDoFinal;
+  const int vec_ok = ((reinterpret_cast<uintptr_t>(act) & 15u) == 0 && ld % 4 == 0) ? 1 : 0;
+#define CI_CNT(I) launch_count_final<I>(act, M, N, ld, thr, vec_ok, counts, K, core_idx, ticket, mc, kwhat, \
+                                        debug, grid_b, nt, s)
+  if (items <= 4) return CI_CNT(4);
+  if (items <= 8) return CI_CNT(8);
+  if (items <= 16) return CI_CNT(16);
+  if (items <= 40) return CI_CNT(40);  // Def. 2 keeps up to 40 counts per thread in registers
+  return CI_CNT(0);
+#undef CI_CNT
 }
 
 int launch_scatter_count(const int32_t* idx, int64_t n_idx, int64_t N, int32_t* counts, hipStream_t s) {

@@ -170,10 +170,12 @@ def test_ffn_dense_rejects_bad_arguments_without_a_gpu(lib):
 def test_next_row_entry_points_reject_bad_arguments_without_a_gpu(lib):
     F = FAKE
     r = lib.raw.coreinfer_count_tokens
-    assert r(None, 4, 64, 64, 0.2, F, 0, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, 4, 64, 64, 0.2, None, 0, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, 4, 64, 64, 1.2, F, 0, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, 4, 64, 10, 0.2, F, 0, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(None, 4, 64, 64, 0.2, F, 0, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 64, 0.2, None, 0, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 64, 1.2, F, 0, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 10, 0.2, F, 0, F, 1 << 20, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 4, 64, 64, 0.2, F, 0, None, 1 << 20, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 4, 64, 64, 0.2, F, 0, F, 16, None) == lib.CI_ERR_WORKSPACE
     r = lib.raw.coreinfer_count_select
     assert r(None, 64, 10, 0.4, F, F, 256, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 64, 70000, 0.4, F, F, 256, None) == lib.CI_ERR_INVALID_ARG
