@@ -5,8 +5,9 @@
 //     (looping when M exceeds the grid).  The token's N activations become
 //     integer keys (the IEEE bits of a positive float are monotone in its
 //     value; everything that is not > 0 becomes key 0), loaded once and kept in
-//     registers.  A three-pass most-significant-digit radix select (11 + 11 +
-//     9 bits) over LDS histograms finds the value T of the k-th largest key,
+//     registers.  A most-significant-digit radix select (11 + 11 + 9 bits; the
+//     last digit by ranking the few keys left against each other when there are
+//     at most 64) over LDS histograms finds the value T of the k-th largest key,
 //     k being the share alpha of the positive keys.  The histograms are
 //     replicated eight times by lane so that activations sharing an exponent
 //     do not serialise on one LDS address.  Keys > T are token-wise core
@@ -151,6 +152,9 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
                                                                uint32_t* ticket) {
   __shared__ SelShared sh;
   __shared__ uint32_t cut_s;
+  constexpr int kCand = 64;
+  __shared__ uint32_t cand[kCand];
+  __shared__ uint32_t cand_n;
   extern __shared__ uint32_t dyn[];  // [kHistWords] histograms
   uint32_t* hist = dyn;
   const int tid = threadIdx.x, nt = blockDim.x;
@@ -214,8 +218,38 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
     uint32_t prefix = 0, prefix_mask = 0x80000000u, need = k, n_eq = 0;
     radix_pass<ITEMS>(key_sel, n_iter, 20, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
     radix_pass<ITEMS>(key_sel, n_iter, 9, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
-    radix_pass<ITEMS>(key_sel, n_iter, 0, 512, hist, &sh, prefix, prefix_mask, need, n_eq);
-    const uint32_t T = prefix;  // the k-th largest key; `need` of the n_eq keys == T are in the top k
+    uint32_t T;  // the k-th largest key; `need` of the n_eq keys == T are in the top k
+    if (n_eq <= kCand) {  // uniform; the usual case: after 22 bits only a few keys are left
+      // the candidates go to a short list and are ranked against each other
+      if (tid == 0) cand_n = 0;
+      __syncthreads();
+      for_items<ITEMS>(n_iter, [&](int i) {
+        const uint32_t key = key_sel(i);
+        if ((key & prefix_mask) == prefix) cand[atomicAdd(&cand_n, 1u)] = key;
+      });
+      __syncthreads();
+      if (tid < (int)n_eq) {
+        const uint32_t c = cand[tid];
+        uint32_t g = 0, ge = 0;
+        for (uint32_t j = 0; j < n_eq; ++j) {
+          g += cand[j] > c;
+          ge += cand[j] >= c;
+        }
+        if (g < need && need <= ge) {  // equal candidates write the same three values
+          sh.bin = c;
+          sh.above = g;
+          sh.in_bin = ge - g;
+        }
+      }
+      __syncthreads();
+      T = sh.bin;
+      need -= sh.above;
+      n_eq = sh.in_bin;
+      __syncthreads();  // sh and the list are reused
+    } else {
+      radix_pass<ITEMS>(key_sel, n_iter, 0, 512, hist, &sh, prefix, prefix_mask, need, n_eq);
+      T = prefix;
+    }
 
     // index of the last tie that is taken; ties in index order = iteration, then wave, then lane
     if (tid == 0) cut_s = 0x7fffffffu;  // all ties taken (the usual case: need == n_eq)
