@@ -83,7 +83,8 @@ int coreinfer_version(void);
  *   (0/1; 1 launches only the first decode kernel so that it can be timed
  *   alone -- y is then NOT written);
  *   "select_wgs_per_cu" (1..8), "select_debug" (timing only: 1 stops after the
- *   per-token phase, 2 after the ticket; core_idx is then NOT written);
+ *   counts, core_idx is then NOT written; 2 runs Def. 2 in one workgroup even
+ *   where the parallel kernel applies);
  *   "gemv_wgs_per_cu" (1..32), "gemm_ring" (0/1: register-ring GEMM kernels),
  *   "gemm_big" (0 never, 1 when the grid is large enough, 2 whenever the shape
  *   divides: the 256 x 256-tile GEMM kernel);

@@ -139,7 +139,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // ---- launchers (one per translation unit) ----------------------------------
 enum { kSelZero = 1, kSelTokens = 2, kSelFinal = 4, kSelAccumulate = 8 };
 struct SelectWs {
-  size_t off_thr, off_ticket, off_counts, total;
+  size_t off_thr, off_hist, off_counts, total;
 };
 void select_ws_layout(int64_t M, int64_t N, SelectWs* w);
 // ws: laid out by select_ws_layout (may be null when only kSelZero is asked for)

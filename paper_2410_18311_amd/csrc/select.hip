@@ -16,16 +16,20 @@
 //     that is taken (skipped when all of them are).  The token's result is the
 //     pair (T, cut): neuron n is in its core set iff key > T or (key == T and
 //     n <= cut).
-// count_final_kernel -- Eq. 3 and Def. 2.  Counting is a second pass over the
-//     activations by neuron: a workgroup owns 256 neurons and a share of the
-//     tokens, compares every activation with its token's (T, cut) and keeps the
-//     tallies in registers -- no atomics on the counters, and the counts are
-//     the same whatever the scheduling.  Partial tallies go to the workspace;
-//     the workgroup that finishes last (a ticket taken after a device-scope
-//     fence) adds them up, writes the counts, and selects the K neurons first
-//     in the order (count descending, index ascending): threshold count by a
-//     radix select over the counts (<= 65535), then an ordered compaction that
-//     writes S ascending: position = #greater before + min(#equal before, need).
+// count_kernel -- Eq. 3.  Counting is a second pass over the activations by
+//     neuron: a workgroup owns 256 neurons, walks all tokens, compares every
+//     activation with its token's (T, cut) and keeps the tallies in registers
+//     -- no atomics on the counters, and the counts are the same whatever the
+//     scheduling.  It also adds its neurons' counts to a histogram of count
+//     values.
+// def2_parallel_kernel -- Def. 2 / Eq. 2 for counts below 2048 (every prompt
+//     length of the workloads): each workgroup reads the threshold count off
+//     the histogram, tallies the neurons before its own block, and places its
+//     neurons: S ascending, position = #greater before + min(#equal before,
+//     need) in the order (count descending, index ascending).
+// def2_single_kernel -- the same in one workgroup for any counts up to 65535
+//     (radix select over the counts, table-based ordered compaction); also
+//     serves counts that come from the caller.
 #include "common.hpp"
 
 namespace ci {
@@ -37,13 +41,13 @@ constexpr int kCopies = 8;               // histogram replicas, chosen by lane &
 constexpr int kCopyStride = kBins + 8;   // words; the +8 spreads the replicas over LDS banks
 constexpr int kHistWords = kCopies * kCopyStride;
 constexpr int kMaxWaves = 16;
+constexpr int kCountBins = 2048;  // counts below this go to a global histogram for the parallel Def. 2
 
 struct SelShared {
   uint32_t wave_tot[kMaxWaves];
   uint32_t bin;      // chosen digit
   uint32_t above;    // keys in higher digits
   uint32_t in_bin;   // keys in the chosen digit
-  uint32_t ticket;
 };
 
 __device__ __forceinline__ uint32_t wave_count(bool pred) { return (uint32_t)__popcll(__ballot(pred)); }
@@ -149,7 +153,7 @@ template <int ITEMS>
 __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __restrict__ act, int M, int N,
                                                                int64_t ld, int64_t q_alpha,
                                                                uint32_t* __restrict__ thr,
-                                                               uint32_t* ticket) {
+                                                               uint32_t* ghist) {
   __shared__ SelShared sh;
   __shared__ uint32_t cut_s;
   constexpr int kCand = 64;
@@ -160,7 +164,8 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int n_iter = (N + nt - 1) / nt;
-  if (ticket && blockIdx.x == 0 && tid == 0) *ticket = 0u;  // for the counting launch that follows
+  if (ghist && blockIdx.x == 0)  // cleared here for the counting launch that follows
+    for (int j = tid; j < kCountBins; j += nt) ghist[j] = 0u;
 
   for (int m = blockIdx.x; m < M; m += gridDim.x) {
     const float* row = act + (size_t)m * ld;
@@ -318,64 +323,150 @@ __device__ __forceinline__ void count_tokens_of_lane(const float* __restrict__ a
   }
 }
 
-// What count_final_kernel does, individually switchable.
-enum { kDoCount = 1, kDoFinal = 2, kAccumulate = 4 };
+// Eq. 3: a workgroup owns 256 neurons and walks all tokens.  With `ghist` it also adds its
+// neurons' final counts to the histogram of count values (integer atomics, commutative).
+__global__ __launch_bounds__(1024) void count_kernel(const float* __restrict__ act, int M, int N, int64_t ld,
+                                                     const uint32_t* __restrict__ thr, int vec_ok,
+                                                     int32_t* counts, int accumulate, uint32_t* ghist) {
+  __shared__ uint32_t tally[256];
+  __shared__ uint32_t vhist[kCountBins];
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+  const int nb = blockIdx.x;
+  const int n0 = nb * 256 + lane * 4;  // this lane's four neurons
+  for (int j = tid; j < 256; j += nt) tally[j] = 0;
+  __syncthreads();
+  uint32_t cnt[4] = {0, 0, 0, 0};
+  if (vec_ok && n0 + 3 < N) count_tokens_of_lane<true>(act, ld, thr, M, N, n0, wave, nw, cnt);
+  else count_tokens_of_lane<false>(act, ld, thr, M, N, n0, wave, nw, cnt);
+  // block tallies: integer adds in LDS (commutative), then one plain store per neuron
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    if (cnt[c]) atomicAdd(&tally[lane * 4 + c], cnt[c]);
+  __syncthreads();
+  // the count values cluster on a few bins: they are first tallied per workgroup in LDS, so that a
+  // hot bin receives one device-scope atomic per workgroup, not one per neuron (those serialise)
+  if (ghist) {
+    for (int j = tid; j < kCountBins; j += nt) vhist[j] = 0;
+    __syncthreads();
+  }
+  for (int j = tid; j < 256; j += nt) {
+    const int n = nb * 256 + j;
+    if (n < N) {
+      const int32_t c = (int32_t)tally[j] + (accumulate ? counts[n] : 0);
+      counts[n] = c;
+      if (ghist && c >= 0 && c < kCountBins) atomicAdd(&vhist[c], 1u);
+    }
+  }
+  if (ghist) {
+    __syncthreads();
+    for (int j = tid; j < kCountBins; j += nt)
+      if (vhist[j]) atomicAdd(&ghist[j], vhist[j]);
+  }
+}
 
+// Def. 2 in parallel, for counts below kCountBins whose histogram `ghist` is known: every workgroup
+// (256 threads = 256 neurons) finds the threshold count T from the histogram, tallies the neurons
+// before its own that are above / at T, and places its own: position = #greater before +
+// min(#equal before, need).  The tally re-reads the counts before the block (cache resident;
+// N <= 65536 keeps that to a few MB in all).
+__global__ __launch_bounds__(256) void def2_parallel_kernel(const int32_t* __restrict__ counts,
+                                                            const uint32_t* __restrict__ ghist, int N, int K,
+                                                            int32_t* __restrict__ core_idx, int vec_ok) {
+  __shared__ uint32_t wtot[4], wg[4], we[4];
+  __shared__ uint32_t T_s, need_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // (1) T: the count value with #(count > T) < K <= #(count >= T); thread t owns bins 8t .. 8t+7
+  uint32_t bins[8], mine = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { bins[j] = ghist[tid * 8 + j]; mine += bins[j]; }
+  uint32_t suf = mine;  // inclusive suffix sum over the wave
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_down(suf, off, kWave);
+    if (lane + off < 64) suf += o;
+  }
+  if (lane == 0) wtot[wave] = suf;
+  __syncthreads();
+  uint32_t higher = 0;
+  for (int w = wave + 1; w < 4; ++w) higher += wtot[w];
+  const uint32_t incl = suf + higher, excl = incl - mine;
+  if (excl < (uint32_t)K && (uint32_t)K <= incl) {
+    uint32_t run = excl;
+#pragma unroll
+    for (int j = 7; j >= 0; --j) {
+      if (run < (uint32_t)K && run + bins[j] >= (uint32_t)K) { T_s = (uint32_t)(tid * 8 + j); need_s = (uint32_t)K - run; }
+      run += bins[j];
+    }
+  }
+  __syncthreads();
+  const uint32_t T = T_s, need = need_s;
+  // (2) neurons before this block that are above / at T
+  const int before = blockIdx.x * 256;
+  uint32_t g = 0, e = 0;
+  if (vec_ok) {  // 16-byte loads, eight in flight per thread (the loop is nothing but latency)
+    const int4* cv = reinterpret_cast<const int4*>(counts);
+    const int nv = before / 4;
+    for (int i0 = tid; i0 < nv; i0 += 256 * 8) {
+      int4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = cv[min(i0 + u * 256, nv - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (i0 + u * 256 < nv) {
+          g += ((uint32_t)v[u].x > T) + ((uint32_t)v[u].y > T) + ((uint32_t)v[u].z > T) + ((uint32_t)v[u].w > T);
+          e += ((uint32_t)v[u].x == T) + ((uint32_t)v[u].y == T) + ((uint32_t)v[u].z == T) + ((uint32_t)v[u].w == T);
+        }
+      }
+    }
+  } else {
+    for (int i0 = tid; i0 < before; i0 += 256 * 8) {
+      uint32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = (uint32_t)counts[min(i0 + u * 256, before - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (i0 + u * 256 < before) {
+          g += v[u] > T;
+          e += v[u] == T;
+        }
+      }
+    }
+  }
+  g = (uint32_t)wave_sum((int)g);
+  e = (uint32_t)wave_sum((int)e);
+  // (3) this block's neurons, in index order = wave, then lane
+  const int n = before + tid;
+  const bool valid = n < N;
+  const uint32_t c = valid ? (uint32_t)counts[n] : 0u;
+  const bool isg = valid && c > T, ise = valid && c == T;
+  const uint64_t bg = __ballot(isg), be = __ballot(ise);
+  if (lane == 0) { wg[wave] = g; we[wave] = e; wtot[wave] = ((uint32_t)__popcll(bg) << 16) | (uint32_t)__popcll(be); }
+  __syncthreads();
+  uint32_t g_before = 0, e_before = 0;
+  for (int w = 0; w < 4; ++w) {
+    g_before += wg[w];
+    e_before += we[w];
+    if (w < wave) { g_before += wtot[w] >> 16; e_before += wtot[w] & 0xffffu; }
+  }
+  g_before += (uint32_t)__popcll(bg & lanemask_lt());
+  e_before += (uint32_t)__popcll(be & lanemask_lt());
+  const uint32_t pos = g_before + (e_before < need ? e_before : need);
+  if (isg || (ise && e_before < need)) core_idx[pos] = n;
+}
+
+// Def. 2 in one workgroup (any counts up to 65535; also for counts that come from the caller).
 template <int ITEMS>
-__global__ __launch_bounds__(1024) void count_final_kernel(const float* __restrict__ act, int M, int N,
-                                                           int64_t ld, const uint32_t* __restrict__ thr,
-                                                           int vec_ok, int32_t* counts, int K,
-                                                           int32_t* core_idx, uint32_t* ticket,
-                                                           int max_count, int what, int debug) {
+__global__ __launch_bounds__(1024) void def2_single_kernel(int N, int32_t* counts, int K, int32_t* core_idx,
+                                                           int max_count) {
   __shared__ SelShared sh;
-  extern __shared__ uint32_t dyn[];  // counting: [1024] block tallies; Def. 2: [kHistWords] histograms
+  extern __shared__ uint32_t dyn[];  // [kHistWords] histograms
   uint32_t* hist = dyn;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int n_iter = (N + nt - 1) / nt;
 
-  // ------------------------------------------------ Eq. 3 ---------------------
-  if (what & kDoCount) {
-    const int nb = blockIdx.x;
-    const int n0 = nb * 256 + lane * 4;  // this lane's four neurons
-    for (int j = tid; j < 256; j += nt) dyn[j] = 0;
-    __syncthreads();
-    uint32_t cnt[4] = {0, 0, 0, 0};
-    if (vec_ok && n0 + 3 < N) count_tokens_of_lane<true>(act, ld, thr, M, N, n0, wave, nw, cnt);
-    else count_tokens_of_lane<false>(act, ld, thr, M, N, n0, wave, nw, cnt);
-    // block tallies: integer adds in LDS (commutative), then one plain store per neuron
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-      if (cnt[c]) atomicAdd(&dyn[lane * 4 + c], cnt[c]);
-    __syncthreads();
-    const bool acc = (what & kAccumulate) != 0;
-    for (int j = tid; j < 256; j += nt) {
-      const int n = nb * 256 + j;
-      if (n < N) counts[n] = (int32_t)dyn[j] + (acc ? counts[n] : 0);
-    }
-  }
-
-  // ------------------------------------------------ Def. 2 / Eq. 2 -----------
-  // The workgroup that finishes last sees every count: each workgroup's stores are complete
-  // (per-wave wait, barrier, one device-scope fence) before it takes its ticket.  Same-address
-  // tickets cost about 25-50 ns each, one reason why the counting pass uses few, wide workgroups.
-  if (debug & 1) return;
-  if (what & kDoCount) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    if (tid == 0) {
-      __threadfence();
-      sh.ticket = atomicAdd(ticket, 1u);
-    }
-    __syncthreads();
-    if (sh.ticket != gridDim.x - 1) return;
-    __threadfence();
-  }
-  if (debug & 2) return;
-  if (!(what & kDoFinal)) return;  // counts only (running form of Eq. 3)
-
-  // Plain loads: the fence above (acquire at device scope) has dropped this CU's stale lines, and
-  // plain loads can all be in flight at once.
+  // plain loads: all of a thread's counts are in flight at once
   auto total_count = [&](int e) -> uint32_t { return (uint32_t)counts[e]; };
 
   uint32_t cc[ITEMS > 0 ? ITEMS : 1];
@@ -499,10 +590,9 @@ __global__ __launch_bounds__(1024) void count_final_kernel(const float* __restri
   }
 }
 
-__global__ void zero_i32_kernel(int32_t* p, int n, uint32_t* ticket) {
+__global__ void zero_i32_kernel(int32_t* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
-  if (i == 0 && ticket) *ticket = 0;
 }
 
 // counts[idx] += 1 for every entry of an index list (entries outside [0, N)
@@ -578,7 +668,7 @@ __global__ __launch_bounds__(1024) void best_group_kernel(const int32_t* __restr
 
 template <int ITEMS>
 int launch_threshold(const float* act, int M, int N, int64_t ld, int64_t q_alpha, uint32_t* thr,
-                     uint32_t* ticket, int grid, int nt, hipStream_t s) {
+                     uint32_t* ghist, int grid, int nt, hipStream_t s) {
   static bool attr_done = false;  // raise the dynamic-LDS ceiling once (64 KB by default)
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS>),
@@ -587,24 +677,22 @@ int launch_threshold(const float* act, int M, int N, int64_t ld, int64_t q_alpha
     attr_done = true;
   }
   hipLaunchKernelGGL((token_threshold_kernel<ITEMS>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act, M,
-                     N, ld, q_alpha, thr, ticket);
+                     N, ld, q_alpha, thr, ghist);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
 
 template <int ITEMS>
-int launch_count_final(const float* act, int M, int N, int64_t ld, const uint32_t* thr, int vec_ok,
-                       int32_t* counts, int K, int32_t* core_idx, uint32_t* ticket, int max_count, int what,
-                       int debug, int grid, int nt, hipStream_t s) {
+int launch_def2_single(int N, int32_t* counts, int K, int32_t* core_idx, int max_count, int nt, hipStream_t s) {
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&count_final_kernel<ITEMS>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&def2_single_kernel<ITEMS>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024) != hipSuccess)
       return CI_ERR_HIP;
     attr_done = true;
   }
-  hipLaunchKernelGGL((count_final_kernel<ITEMS>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act, M, N,
-                     ld, thr, vec_ok, counts, K, core_idx, ticket, max_count, what, debug);
+  hipLaunchKernelGGL((def2_single_kernel<ITEMS>), dim3(1), dim3(nt), (size_t)kHistWords * 4, s, N, counts, K,
+                     core_idx, max_count);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
@@ -613,12 +701,12 @@ size_t round256z(size_t n) { return (n + 255) / 256 * 256; }
 
 }  // namespace
 
-// Workspace of one selection: per-token (T, cut) pairs, the ticket word, and
-// counters for callers that pass none.
+// Workspace of one selection: per-token (T, cut) pairs, the histogram of count
+// values, and counters for callers that pass none.
 void select_ws_layout(int64_t M, int64_t N, SelectWs* w) {
   w->off_thr = 0;
-  w->off_ticket = round256z((size_t)(M > 0 ? M : 1) * 2 * sizeof(uint32_t));
-  w->off_counts = w->off_ticket + 256;
+  w->off_hist = round256z((size_t)(M > 0 ? M : 1) * 2 * sizeof(uint32_t));
+  w->off_counts = w->off_hist + round256z((size_t)kCountBins * sizeof(uint32_t));
   w->total = w->off_counts + round256z((size_t)N * sizeof(int32_t));
 }
 
@@ -635,28 +723,27 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
   if (rc != CI_OK) return rc;
 
   if (what & kSelZero) {
-    hipLaunchKernelGGL(zero_i32_kernel, dim3((N + 255) / 256), dim3(256), 0, s, counts, N, (uint32_t*)nullptr);
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((N + 255) / 256), dim3(256), 0, s, counts, N);
     CI_HIP_CHECK_LAUNCH();
   }
   if (!(what & (kSelTokens | kSelFinal))) return CI_OK;
 
-  SelectWs w;
-  select_ws_layout(M, N, &w);
-  char* base = reinterpret_cast<char*>(ws);
-  uint32_t* thr = ws ? reinterpret_cast<uint32_t*>(base + w.off_thr) : nullptr;
-  uint32_t* ticket = ws ? reinterpret_cast<uint32_t*>(base + w.off_ticket) : nullptr;
-
   const int nt = N >= 4096 ? 1024 : 256;
   const int items = (N + nt - 1) / nt;
-  const int mc = (int)max_count;
-  const int debug = (what & kSelFinal) ? params().select_debug : 0;
-  int kwhat = 0;
-  int grid_b = 1;
+  const int nblocks = (N + 255) / 256;
+  // Def. 2 in parallel needs the histogram that the counting launch fills
+  const bool parallel_final = (what & kSelTokens) && (what & kSelFinal) && !(what & kSelAccumulate) &&
+                              max_count < kCountBins && nblocks <= 256 && params().select_debug == 0;
   if (what & kSelTokens) {
+    SelectWs w;
+    select_ws_layout(M, N, &w);
+    char* base = reinterpret_cast<char*>(ws);
+    uint32_t* thr = reinterpret_cast<uint32_t*>(base + w.off_thr);
+    uint32_t* ghist = parallel_final ? reinterpret_cast<uint32_t*>(base + w.off_hist) : nullptr;
     int grid = di.cus * params().select_wgs_per_cu;
     if (grid > M) grid = M;
     if (grid < 1) grid = 1;
-#define CI_THR(I) launch_threshold<I>(act, M, N, ld, q_alpha, thr, ticket, grid, nt, s)
+#define CI_THR(I) launch_threshold<I>(act, M, N, ld, q_alpha, thr, ghist, grid, nt, s)
     if (items <= 4) rc = CI_THR(4);
     else if (items <= 8) rc = CI_THR(8);
     else if (items <= 16) rc = CI_THR(16);
@@ -664,20 +751,26 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
     else rc = CI_THR(0);
 #undef CI_THR
     if (rc != CI_OK) return rc;
-    grid_b = (N + 255) / 256;
-    kwhat |= kDoCount;
-    if (what & kSelAccumulate) kwhat |= kAccumulate;
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(act) & 15u) == 0 && ld % 4 == 0) ? 1 : 0;
+    hipLaunchKernelGGL(count_kernel, dim3(nblocks), dim3(nt), 0, s, act, M, N, ld, thr, vec_ok, counts,
+                       (what & kSelAccumulate) ? 1 : 0, ghist);
+    CI_HIP_CHECK_LAUNCH();
+    if (parallel_final) {
+      const int cvec = (reinterpret_cast<uintptr_t>(counts) & 15u) == 0 ? 1 : 0;
+      hipLaunchKernelGGL(def2_parallel_kernel, dim3(nblocks), dim3(256), 0, s, counts, ghist, N, K, core_idx, cvec);
+      CI_HIP_CHECK_LAUNCH();
+      return CI_OK;
+    }
   }
-  if (what & kSelFinal) kwhat |= kDoFinal;
-  const int vec_ok = ((reinterpret_cast<uintptr_t>(act) & 15u) == 0 && ld % 4 == 0) ? 1 : 0;
-#define CI_CNT(I) launch_count_final<I>(act, M, N, ld, thr, vec_ok, counts, K, core_idx, ticket, mc, kwhat, \
-                                        debug, grid_b, nt, s)
-  if (items <= 4) return CI_CNT(4);
-  if (items <= 8) return CI_CNT(8);
-  if (items <= 16) return CI_CNT(16);
-  if (items <= 40) return CI_CNT(40);  // Def. 2 keeps up to 40 counts per thread in registers
-  return CI_CNT(0);
-#undef CI_CNT
+  if (!(what & kSelFinal) || params().select_debug == 1) return CI_OK;
+  const int mc = (int)max_count;
+#define CI_DEF2(I) launch_def2_single<I>(N, counts, K, core_idx, mc, nt, s)
+  if (items <= 4) return CI_DEF2(4);
+  if (items <= 8) return CI_DEF2(8);
+  if (items <= 16) return CI_DEF2(16);
+  if (items <= 40) return CI_DEF2(40);  // up to 40 counts per thread in registers
+  return CI_DEF2(0);
+#undef CI_DEF2
 }
 
 int launch_scatter_count(const int32_t* idx, int64_t n_idx, int64_t N, int32_t* counts, hipStream_t s) {
