@@ -678,3 +678,60 @@ def test_decode_graph_replays_match_eager(lib):
     g.replay()
     torch.cuda.synchronize()
     assert_close_rms(y[0], _oracle_ffn("relu", x[0], S, w, "out_major"), torch.float16, "graph, new input")
+
+
+def test_prefill_graph_replays_match_eager(lib):
+    """Dense FFN, selection, deployment and the union build captured in one HIP graph: every replay
+    gives the eager result, with stale workspaces and other work in between (nothing in these
+    paths relies on memory being cleared outside the captured kernels)."""
+    M, d, N, B = 96, 256, 1536, 3
+    dt = torch.float16
+    w = rand_weights(d, N, dt, "relu", "neuron_major", seed=11, device=DEV)
+    X = torch.randn(M, d, generator=torch.Generator().manual_seed(4)).to(dt).to(DEV)
+    K = lib.keep_count(0.3, N)
+    A = torch.empty(M, N, dtype=torch.float32, device=DEV)
+    Y = torch.empty(M, d, dtype=dt, device=DEV)
+    dws = torch.empty(lib.ffn_dense_workspace_size(M, d, N, dt), dtype=torch.uint8, device=DEV)
+    sws = torch.empty(lib.select_workspace_size(M, N), dtype=torch.uint8, device=DEV)
+    idx = torch.empty(K, dtype=torch.int32, device=DEV)
+    cnt = torch.empty(N, dtype=torch.int32, device=DEV)
+    bufs = lib.compact(w["w_up"], None, w["b_up"], w["w_down"], "neuron_major", "relu",
+                       torch.arange(K, dtype=torch.int32, device=DEV))
+    sets = torch.stack([torch.sort(torch.randperm(N, generator=torch.Generator().manual_seed(s))[:K]).values
+                        for s in range(B)]).to(torch.int32).to(DEV)
+    uws = torch.empty(N * 4 + 256, dtype=torch.uint8, device=DEV)
+    uidx = torch.empty(N, dtype=torch.int32, device=DEV)
+    umask = torch.empty(N, dtype=torch.int32, device=DEV)
+    ucount = torch.empty(1, dtype=torch.int32, device=DEV)
+
+    def run():
+        lib.ffn_dense(X, w["w_up"], None, w["b_up"], w["w_down"], w["b_down"], "neuron_major", "relu",
+                      want_y=True, want_a=True, Y=Y, A=A, ws=dws)
+        lib.select(A, 0.2, 0.3, core_idx=idx, counts=cnt, ws=sws)
+        lib.compact(w["w_up"], None, w["b_up"], w["w_down"], "neuron_major", "relu", idx, out=bufs)
+        lib._check(lib.raw.coreinfer_union_build(sets.data_ptr(), B, K, N, N, uidx.data_ptr(), umask.data_ptr(),
+                                                 ucount.data_ptr(), uws.data_ptr(), uws.numel(),
+                                                 torch.cuda.current_stream().cuda_stream), "union_build")
+
+    run()
+    torch.cuda.synchronize()
+    S_ref, c_ref = orc.select(A.cpu().numpy(), 0.2, 0.3)
+    assert idx.cpu().numpy().tolist() == S_ref.tolist() and cnt.cpu().numpy().tolist() == c_ref.tolist()
+    want = {"idx": idx.clone(), "cnt": cnt.clone(), "up": bufs["w_up_c"].clone(), "down": bufs["w_down_c"].clone(),
+            "Y": Y.clone(), "uidx": uidx[:int(ucount.item())].clone(), "un": int(ucount.item())}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    for i in range(3):
+        for t in (dws, sws, uws):
+            t.fill_(0xA5)                                # stale scratch must not matter
+        for t in (idx, cnt, uidx, ucount):
+            t.fill_(-7)
+        bufs["w_up_c"].zero_(); bufs["w_down_c"].zero_(); Y.zero_()
+        (torch.randn(128, 128, device=DEV) @ torch.randn(128, 128, device=DEV)).sum().item()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, want["idx"]) and torch.equal(cnt, want["cnt"]), f"replay {i}: selection"
+        assert torch.equal(bufs["w_up_c"], want["up"]) and torch.equal(bufs["w_down_c"], want["down"]), f"replay {i}"
+        assert torch.equal(Y, want["Y"]), f"replay {i}: dense output"
+        assert int(ucount.item()) == want["un"] and torch.equal(uidx[:want["un"]], want["uidx"]), f"replay {i}: union"
