@@ -65,16 +65,25 @@ __global__ __launch_bounds__(256) void gather_cols_t_kernel(const E* __restrict_
     ok = index_ok(idx, k, N);
     n = ok ? (size_t)idx[k] : 0;
   }
-  for (int jj = ty; jj < 64; jj += 4) {
-    const int j = j0 + jj;
-    E v = 0;
-    if (ok && j < d) v = in[(size_t)j * N + n];
-    tile[jj][tx] = v;
+  // all 16 loads of a thread in flight before the first is used
+  E v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int j = j0 + ty + 4 * i;
+    const bool take = ok && j < d;
+    const E t = in[take ? (size_t)j * N + n : (size_t)0];
+    v[i] = take ? t : (E)0;
   }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) tile[ty + 4 * i][tx] = v[i];
   __syncthreads();
   const int j = j0 + tx;
-  for (int kk = ty; kk < 64; kk += 4) {
-    if (k0 + kk < K && j < d) out[(size_t)(k0 + kk) * d + j] = tile[tx][kk];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = tile[tx][ty + 4 * i];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int kk = ty + 4 * i;
+    if (k0 + kk < K && j < d) out[(size_t)(k0 + kk) * d + j] = v[i];
   }
 }
 
@@ -176,15 +185,21 @@ __global__ __launch_bounds__(256) void delta_cols_t_kernel(const E* __restrict__
   const bool ok = t < c;
   const size_t n = ok ? (size_t)enter_list[t] : 0;
   if (ty == 0) sdst[tx] = ok ? free_list[t] : 0;
-  for (int jj = ty; jj < 64; jj += 4) {
-    const int j = j0 + jj;
-    E v = 0;
-    if (ok && j < d) v = in[(size_t)j * N + n];
-    tile[jj][tx] = v;
+  E v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int j = j0 + ty + 4 * i;
+    const bool take = ok && j < d;
+    const E x = in[take ? (size_t)j * N + n : (size_t)0];
+    v[i] = take ? x : (E)0;
   }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) tile[ty + 4 * i][tx] = v[i];
   __syncthreads();
   const int j = j0 + tx;
-  for (int kk = ty; kk < 64; kk += 4) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int kk = ty + 4 * i;
     if (t0 + kk < c && j < d) out[(size_t)sdst[kk] * d + j] = tile[tx][kk];
   }
 }

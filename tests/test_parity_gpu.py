@@ -104,7 +104,8 @@ def test_select_is_deterministic_and_permutation_invariant(lib):
 
 @pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("act,layout", [("relu", "out_major"), ("swiglu", "out_major"), ("relu", "neuron_major")])
-@pytest.mark.parametrize("d,N,K", [(64, 200, 77), (1024, 3000, 1201), (256, 1024, 1024), (8, 5, 1)])
+@pytest.mark.parametrize("d,N,K", [(64, 200, 77), (1024, 3000, 1201), (256, 1024, 1024), (8, 5, 1),
+                                   (104, 520, 300), (72, 4096, 100), (192, 2056, 2056), (136, 1544, 97)])
 def test_compact_matches_oracle(lib, dt, act, layout, d, N, K):
     _say("compact case", dt, act, layout, d, N, K)
     dtype = DTYPES[dt]
