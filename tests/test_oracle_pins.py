@@ -283,6 +283,9 @@ def test_sparse_ffn_neuron_by_neuron():
                                    y_relu, rtol=1e-12, atol=1e-13)
         np.testing.assert_allclose(orc.ffn_swiglu(t["x"][b], S, t["W_gate"], t["W_up"], t["W_down"]),
                                    y_sw, rtol=1e-12, atol=1e-13)
+        # an output bias (Llama has none, the interface allows one) is added once, in full
+        np.testing.assert_allclose(orc.ffn_swiglu(t["x"][b], S, t["W_gate"], t["W_up"], t["W_down"], t["b_down"]),
+                                   y_sw + t["b_down"], rtol=1e-12, atol=1e-13)
 
 
 def test_beta_one_is_the_dense_ffn_and_masked_dense_formulation():
