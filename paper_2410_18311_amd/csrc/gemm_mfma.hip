@@ -243,12 +243,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 // memory round trip.  Every load is unconditional (rows past the edge are
 // clamped: they only feed outputs that are never stored), so the number of
 // outstanding loads is the same on every path and the waits are exact.
-template <class D, int EPI>
+template <class D, int EPI, int RD, bool GUARD>  // RD: k-tiles in flight per thread; GUARD: nk % RD != 0 allowed
 __global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
   using T = typename D::T;
   constexpr bool DUAL = (EPI == EPI_SWIGLU);
   constexpr int NB = DUAL ? 2 : 1;
-  constexpr int RD = DUAL ? 2 : 3;  // k-tiles in flight per thread
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   T* smem = reinterpret_cast<T*>(smem_raw);
   constexpr int TILE = BM * LDK;
@@ -315,51 +314,76 @@ __global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
   __syncthreads();
 
   // Software pipeline: while tile kt is multiplied out of one LDS stage, tile kt + 1 moves from its
-  // register slot into the other stage and the slot is refilled with tile kt + 1 + RD -- one
-  // quarter of the stores and loads per MFMA k-step, so that the memory pipeline, the LDS and the
-  // matrix cores work at the same time instead of in turn.
+  // register slot into the other stage and the slot is refilled with tile kt + 1 + RD -- a third of
+  // the stores and loads in each of the first three MFMA k-steps.  The fragments of k-step s + 1
+  // are read while k-step s is multiplied (two register sets), so a wave never waits for the LDS
+  // read it has just issued; the one barrier per k-tile sits before the last k-step, whose MFMAs
+  // cover the first fragment reads of the next tile.
+  const int l31 = lane & 31, khalf = (lane >> 5) * 8;
+  uint4 fa[2][2], fb[2][NB][2];
+#define CI_RING_FRAGS(buf, base, s)                                                                 \
+  do {                                                                                              \
+    _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                                \
+      fa[buf][i_] = *reinterpret_cast<const uint4*>((base) + (wm * 64 + i_ * 32 + l31) * LDK + (s) * 16 + khalf); \
+    _Pragma("unroll") for (int q_ = 0; q_ < NB; ++q_)                                               \
+      _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_)                                              \
+        fb[buf][q_][j_] = *reinterpret_cast<const uint4*>((base) + TILE * (1 + q_) +                \
+                                                          (wn * 64 + j_ * 32 + l31) * LDK + (s) * 16 + khalf); \
+  } while (0)
+  CI_RING_FRAGS(0, smem, 0);
+
+  constexpr int NP = 4 + 4 * NB;                                  // 16-byte pieces per thread and k-tile
+  constexpr int kPieceLo[4] = {0, (NP + 2) / 3, (2 * NP + 2) / 3, NP};  // 3 + 3 + 2, or 4 + 4 + 4
   for (int kt0 = 0; kt0 < nk; kt0 += RD) {
 #pragma unroll
     for (int r = 0; r < RD; ++r) {
       const int kt = kt0 + r;
-      constexpr int kNextSlotOf[3] = {1 % RD, 2 % RD, 0};
-      const int rn = kNextSlotOf[r];  // slot of tile kt + 1
+      const int rn = (r + 1) % RD;  // slot of tile kt + 1
       const T* sA = smem + (kt & 1) * STAGE;
-      T* sN = smem + ((kt + 1) & 1) * STAGE;  // last read while tile kt - 1 was multiplied, before the previous barrier
+      T* sN = smem + ((kt + 1) & 1) * STAGE;  // last read before the barrier inside tile kt - 1
       const int kk_next = min(kt + 1 + RD, nk - 1) * BK;
 #pragma unroll
       for (int s = 0; s < BK / 16; ++s) {
-        const int koff = s * 16 + (lane >> 5) * 8;
-        uint4 fa[2], fb[NB][2];
+        if (s == BK / 16 - 1) {
+          // every wave has read all fragments of this tile and stored its share of the next one
+          __syncthreads();
+          CI_RING_FRAGS(0, sN, 0);
+        } else {
+          CI_RING_FRAGS((s + 1) & 1, sA, s + 1);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-          fa[i] = *reinterpret_cast<const uint4*>(sA + (wm * 64 + i * 32 + (lane & 31)) * LDK + koff);
-#pragma unroll
-        for (int q = 0; q < NB; ++q)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            fb[q][j] = *reinterpret_cast<const uint4*>(sA + TILE * (1 + q) +
-                                                       (wn * 64 + j * 32 + (lane & 31)) * LDK + koff);
-        // quarter s of tile kt + 1: registers -> LDS, then the registers are refilled
-        *reinterpret_cast<uint4*>(sN + lds_off[s]) = ra[rn][s];
-#pragma unroll
-        for (int q = 0; q < NB; ++q) *reinterpret_cast<uint4*>(sN + TILE * (1 + q) + lds_off[s]) = rb[rn][q][s];
-        ra[rn][s] = ld16(pa[s] + kk_next);
-#pragma unroll
-        for (int q = 0; q < NB; ++q) rb[rn][q][s] = ld16(pb[q][s] + kk_next);
-        if (kt < nk) {  // padding iterations (nk not a multiple of RD) skip the arithmetic only
+          for (int p = 0; p < NP; ++p) {
+            if (p < kPieceLo[s] || p >= kPieceLo[s + 1]) continue;
+            if (p < 4) {
+              *reinterpret_cast<uint4*>(sN + lds_off[p]) = ra[rn][p];
+              ra[rn][p] = ld16(pa[p] + kk_next);
+            } else {
+              const int q = (p - 4) >> 2, i = (p - 4) & 3;
+              *reinterpret_cast<uint4*>(sN + TILE * (1 + q) + lds_off[i]) = rb[rn][q][i];
+              rb[rn][q][i] = ld16(pb[q][i] + kk_next);
+            }
+          }
+        }
+        if (!GUARD || kt < nk) {  // padding iterations (nk not a multiple of RD) skip the arithmetic only
 #pragma unroll
           for (int q = 0; q < NB; ++q)
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-              for (int j = 0; j < 2; ++j) acc[q][i][j] = mfma32<D>(fa[i], fb[q][j], acc[q][i][j]);
+              for (int j = 0; j < 2; ++j) acc[q][i][j] = mfma32<D>(fa[s & 1][i], fb[s & 1][q][j], acc[q][i][j]);
         }
-        __builtin_amdgcn_sched_barrier(0);  // keeps the quarters (and with them the load order) apart
+        // one LDS or global instruction after each MFMA rather than a burst of them before the first
+#pragma unroll
+        for (int m = 0; m < 4 * NB; ++m) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+          __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keeps the k-steps (and with them the load order) apart
       }
-      __syncthreads();
     }
   }
+#undef CI_RING_FRAGS
 #undef CI_GEMM_ISSUE
 
   gemm_epilogue<D, EPI>(g, acc, m0, n0, wm, wn, lane);
@@ -368,20 +392,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
 // ---------------------------------------------------------------------------
 // Large-tile kernel for shapes that divide evenly: 256 x 256 outputs per
 // workgroup (SwiGLU: 256 rows x 128 gate + the same 128 up columns), eight waves
-// of 128 x 64 with 8 accumulator tiles each (two waves per SIMD: a single wave
-// does not overlap its LDS fragment reads with its own MFMAs).  A compute unit can keep only a
-// limited number of cache lines in flight, which caps what it can pull from L2
-// at roughly 20-25 bytes per clock; a 128 x 128 tile needs 64 bytes per clock to
-// keep its matrix cores busy, a 256 x 256 tile 32.  Two k-tiles ahead live in
-// registers (an L2 miss takes longer than one k-tile of MFMAs); a third of the next one moves to the other LDS stage (and is re-requested
-// for the tile after) between the MFMAs of each k-step; the one barrier per
-// k-tile sits before the last k-step, whose MFMAs cover the first fragment reads
-// of the next tile.
+// of 128 x 64 with 8 accumulator tiles each, two waves per SIMD.  What bounds a
+// tiled MFMA kernel on this chip is LDS traffic: per k-tile a compute unit
+// writes the two operand tiles once and every wave reads its fragments, and at
+// 128 bytes per clock that takes about as long as the tile's MFMAs for this
+// shape (1.5 times as long for 128 x 128 tiles with 64 x 64 wave tiles), so the
+// LDS instructions have to issue between the MFMAs, never in a burst in front
+// of them.  One k-tile ahead lives in registers; a third of it moves to the
+// other LDS stage (and is re-requested for the tile after) in each of the first
+// three k-steps; fragments are double-buffered; the one barrier per k-tile sits
+// before the last k-step, whose MFMAs cover the first fragment reads of the next
+// tile.  (Four waves of 128 x 128 read a third less from LDS and do overlap
+// their own reads with their MFMAs when scheduled this way, but came out no
+// faster: the stores and the barrier weigh more with one wave per SIMD.)
 constexpr int GM = 256;
 constexpr int LDN = 256 + 32;  // LDS row pitch of a k-major B tile (576 bytes: rows alternate bank halves)
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+constexpr int kFullChip = 256;          // compute units of an MI355X
 constexpr int kBigMinWorkgroups = 160;  // below this the 128 x 128 kernel fills the chip better
 
 template <class D, int EPI>
@@ -568,6 +597,15 @@ __global__ __launch_bounds__(512) void gemm_mfma_big_kernel(GemmArgs g) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<D>(fa[s & 1][i], fb[s & 1][j], acc[i][j]);
         }
+        // within a k-step: one LDS or global instruction after each MFMA instead of a burst of them
+        // before the first (the matrix pipe idles while a burst issues)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+          __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
+        }
         __builtin_amdgcn_sched_barrier(0);  // keeps the k-steps (and with them the load order) apart
       }
     }
@@ -710,6 +748,19 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   for (int k = 0; k < 4; ++k) y[k] = from_float<D>(o[k]);
 }
 
+template <class D, int EPI, int RD, bool GUARD>
+int launch_ring(const GemmArgs& g, int tiles, int splits, size_t lds, hipStream_t s) {
+  static bool attr_done = false;
+  if (lds > 48 * 1024 && !attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_ring_kernel<D, EPI, RD, GUARD>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return CI_ERR_HIP;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((gemm_mfma_ring_kernel<D, EPI, RD, GUARD>), dim3(tiles, splits), dim3(256), lds, s, g);
+  return CI_OK;
+}
+
 template <class D, int EPI, bool BNN>
 int launch_mfma(const GemmArgs& g, hipStream_t s) {
   constexpr int NB = (EPI == EPI_SWIGLU) ? 2 : 1;
@@ -740,14 +791,25 @@ int launch_mfma(const GemmArgs& g, hipStream_t s) {
     }
     hipLaunchKernelGGL((gemm_mfma_big_kernel<D, EPI, BNN && EPI == EPI_LINEAR>), dim3(big_tiles, splits), dim3(512), lds_big, s, g);
   } else if (ring) {
-    static bool ring_attr_done = false;
-    if (lds > 48 * 1024 && !ring_attr_done) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_ring_kernel<D, EPI>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return CI_ERR_HIP;
-      ring_attr_done = true;
+    // deepest ring whose depth divides every split's k-tile count (no padding iterations); else the
+    // guarded variant.  SwiGLU holds three operand tiles per k-tile, so its ring stays at two.
+    const int chunk = g.partial ? g.k_chunk : g.Kk;
+    const int nkc = (g.Kk % chunk == 0) ? chunk / BK : 0;  // 0: the splits differ in length
+    int rc = CI_OK;
+    if constexpr (EPI == EPI_SWIGLU) {
+      rc = (nkc > 0 && nkc % 2 == 0) ? launch_ring<D, EPI, 2, false>(g, tiles, splits, lds, s)
+                                     : launch_ring<D, EPI, 2, true>(g, tiles, splits, lds, s);
+    } else {
+      if (nkc > 0 && nkc % 4 == 0 && tiles * splits <= kFullChip)
+        rc = launch_ring<D, EPI, 4, false>(g, tiles, splits, lds, s);  // one workgroup per CU: registers to spare
+      else if (nkc > 0 && nkc % 3 == 0)
+        rc = launch_ring<D, EPI, 3, false>(g, tiles, splits, lds, s);
+      else if (nkc > 0 && nkc % 2 == 0)
+        rc = launch_ring<D, EPI, 2, false>(g, tiles, splits, lds, s);
+      else
+        rc = launch_ring<D, EPI, 3, true>(g, tiles, splits, lds, s);
     }
-    hipLaunchKernelGGL((gemm_mfma_ring_kernel<D, EPI>), dim3(tiles, splits), dim3(256), lds, s, g);
+    if (rc != CI_OK) return rc;
   } else {
     hipLaunchKernelGGL((gemm_mfma_kernel<D, EPI, BNN>), dim3(tiles, splits), dim3(256), lds, s, g);
   }
