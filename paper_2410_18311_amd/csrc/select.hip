@@ -1,5 +1,5 @@
-// Sentence-wise core neuron selection (Sec. 3.1 of arXiv 2410.18311), two
-// launches per sentence and layer, no floating-point or counter atomics:
+// Sentence-wise core neuron selection (Sec. 3.1 of arXiv 2410.18311), three
+// short launches per sentence and layer, no floating-point or counter atomics:
 //
 // token_threshold_kernel -- Def. 1 / Eq. 1.  One workgroup per prompt token
 //     (looping when M exceeds the grid).  The token's N activations become
