@@ -747,6 +747,9 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
     if (items <= 4) rc = CI_THR(4);
     else if (items <= 8) rc = CI_THR(8);
     else if (items <= 16) rc = CI_THR(16);
+    else if (items <= 24) rc = CI_THR(24);
+    else if (items <= 32) rc = CI_THR(32);
+    else if (items <= 36) rc = CI_THR(36);
     else if (items <= 40) rc = CI_THR(40);
     else rc = CI_THR(0);
 #undef CI_THR

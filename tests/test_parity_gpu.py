@@ -44,6 +44,10 @@ def _select_case(lib, A_np, alpha, beta, what):
     (300, 2048, "relu", 0, 0.2, 0.4),          # more tokens than workgroups: LDS-private counters
     (700, 1500, "abs", 3, 0.1, 0.6),
     (5, 36864, "relu", 0, 0.2, 0.4),
+    (6, 22016, "abs", 0, 0.2, 0.4),            # 22, 28, 36, 40 keys per thread: the register-cached variants
+    (4, 28672, "relu", 4, 0.2, 0.4),
+    (3, 36000, "abs", 6, 0.3, 0.3),
+    (3, 40960, "relu", 0, 0.2, 0.4),
     (3, 50000, "abs", 0, 0.05, 0.1),           # beyond the register-cached sizes
     (9, 13824, "abs", 0, 1.0, 1.0),
     (9, 1000, "relu", 2, 1.0, 0.001),
