@@ -41,6 +41,7 @@ constexpr int kCopies = 8;               // histogram replicas, chosen by lane &
 constexpr int kCopyStride = kBins + 8;   // words; the +8 spreads the replicas over LDS banks
 constexpr int kHistWords = kCopies * kCopyStride;
 constexpr int kMaxWaves = 16;
+constexpr uint32_t kNoKey = 0xffffffffu;  // stands for an activation that is not positive
 constexpr int kCountBins = 2048;  // counts below this go to a global histogram for the parallel Def. 2
 
 struct SelShared {
@@ -133,8 +134,13 @@ __device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, 
                                            uint32_t& k, uint32_t& n_eq) {
   const int tid = threadIdx.x, nt = blockDim.x;
   uint32_t* my_hist = hist + (tid & (kCopies - 1)) * kCopyStride;
-  // clear the replicas (the padding words are never read)
-  for (int j = tid; j < kCopies * nb; j += nt) hist[(j / nb) * kCopyStride + (j % nb)] = 0;
+  // clear the replicas, 16 bytes per store (nb is a multiple of 4 and the replica stride keeps
+  // 16-byte alignment; the padding words are never read)
+  {
+    const int q = nb >> 2;  // 16-byte pieces per replica
+    for (int j = tid; j < kCopies * q; j += nt)
+      *reinterpret_cast<uint4*>(hist + (j / q) * kCopyStride + (j % q) * 4) = make_uint4(0, 0, 0, 0);
+  }
   __syncthreads();
   for_items<ITEMS>(n_iter, [&](int i) {
     const uint32_t key = key_at(i);
@@ -159,7 +165,7 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
   constexpr int kCand = 64;
   __shared__ uint32_t cand[kCand];
   __shared__ uint32_t cand_n;
-  extern __shared__ uint32_t dyn[];  // [kHistWords] histograms
+  extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];  // [kHistWords] histograms, cleared 16 bytes at a time
   uint32_t* hist = dyn;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
@@ -186,30 +192,28 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
 #pragma unroll
         for (int j = 0; j < BATCH; ++j) {
           const int e = (i0 + j) * nt + tid;
-          kc[i0 + j] = (e < N && av[j] > 0.f) ? f2u(av[j]) : 0u;
+          kc[i0 + j] = (e < N && av[j] > 0.f) ? f2u(av[j]) : kNoKey;
         }
       }
 #pragma unroll
-      for (int i = 0; i < ITEMS; ++i) npos += wave_count(kc[i] != 0);
+      for (int i = 0; i < ITEMS; ++i) npos += wave_count(kc[i] != kNoKey);
     } else {
       for (int i = 0; i < n_iter; ++i) {
         const int e = i * nt + tid;
         npos += wave_count(e < N && row[e] > 0.f);
       }
     }
-    // key of this thread's i-th element; 0 (never a candidate) past the end
+    // key of this thread's i-th element.  Elements that are not positive, and those past the end,
+    // get all-ones: bit 31 is part of the prefix mask from the start, so they match no prefix, and
+    // no threshold equals them
     auto key_at = [&](int i) -> uint32_t {
       if (ITEMS > 0) return kc[ITEMS > 0 ? i : 0];  // i is a constant after unrolling
       const int e = i * nt + tid;
-      if (e >= N) return 0u;
+      if (e >= N) return kNoKey;
       const float a = row[e];
-      return (a > 0.f) ? f2u(a) : 0u;
+      return (a > 0.f) ? f2u(a) : kNoKey;
     };
-    // for the histogram passes a zero key must match no prefix: map it to all-ones
-    auto key_sel = [&](int i) -> uint32_t {
-      const uint32_t key = key_at(i);
-      return key != 0 ? key : 0xffffffffu;
-    };
+    auto key_sel = key_at;
 
     const uint32_t P = block_sum_waves(npos, &sh);
     const uint32_t k = (uint32_t)((q_alpha * (int64_t)P + 999999) / 1000000);  // share of the positives
@@ -262,7 +266,7 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
       uint32_t base = 0;                // ties seen in earlier iterations
       for_items<ITEMS>(n_iter, [&](int i) {
         if (base < need) {  // uniform condition
-          const bool tie = key_at(i) == T;  // T >= 1, so elements past the end (key 0) never match
+          const bool tie = key_at(i) == T;  // T < 2^31, so elements without a key never match
           const uint64_t bal = __ballot(tie);
           __syncthreads();
           if (lane == 0) sh.wave_tot[wave] = (uint32_t)__popcll(bal);
@@ -460,7 +464,7 @@ template <int ITEMS>
 __global__ __launch_bounds__(1024) void def2_single_kernel(int N, int32_t* counts, int K, int32_t* core_idx,
                                                            int max_count) {
   __shared__ SelShared sh;
-  extern __shared__ uint32_t dyn[];  // [kHistWords] histograms
+  extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];  // [kHistWords] histograms, cleared 16 bytes at a time
   uint32_t* hist = dyn;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
