@@ -43,6 +43,7 @@ constexpr int kHistWords = kCopies * kCopyStride;
 constexpr int kMaxWaves = 16;
 constexpr uint32_t kNoKey = 0xffffffffu;  // stands for an activation that is not positive
 constexpr int kCountBins = 2048;  // counts below this go to a global histogram for the parallel Def. 2
+constexpr int kHistCopies = 8;    // copies of that histogram, by workgroup: atomics on one address serialise
 
 struct SelShared {
   uint32_t wave_tot[kMaxWaves];
@@ -170,8 +171,8 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int n_iter = (N + nt - 1) / nt;
-  if (ghist && blockIdx.x == 0)  // cleared here for the counting launch that follows
-    for (int j = tid; j < kCountBins; j += nt) ghist[j] = 0u;
+  if (ghist)  // cleared here, a slice per workgroup, for the counting launch that follows
+    for (int j = blockIdx.x * nt + tid; j < kCountBins * kHistCopies; j += gridDim.x * nt) ghist[j] = 0u;
 
   for (int m = blockIdx.x; m < M; m += gridDim.x) {
     const float* row = act + (size_t)m * ld;
@@ -289,20 +290,21 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
   }
 }
 
-// Tallies of one lane's four neurons n0 .. n0+3 over the tokens wave, wave + nw, ... (UN at a time
-// in flight: the pass is latency-bound, it has few workgroups).  VEC: one 16-byte load per token,
-// else four clamped 4-byte loads (unaligned rows or the last neurons of the layer).
-template <bool VEC>
+// Tallies of one lane's four neurons n0 .. n0+3 over its share of the tokens.  A wave instruction
+// covers TPW tokens (lane / (64 / TPW) picks the token, the other lane bits the neuron quad); waves
+// take batches of UN * TPW tokens in turn, UN loads per lane in flight.  VEC: one 16-byte load per
+// token, else four clamped 4-byte loads (unaligned rows or the last neurons of the layer).
+template <bool VEC, int TPW>
 __device__ __forceinline__ void count_tokens_of_lane(const float* __restrict__ act, int64_t ld,
                                                      const uint32_t* __restrict__ thr, int M, int N,
-                                                     int n0, int wave, int nw, uint32_t (&cnt)[4]) {
+                                                     int n0, int ts, int wave, int nw, uint32_t (&cnt)[4]) {
   constexpr int UN = 8;
-  for (int m0 = wave * UN; m0 < M; m0 += nw * UN) {
+  for (int m0 = wave * UN * TPW; m0 < M; m0 += nw * UN * TPW) {
     float v[UN][4];
     uint32_t T[UN], cut[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const int m = min(m0 + u, M - 1);  // clamped: a repeated token is masked below
+      const int m = min(m0 + u * TPW + ts, M - 1);  // clamped: a repeated token is masked below
       const float* p = act + (size_t)m * ld;
       if (VEC) {
         const float4 q = *reinterpret_cast<const float4*>(p + n0);
@@ -316,37 +318,44 @@ __device__ __forceinline__ void count_tokens_of_lane(const float* __restrict__ a
     }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      if (m0 + u < M) {  // uniform per wave
+      const uint32_t live = (m0 + u * TPW + ts < M) ? 1u : 0u;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const uint32_t key = (n0 + c < N && v[u][c] > 0.f) ? f2u(v[u][c]) : 0u;
-          cnt[c] += (key > T[u] || (key == T[u] && (uint32_t)(n0 + c) <= cut[u])) ? 1u : 0u;
-        }
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t key = (n0 + c < N && v[u][c] > 0.f) ? f2u(v[u][c]) : 0u;
+        cnt[c] += (key > T[u] || (key == T[u] && (uint32_t)(n0 + c) <= cut[u])) ? live : 0u;
       }
     }
   }
 }
 
-// Eq. 3: a workgroup owns 256 neurons and walks all tokens.  With `ghist` it also adds its
-// neurons' final counts to the histogram of count values (integer atomics, commutative).
+// Eq. 3: a workgroup owns NPW neurons and walks all tokens (NPW = 64 gives the launch four times
+// the workgroups of NPW = 256: the pass is bound by vector instructions per compute unit, and the
+// layers here have only 43 to 144 blocks of 256 neurons).  With `ghist` it also adds its neurons'
+// final counts to the histogram of count values (integer atomics, commutative).
+template <int NPW>
 __global__ __launch_bounds__(1024) void count_kernel(const float* __restrict__ act, int M, int N, int64_t ld,
                                                      const uint32_t* __restrict__ thr, int vec_ok,
                                                      int32_t* counts, int accumulate, uint32_t* ghist) {
-  __shared__ uint32_t tally[256];
+  constexpr int TPW = 256 / NPW;   // tokens per wave instruction
+  constexpr int LPR = 64 / TPW;    // lanes per token row
+  __shared__ uint32_t tally[NPW];
   __shared__ uint32_t vhist[kCountBins];
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int nb = blockIdx.x;
-  const int n0 = nb * 256 + lane * 4;  // this lane's four neurons
-  for (int j = tid; j < 256; j += nt) tally[j] = 0;
+  const int quad = lane % LPR, ts = lane / LPR;
+  const int n0 = nb * NPW + quad * 4;  // this lane's four neurons
+  for (int j = tid; j < NPW; j += nt) tally[j] = 0;
   __syncthreads();
   uint32_t cnt[4] = {0, 0, 0, 0};
-  if (vec_ok && n0 + 3 < N) count_tokens_of_lane<true>(act, ld, thr, M, N, n0, wave, nw, cnt);
-  else count_tokens_of_lane<false>(act, ld, thr, M, N, n0, wave, nw, cnt);
+  // rows of the last, partial block take the element-wise path as a whole (uniform per workgroup
+  // would be enough; per lane keeps the full blocks' lanes on the vector path)
+  if (vec_ok && n0 + 3 < N) count_tokens_of_lane<true, TPW>(act, ld, thr, M, N, min(n0, N - 4), ts, wave, nw, cnt);
+  else count_tokens_of_lane<false, TPW>(act, ld, thr, M, N, n0, ts, wave, nw, cnt);
   // block tallies: integer adds in LDS (commutative), then one plain store per neuron
 #pragma unroll
   for (int c = 0; c < 4; ++c)
-    if (cnt[c]) atomicAdd(&tally[lane * 4 + c], cnt[c]);
+    if (cnt[c]) atomicAdd(&tally[quad * 4 + c], cnt[c]);
   __syncthreads();
   // the count values cluster on a few bins: they are first tallied per workgroup in LDS, so that a
   // hot bin receives one device-scope atomic per workgroup, not one per neuron (those serialise)
@@ -354,8 +363,8 @@ __global__ __launch_bounds__(1024) void count_kernel(const float* __restrict__ a
     for (int j = tid; j < kCountBins; j += nt) vhist[j] = 0;
     __syncthreads();
   }
-  for (int j = tid; j < 256; j += nt) {
-    const int n = nb * 256 + j;
+  for (int j = tid; j < NPW; j += nt) {
+    const int n = nb * NPW + j;
     if (n < N) {
       const int32_t c = (int32_t)tally[j] + (accumulate ? counts[n] : 0);
       counts[n] = c;
@@ -364,8 +373,9 @@ __global__ __launch_bounds__(1024) void count_kernel(const float* __restrict__ a
   }
   if (ghist) {
     __syncthreads();
+    uint32_t* gcopy = ghist + (nb % kHistCopies) * kCountBins;
     for (int j = tid; j < kCountBins; j += nt)
-      if (vhist[j]) atomicAdd(&ghist[j], vhist[j]);
+      if (vhist[j]) atomicAdd(&gcopy[j], vhist[j]);
   }
 }
 
@@ -383,7 +393,12 @@ __global__ __launch_bounds__(256) void def2_parallel_kernel(const int32_t* __res
   // (1) T: the count value with #(count > T) < K <= #(count >= T); thread t owns bins 8t .. 8t+7
   uint32_t bins[8], mine = 0;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) { bins[j] = ghist[tid * 8 + j]; mine += bins[j]; }
+  for (int j = 0; j < 8; ++j) {
+    bins[j] = 0;
+#pragma unroll
+    for (int r = 0; r < kHistCopies; ++r) bins[j] += ghist[r * kCountBins + tid * 8 + j];
+    mine += bins[j];
+  }
   uint32_t suf = mine;  // inclusive suffix sum over the wave
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -710,7 +725,7 @@ size_t round256z(size_t n) { return (n + 255) / 256 * 256; }
 void select_ws_layout(int64_t M, int64_t N, SelectWs* w) {
   w->off_thr = 0;
   w->off_hist = round256z((size_t)(M > 0 ? M : 1) * 2 * sizeof(uint32_t));
-  w->off_counts = w->off_hist + round256z((size_t)kCountBins * sizeof(uint32_t));
+  w->off_counts = w->off_hist + round256z((size_t)kCountBins * kHistCopies * sizeof(uint32_t));
   w->total = w->off_counts + round256z((size_t)N * sizeof(int32_t));
 }
 
@@ -759,8 +774,14 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
 #undef CI_THR
     if (rc != CI_OK) return rc;
     const int vec_ok = ((reinterpret_cast<uintptr_t>(act) & 15u) == 0 && ld % 4 == 0) ? 1 : 0;
-    hipLaunchKernelGGL(count_kernel, dim3(nblocks), dim3(nt), 0, s, act, M, N, ld, thr, vec_ok, counts,
-                       (what & kSelAccumulate) ? 1 : 0, ghist);
+    // 64 neurons per workgroup when blocks of 256 would leave more than half of the chip idle
+    const int acc = (what & kSelAccumulate) ? 1 : 0;
+    if (nblocks <= di.cus / 2)
+      hipLaunchKernelGGL(count_kernel<64>, dim3((N + 63) / 64), dim3(nt), 0, s, act, M, N, ld, thr, vec_ok, counts,
+                         acc, ghist);
+    else
+      hipLaunchKernelGGL(count_kernel<256>, dim3(nblocks), dim3(nt), 0, s, act, M, N, ld, thr, vec_ok, counts,
+                         acc, ghist);
     CI_HIP_CHECK_LAUNCH();
     if (parallel_final) {
       const int cvec = (reinterpret_cast<uintptr_t>(counts) & 15u) == 0 ? 1 : 0;
