@@ -57,6 +57,32 @@ def test_select_matches_oracle(lib, M, N, kind, levels, alpha, beta):
     _select_case(lib, A, alpha, beta, f"{kind}/{levels}")
 
 
+def test_select_random_shapes_and_tie_patterns(lib):
+    """Seeded sweep over shapes and value patterns the fixed cases do not list: every
+    keys-per-thread variant of the kernels, few and many distinct values, keep fractions
+    from 0.1 % to 100 %, rows of different sparsity, special values."""
+    rng = np.random.default_rng(20241018)
+    widths = [1, 2, 63, 64, 65, 255, 257, 1000, 4095, 4096, 4097, 8200, 12288, 16385, 20000, 24577, 30000,
+              33000, 36865, 40961, 45000]
+    for case in range(48):
+        N = int(widths[case % len(widths)]) if case < 2 * len(widths) else int(rng.integers(1, 45000))
+        M = int(rng.integers(1, 24)) if N > 8192 else int(rng.integers(1, 400))
+        kind = ["relu", "abs", "raw"][case % 3]
+        levels = int(rng.choice([0, 0, 1, 2, 3, 7, 50]))
+        alpha = float(rng.choice([0.001, 0.05, 0.2, 0.33, 0.5, 0.999, 1.0]))
+        beta = float(rng.choice([0.001, 0.1, 0.25, 0.4, 0.75, 1.0]))
+        A = wl.activation_like(M, N, seed=1000 + case, kind=kind, levels=levels)
+        if case % 5 == 0:      # rows with very different numbers of positives
+            keep = rng.random((M, 1)) ** 3
+            A = np.where(rng.random((M, N)) < keep, A, np.float32(0.0)).astype(np.float32)
+        if case % 7 == 0:      # special values: +inf ranks first, NaN and -0.0 are never positive
+            flat = A.reshape(-1)
+            idx = rng.integers(0, flat.size, size=min(6, flat.size))
+            flat[idx] = np.array([np.inf, np.nan, -0.0, np.float32(1e-45), -np.inf, np.float32(3.4e38)],
+                                 dtype=np.float32)[:idx.size]
+        _select_case(lib, A, alpha, beta, f"random case {case}: {kind}/{levels}")
+
+
 def test_select_degenerate_rows(lib):
     rng = np.random.default_rng(5)
     N = 3000
@@ -233,6 +259,39 @@ def test_decode_gathered_matches_oracle(lib, dt, act, d, N, K, B):
         assert_close_rms(y[b], _oracle_ffn(act, x[b], S[b], w, "neuron_major"), dtype, f"gathered b={b}")
 
 
+def test_decode_random_shapes(lib):
+    """Seeded sweep: widths that are no multiple of any tile, core sets from one neuron to all of
+    them, one to eight rows of x, both ways of handing over the core neurons."""
+    rng = np.random.default_rng(7)
+    for case in range(36):
+        dt = ["f16", "bf16", "f32"][case % 3]
+        act = ["relu", "swiglu"][(case // 3) % 2]
+        dtype = DTYPES[dt]
+        d = 8 * int(rng.integers(1, 700))
+        N = int(rng.integers(1, 3000))
+        K = int(rng.choice([1, N, max(1, N // 2), int(rng.integers(1, N + 1))]))
+        B = int(rng.integers(1, 9))
+        gathered = case % 2 == 1
+        _say("decode random case", case, dt, act, d, N, K, B, "gathered" if gathered else "compacted")
+        layout = "neuron_major" if gathered else "out_major"
+        w = rand_weights(d, N, dtype, act, layout, seed=900 + case, device=DEV)
+        x = torch.randn(B, d, generator=torch.Generator().manual_seed(case)).to(dtype).to(DEV)
+        if gathered:
+            S = np.stack([np.sort(rng.choice(N, size=K, replace=False)) for _ in range(B)])
+            desc = lib.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"],
+                                    core_idx=torch.from_numpy(S.astype(np.int32)).to(DEV))
+        else:
+            S1 = np.sort(rng.choice(N, size=K, replace=False))
+            S = np.stack([S1] * B)
+            c = lib.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], layout, act,
+                            torch.from_numpy(S1.astype(np.int32)).to(DEV))
+            desc = lib.make_weights(c["w_up_c"], c["w_gate_c"], c["b_up_c"], c["w_down_c"], w["b_down"])
+        y = lib.ffn_decode(x, desc, act)
+        torch.cuda.synchronize()
+        for b in range(B):
+            assert_close_rms(y[b], _oracle_ffn(act, x[b], S[b], w, layout), dtype, f"random case {case} row {b}")
+
+
 def test_decode_gathered_ignores_out_of_range_entries(lib):
     d, N, K = 256, 500, 40
     w = rand_weights(d, N, torch.float16, "relu", "neuron_major", seed=2, device=DEV)
@@ -286,6 +345,34 @@ def test_dense_matches_oracle(lib, dt, act, layout, M, d, N):
                           want_y=False, want_a=True)
     torch.cuda.synchronize()
     assert torch.equal(A, A2)
+
+
+def test_dense_random_shapes(lib):
+    """Seeded sweep over prompt lengths and widths around the tile edges of every GEMM variant
+    (ragged and even, reduction lengths that are and are not multiples of the k tile)."""
+    rng = np.random.default_rng(11)
+    for case in range(30):
+        dt = ["f16", "bf16", "f32"][case % 3]
+        act = ["relu", "swiglu"][(case // 3) % 2]
+        layout = ["out_major", "neuron_major"][(case // 6) % 2]
+        dtype = DTYPES[dt]
+        vec = 4 if dt == "f32" else 8
+        M = int(rng.choice([5, 64, 127, 128, 129, 255, 256, 300, 512]))
+        d = vec * int(rng.integers(1, 1200 // vec))
+        N = vec * int(rng.integers(1, 1600 // vec))
+        if case % 5 == 0:          # shapes every kernel divides
+            M, d, N = 256 * int(rng.integers(1, 3)), 64 * int(rng.integers(1, 12)), 256 * int(rng.integers(1, 6))
+        _say("dense random case", case, dt, act, layout, M, d, N)
+        w = rand_weights(d, N, dtype, act, layout, seed=500 + case, device=DEV)
+        X = torch.randn(M, d, generator=torch.Generator().manual_seed(case)).to(dtype).to(DEV)
+        Y, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], layout, act,
+                             want_y=True, want_a=True)
+        torch.cuda.synchronize()
+        A_ref = (orc.score_relu(f64(X), f64(w["w_up"]), f64(w["b_up"])) if act == "relu"
+                 else orc.score_swiglu(f64(X), f64(w["w_gate"]), f64(w["w_up"])))
+        rms = np.sqrt(np.mean(A_ref ** 2))
+        assert np.max(np.abs(f64(A) - A_ref)) <= 1e-4 * rms, f"random case {case}: scores"
+        assert_close_rms(Y, _oracle_ffn(act, X, None, w, layout), dtype, f"random case {case}: Y")
 
 
 @pytest.mark.parametrize("dt", ["f16", "bf16"])
