@@ -178,6 +178,8 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
     const float* row = act + (size_t)m * ld;
     uint32_t kc[ITEMS > 0 ? ITEMS : 1];
     uint32_t npos = 0;
+    uint32_t lane_id = (uint32_t)tid;  // thread index within the workgroup
+    asm volatile("" : "+v"(lane_id));
     if (ITEMS > 0) {
       // branch-free loads, issued back to back in batches (a batch bounds the registers that hold
       // values not yet turned into keys)
@@ -187,13 +189,17 @@ __global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __re
         float av[BATCH];
 #pragma unroll
         for (int j = 0; j < BATCH; ++j) {
-          const int e = (i0 + j) * nt + tid;
-          av[j] = row[e < N ? e : N - 1];
+          // uniform base of the item + a 32-bit lane offset (clamped inside the row); the lane
+          // index is made opaque per token so that the offsets are not all computed ahead of
+          // the token loop and kept in two registers each
+          const int s0 = ((i0 + j) * nt < N) ? (i0 + j) * nt : 0;
+          const float* item = row + s0;
+          av[j] = item[min(lane_id, (uint32_t)(N - 1 - s0))];
         }
 #pragma unroll
         for (int j = 0; j < BATCH; ++j) {
-          const int e = (i0 + j) * nt + tid;
-          kc[i0 + j] = (e < N && av[j] > 0.f) ? f2u(av[j]) : kNoKey;
+          const uint32_t e = (uint32_t)((i0 + j) * nt) + lane_id;
+          kc[i0 + j] = (e < (uint32_t)N && av[j] > 0.f) ? f2u(av[j]) : kNoKey;
         }
       }
 #pragma unroll
