@@ -113,7 +113,7 @@ struct Params {
   int decode_wgs = 0;        // absolute number of neuron slices per sentence (0 = per-CU rule)
   int decode_threads = 0;  // 0 = derived from d
   int decode_depth = 4;    // weight rows in flight per thread (4, 8 or 16)
-  int select_wgs_per_cu = 1;
+  int select_wgs_per_cu = 2;
   int select_debug = 0;
   int gemv_wgs_per_cu = 4;
   int gemm_ring = 1;         // register-ring GEMM kernel where it applies

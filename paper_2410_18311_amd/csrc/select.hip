@@ -156,8 +156,8 @@ __device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, 
   __syncthreads();  // sh is reused by the next pass
 }
 
-template <int ITEMS>
-__global__ __launch_bounds__(1024) void token_threshold_kernel(const float* __restrict__ act, int M, int N,
+template <int ITEMS, bool TWO>  // TWO: registers capped so that two workgroups of 16 waves share a compute unit
+__global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(const float* __restrict__ act, int M, int N,
                                                                int64_t ld, int64_t q_alpha,
                                                                uint32_t* __restrict__ thr,
                                                                uint32_t* ghist) {
@@ -691,17 +691,17 @@ __global__ __launch_bounds__(1024) void best_group_kernel(const int32_t* __restr
   if (threadIdx.x == 0) best[0] = sg[0];
 }
 
-template <int ITEMS>
+template <int ITEMS, bool TWO = false>
 int launch_threshold(const float* act, int M, int N, int64_t ld, int64_t q_alpha, uint32_t* thr,
                      uint32_t* ghist, int grid, int nt, hipStream_t s) {
   static bool attr_done = false;  // raise the dynamic-LDS ceiling once (64 KB by default)
   if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS, TWO>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024) != hipSuccess)
       return CI_ERR_HIP;
     attr_done = true;
   }
-  hipLaunchKernelGGL((token_threshold_kernel<ITEMS>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act, M,
+  hipLaunchKernelGGL((token_threshold_kernel<ITEMS, TWO>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act, M,
                      N, ld, q_alpha, thr, ghist);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
@@ -765,11 +765,18 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
     char* base = reinterpret_cast<char*>(ws);
     uint32_t* thr = reinterpret_cast<uint32_t*>(base + w.off_thr);
     uint32_t* ghist = parallel_final ? reinterpret_cast<uint32_t*>(base + w.off_hist) : nullptr;
-    int grid = di.cus * params().select_wgs_per_cu;
+    // more tokens than compute units and at most 16 keys per thread: two workgroups per compute
+    // unit (a token round is half instruction issue, half barriers and latency; the register cap
+    // this needs costs a single workgroup about 10 %, so it is not used for short prompts)
+    const bool two = M > di.cus && items <= 16 && params().select_wgs_per_cu >= 2;
+    int grid = di.cus * (two ? 2 : 1);
     if (grid > M) grid = M;
     if (grid < 1) grid = 1;
 #define CI_THR(I) launch_threshold<I>(act, M, N, ld, q_alpha, thr, ghist, grid, nt, s)
-    if (items <= 4) rc = CI_THR(4);
+#define CI_THR2(I) launch_threshold<I, true>(act, M, N, ld, q_alpha, thr, ghist, grid, nt, s)
+    if (two && items <= 8) rc = CI_THR2(8);
+    else if (two) rc = CI_THR2(16);
+    else if (items <= 4) rc = CI_THR(4);
     else if (items <= 8) rc = CI_THR(8);
     else if (items <= 16) rc = CI_THR(16);
     else if (items <= 24) rc = CI_THR(24);
@@ -778,6 +785,7 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
     else if (items <= 40) rc = CI_THR(40);
     else rc = CI_THR(0);
 #undef CI_THR
+#undef CI_THR2
     if (rc != CI_OK) return rc;
     const int vec_ok = ((reinterpret_cast<uintptr_t>(act) & 15u) == 0 && ld % 4 == 0) ? 1 : 0;
     // 64 neurons per workgroup when blocks of 256 would leave more than half of the chip idle

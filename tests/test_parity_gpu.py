@@ -43,6 +43,8 @@ def _select_case(lib, A_np, alpha, beta, what):
     (33, 16384, "relu", 0, 0.2, 0.4),
     (300, 2048, "relu", 0, 0.2, 0.4),          # more tokens than workgroups: LDS-private counters
     (700, 1500, "abs", 3, 0.1, 0.6),
+    (300, 11008, "abs", 0, 0.2, 0.4),          # more tokens than compute units: two workgroups per unit
+    (515, 16384, "relu", 9, 0.2, 0.4),
     (5, 36864, "relu", 0, 0.2, 0.4),
     (6, 22016, "abs", 0, 0.2, 0.4),            # 22, 28, 36, 40 keys per thread: the register-cached variants
     (4, 28672, "relu", 4, 0.2, 0.4),
