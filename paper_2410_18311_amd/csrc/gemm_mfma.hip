@@ -885,7 +885,23 @@ static int down_splits_small(int64_t M, int64_t d, int64_t N) {
 static int down_splits_big(int64_t M, int64_t d, int64_t N) {
   if (M % GM != 0 || d % 256 != 0 || N % BK != 0) return 0;
   const int64_t tb = (M / GM) * (d / 256);
-  if (tb >= kBigMinWorkgroups) return 1;
+  if (tb >= kBigMinWorkgroups) {
+    // enough tiles to fill the chip; a k split can still pay when the last round of workgroups is
+    // mostly empty (576 tiles = 2.25 rounds on 256 compute units take as long as three).  Model:
+    // rounds of tiles, each 1/s of a full tile's time at ~4.5 TFLOP/s per compute unit, plus the
+    // fp32 partial products written and read back at ~4.5 TB/s and one more launch.
+    const double t_tile = 2.0 * GM * 256 * (double)N / 4.5e12;
+    const double t_one = (double)((tb + kFullChip - 1) / kFullChip) * t_tile;
+    int best = 1;
+    double best_t = 0.95 * t_one;  // a split has to win by 5 %
+    for (int sp = 2; sp <= 8; ++sp) {
+      if (N / ((int64_t)sp * BK) < 8) break;  // at least eight k tiles per split
+      const int64_t rounds = (tb * sp + kFullChip - 1) / kFullChip;
+      const double t = (double)rounds * t_tile / sp + 2.0 * sp * (double)M * (double)d * 4.0 / 4.5e12 + 6e-6;
+      if (t < best_t) { best = sp; best_t = t; }
+    }
+    return best;
+  }
   if (tb < 32) return 0;
   int64_t sb = (256 + tb / 2) / tb;
   const int64_t max_k = N / (8 * BK);  // at least eight k tiles per split

@@ -406,6 +406,25 @@ def test_dense_large_tile_kernel_matches_oracle(lib, dt, act, layout, M, d, N):
 
 # ------------------------------------------------------------- whole small path
 
+@pytest.mark.parametrize("layout", ["out_major", "neuron_major"])
+def test_dense_many_tiles_with_split_down_projection(lib, layout):
+    """288 large tiles (two rounds of workgroups, the second nearly empty): the down projection is
+    split over k although the grid is full.  Sampled rows against the oracle."""
+    M, d, N = 4096, 4608, 6400
+    _say("dense many-tile case", layout, M, d, N)
+    w = rand_weights(d, N, torch.float16, "relu", layout, seed=77, device=DEV)
+    X = torch.randn(M, d, generator=torch.Generator().manual_seed(3)).to(torch.float16).to(DEV)
+    Y, A = lib.ffn_dense(X, w["w_up"], None, w["b_up"], w["w_down"], w["b_down"], layout, "relu",
+                         want_y=True, want_a=True)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 255, 256, M - 1], np.random.default_rng(1).integers(0, M, size=44)]))
+    Xs = f64(X)[rows]
+    A_ref = orc.score_relu(Xs, f64(w["w_up"]), f64(w["b_up"]))
+    assert np.max(np.abs(f64(A)[rows] - A_ref)) <= 1e-4 * np.sqrt(np.mean(A_ref ** 2))
+    Y_ref = orc.ffn_relu(Xs, None, f64(w["w_up"]), f64(w["b_up"]), down_out_major64(w, layout), f64(w["b_down"]))
+    assert_close_rms(Y[torch.from_numpy(rows).to(DEV)], Y_ref, torch.float16, "split down projection")
+
+
 def test_tiny_fp32_configuration_end_to_end(lib):
     """The small fp32 configuration, whole: prefill 32 tokens, select, compact,
     16 decode steps; every stage against the oracle."""
