@@ -390,20 +390,26 @@ __global__ __launch_bounds__(1024) void count_kernel(const float* __restrict__ a
 // before its own that are above / at T, and places its own: position = #greater before +
 // min(#equal before, need).  The tally re-reads the counts before the block (cache resident;
 // N <= 65536 keeps that to a few MB in all).
-__global__ __launch_bounds__(256) void def2_parallel_kernel(const int32_t* __restrict__ counts,
-                                                            const uint32_t* __restrict__ ghist, int N, int K,
-                                                            int32_t* __restrict__ core_idx, int vec_ok) {
-  __shared__ uint32_t wtot[4], wg[4], we[4];
+__global__ __launch_bounds__(1024) void def2_parallel_kernel(const int32_t* __restrict__ counts,
+                                                             const uint32_t* __restrict__ ghist, int N, int K,
+                                                             int32_t* __restrict__ core_idx, int vec_ok) {
+  __shared__ uint32_t wtot[4], wg[kMaxWaves], we[kMaxWaves];
   __shared__ uint32_t T_s, need_s;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // (1) T: the count value with #(count > T) < K <= #(count >= T); thread t owns bins 8t .. 8t+7
+  const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+  // (1) T: the count value with #(count > T) < K <= #(count >= T); thread t < 256 owns bins 8t .. 8t+7
   uint32_t bins[8], mine = 0;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    bins[j] = 0;
+  for (int j = 0; j < 8; ++j) bins[j] = 0;
+  if (tid < 256) {
 #pragma unroll
-    for (int r = 0; r < kHistCopies; ++r) bins[j] += ghist[r * kCountBins + tid * 8 + j];
-    mine += bins[j];
+    for (int r = 0; r < kHistCopies; ++r) {
+      const uint4* hp = reinterpret_cast<const uint4*>(ghist + r * kCountBins + tid * 8);
+      const uint4 lo = hp[0], hi = hp[1];
+      bins[0] += lo.x; bins[1] += lo.y; bins[2] += lo.z; bins[3] += lo.w;
+      bins[4] += hi.x; bins[5] += hi.y; bins[6] += hi.z; bins[7] += hi.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) mine += bins[j];
   }
   uint32_t suf = mine;  // inclusive suffix sum over the wave
 #pragma unroll
@@ -411,47 +417,50 @@ __global__ __launch_bounds__(256) void def2_parallel_kernel(const int32_t* __res
     const uint32_t o = __shfl_down(suf, off, kWave);
     if (lane + off < 64) suf += o;
   }
-  if (lane == 0) wtot[wave] = suf;
+  if (lane == 0 && wave < 4) wtot[wave] = suf;
   __syncthreads();
-  uint32_t higher = 0;
-  for (int w = wave + 1; w < 4; ++w) higher += wtot[w];
-  const uint32_t incl = suf + higher, excl = incl - mine;
-  if (excl < (uint32_t)K && (uint32_t)K <= incl) {
-    uint32_t run = excl;
+  if (tid < 256) {
+    uint32_t higher = 0;
+    for (int w = wave + 1; w < 4; ++w) higher += wtot[w];
+    const uint32_t incl = suf + higher, excl = incl - mine;
+    if (excl < (uint32_t)K && (uint32_t)K <= incl) {
+      uint32_t run = excl;
 #pragma unroll
-    for (int j = 7; j >= 0; --j) {
-      if (run < (uint32_t)K && run + bins[j] >= (uint32_t)K) { T_s = (uint32_t)(tid * 8 + j); need_s = (uint32_t)K - run; }
-      run += bins[j];
+      for (int j = 7; j >= 0; --j) {
+        if (run < (uint32_t)K && run + bins[j] >= (uint32_t)K) { T_s = (uint32_t)(tid * 8 + j); need_s = (uint32_t)K - run; }
+        run += bins[j];
+      }
     }
   }
   __syncthreads();
   const uint32_t T = T_s, need = need_s;
-  // (2) neurons before this block that are above / at T
+  // (2) neurons before this block that are above / at T: all threads, eight loads in flight each
+  // (the loop is nothing but latency)
   const int before = blockIdx.x * 256;
   uint32_t g = 0, e = 0;
-  if (vec_ok) {  // 16-byte loads, eight in flight per thread (the loop is nothing but latency)
+  if (vec_ok) {
     const int4* cv = reinterpret_cast<const int4*>(counts);
     const int nv = before / 4;
-    for (int i0 = tid; i0 < nv; i0 += 256 * 8) {
+    for (int i0 = tid; i0 < nv; i0 += nt * 8) {
       int4 v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = cv[min(i0 + u * 256, nv - 1)];
+      for (int u = 0; u < 8; ++u) v[u] = cv[min(i0 + u * nt, nv - 1)];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        if (i0 + u * 256 < nv) {
+        if (i0 + u * nt < nv) {
           g += ((uint32_t)v[u].x > T) + ((uint32_t)v[u].y > T) + ((uint32_t)v[u].z > T) + ((uint32_t)v[u].w > T);
           e += ((uint32_t)v[u].x == T) + ((uint32_t)v[u].y == T) + ((uint32_t)v[u].z == T) + ((uint32_t)v[u].w == T);
         }
       }
     }
   } else {
-    for (int i0 = tid; i0 < before; i0 += 256 * 8) {
+    for (int i0 = tid; i0 < before; i0 += nt * 8) {
       uint32_t v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = (uint32_t)counts[min(i0 + u * 256, before - 1)];
+      for (int u = 0; u < 8; ++u) v[u] = (uint32_t)counts[min(i0 + u * nt, before - 1)];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        if (i0 + u * 256 < before) {
+        if (i0 + u * nt < before) {
           g += v[u] > T;
           e += v[u] == T;
         }
@@ -460,24 +469,30 @@ __global__ __launch_bounds__(256) void def2_parallel_kernel(const int32_t* __res
   }
   g = (uint32_t)wave_sum((int)g);
   e = (uint32_t)wave_sum((int)e);
-  // (3) this block's neurons, in index order = wave, then lane
+  // (3) this block's neurons (threads 0..255), in index order = wave, then lane
   const int n = before + tid;
-  const bool valid = n < N;
+  const bool valid = tid < 256 && n < N;
   const uint32_t c = valid ? (uint32_t)counts[n] : 0u;
   const bool isg = valid && c > T, ise = valid && c == T;
   const uint64_t bg = __ballot(isg), be = __ballot(ise);
-  if (lane == 0) { wg[wave] = g; we[wave] = e; wtot[wave] = ((uint32_t)__popcll(bg) << 16) | (uint32_t)__popcll(be); }
-  __syncthreads();
-  uint32_t g_before = 0, e_before = 0;
-  for (int w = 0; w < 4; ++w) {
-    g_before += wg[w];
-    e_before += we[w];
-    if (w < wave) { g_before += wtot[w] >> 16; e_before += wtot[w] & 0xffffu; }
+  if (lane == 0) {
+    wg[wave] = g;
+    we[wave] = e;
+    if (wave < 4) wtot[wave] = ((uint32_t)__popcll(bg) << 16) | (uint32_t)__popcll(be);
   }
-  g_before += (uint32_t)__popcll(bg & lanemask_lt());
-  e_before += (uint32_t)__popcll(be & lanemask_lt());
-  const uint32_t pos = g_before + (e_before < need ? e_before : need);
-  if (isg || (ise && e_before < need)) core_idx[pos] = n;
+  __syncthreads();
+  if (tid < 256) {
+    uint32_t g_before = 0, e_before = 0;
+    for (int w = 0; w < nw; ++w) {
+      g_before += wg[w];
+      e_before += we[w];
+    }
+    for (int w = 0; w < wave; ++w) { g_before += wtot[w] >> 16; e_before += wtot[w] & 0xffffu; }
+    g_before += (uint32_t)__popcll(bg & lanemask_lt());
+    e_before += (uint32_t)__popcll(be & lanemask_lt());
+    const uint32_t pos = g_before + (e_before < need ? e_before : need);
+    if (isg || (ise && e_before < need)) core_idx[pos] = n;
+  }
 }
 
 // Def. 2 in one workgroup (any counts up to 65535; also for counts that come from the caller).
@@ -799,7 +814,7 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
     CI_HIP_CHECK_LAUNCH();
     if (parallel_final) {
       const int cvec = (reinterpret_cast<uintptr_t>(counts) & 15u) == 0 ? 1 : 0;
-      hipLaunchKernelGGL(def2_parallel_kernel, dim3(nblocks), dim3(256), 0, s, counts, ghist, N, K, core_idx, cvec);
+      hipLaunchKernelGGL(def2_parallel_kernel, dim3(nblocks), dim3(1024), 0, s, counts, ghist, N, K, core_idx, cvec);
       CI_HIP_CHECK_LAUNCH();
       return CI_OK;
     }
