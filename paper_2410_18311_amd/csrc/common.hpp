@@ -131,6 +131,18 @@ Params& params();
 inline int elem_bytes(int dtype) { return dtype == CI_F32 ? 4 : 2; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// True the first time it is called with this flag word while the current device is current:
+// per-device one-time set-up (kernel attributes) keyed by device ordinal.  Setting an attribute
+// twice is harmless, so no lock.
+inline bool first_call_on_device(uint64_t& seen) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return true;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (seen & bit) return false;
+  seen |= bit;
+  return true;
+}
+
 #define CI_HIP_CHECK_LAUNCH()                          \
   do {                                                 \
     if (hipGetLastError() != hipSuccess) return CI_ERR_HIP; \
