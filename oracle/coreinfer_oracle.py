@@ -31,6 +31,10 @@ What is here, and the passage each part follows:
   (Sec. 4.1 says only "once the input sentence's group is determined"): the
   group whose core set is most similar to the prompt's own under Insight-2's
   metric.
+* ``sentence_feature`` / ``assign_centroid`` -- similarity-guided prediction
+  when the groups come from K-Means on a layer's activation (App. A.2.3): the
+  vector a sentence is clustered by, and the K-Means assignment step (nearest
+  centroid) that puts a new prompt into a group.
 * ``count_tokens_into``     -- Eq. 3 as a running sum when a sentence grows.
 * ``compact_update_slots``  -- re-deploying after the core set changed
   (Fig. 1 "stability estimation ... how to update"; the paper gives no rule):
@@ -320,6 +324,37 @@ def assign_group(prompt_set, group_sets):
         if best_sim is None or sim > best_sim:
             best, best_sim = g, sim
     return best, pairs
+
+
+def sentence_feature(A) -> np.ndarray:
+    """The vector a sentence is clustered by.  App. A.2.3 runs K-Means on "the
+    activation" of one layer without saying how a sentence's tokens are
+    summarised; the reading taken here is the mean over the sentence's tokens
+    of the layer's activation rows A [M, N] (the vector Def. 1 ranks)."""
+    A = np.asarray(A, dtype=np.float64)
+    if A.ndim != 2 or A.shape[0] < 1:
+        raise ValueError("A must be [M, N] with M >= 1")
+    return A.sum(axis=0) / A.shape[0]
+
+
+def assign_centroid(feature, centroids):
+    """Group of a new prompt when the groups are K-Means clusters (App. A.2.3):
+    the K-Means assignment step, i.e. the centroid nearest to the prompt's
+    feature vector in Euclidean distance; equal distances go to the lower
+    group index.  Returns (group, squared distances [G])."""
+    f = np.asarray(feature, dtype=np.float64)
+    C = np.asarray(centroids, dtype=np.float64)
+    if C.ndim != 2 or f.ndim != 1 or C.shape[1] != f.shape[0] or C.shape[0] < 1:
+        raise ValueError("feature [N], centroids [G, N] with G >= 1")
+    d2 = np.zeros(C.shape[0])
+    for g in range(C.shape[0]):
+        diff = f - C[g]
+        d2[g] = float(np.dot(diff, diff))
+    best = 0
+    for g in range(1, C.shape[0]):
+        if d2[g] < d2[best]:
+            best = g
+    return best, d2
 
 
 def core_similarity(S1, S2) -> float:

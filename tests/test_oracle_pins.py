@@ -446,3 +446,61 @@ def test_compact_update_slots_hand_example_and_invariants():
     y_slots = orc.ffn_relu(x, slots, W1, b1, W2)
     y_sorted = orc.ffn_relu(x, np.sort(slots), W1, b1, W2)
     assert np.allclose(y_slots, y_sorted, rtol=1e-12, atol=1e-12)
+
+
+def test_assign_centroid_hand_example_library_and_invariances():
+    # hand example: three centroids on a line, feature at 1.9 -> nearest is the one at 2; an exact
+    # midpoint goes to the lower index
+    C = np.array([[0.0, 0.0], [2.0, 0.0], [5.0, 0.0]])
+    g, d2 = orc.assign_centroid(np.array([1.9, 0.0]), C)
+    assert g == 1 and np.allclose(d2, [3.61, 0.01, 9.61])
+    assert orc.assign_centroid(np.array([1.0, 0.0]), C)[0] == 0          # tie between 0 and 1
+    assert orc.assign_centroid(np.array([3.5, 0.0]), C)[0] == 1          # tie between 1 and 2
+    assert orc.assign_centroid(np.array([7.0, 3.0]), C[:1])[0] == 0      # a single group
+    # the library's vector-quantisation step (nearest code book entry, Euclidean)
+    from scipy.cluster.vq import vq
+    rng = np.random.default_rng(5)
+    book = rng.standard_normal((9, 40))
+    obs = rng.standard_normal((60, 40)) * 1.5
+    code, dist = vq(obs, book)
+    for i in range(60):
+        g, d2 = orc.assign_centroid(obs[i], book)
+        assert g == code[i]
+        np.testing.assert_allclose(np.sqrt(d2[g]), dist[i], rtol=1e-12)
+        # brute force, term by term
+        want = [sum((obs[i, n] - book[k, n]) ** 2 for n in range(40)) for k in range(9)]
+        np.testing.assert_allclose(d2, want, rtol=1e-12)
+    # moving everything by the same vector, or rotating the axes, changes no assignment
+    shift = rng.standard_normal(40)
+    Q, _ = np.linalg.qr(rng.standard_normal((40, 40)))
+    for i in range(20):
+        g = orc.assign_centroid(obs[i], book)[0]
+        assert orc.assign_centroid(obs[i] + shift, book + shift)[0] == g
+        assert orc.assign_centroid(obs[i] @ Q, book @ Q)[0] == g
+    # a centroid is its own nearest centroid, at distance zero
+    for k in range(9):
+        g, d2 = orc.assign_centroid(book[k], book)
+        assert g == k and d2[k] == 0.0
+
+
+def test_sentence_feature_is_the_token_mean():
+    A = np.array([[1.0, 0.0, 4.0], [3.0, 0.0, 0.0], [2.0, 6.0, 2.0], [2.0, 2.0, 2.0]])
+    assert orc.sentence_feature(A).tolist() == [2.0, 2.0, 2.0]
+    rng = np.random.default_rng(2)
+    B = rng.standard_normal((7, 5))
+    f = orc.sentence_feature(B)
+    for n in range(5):
+        assert abs(f[n] - sum(B[m, n] for m in range(7)) / 7) < 1e-15
+    # one token: the feature is that token's row; repeating the sentence changes nothing;
+    # the token order does not matter
+    assert np.array_equal(orc.sentence_feature(B[:1]), B[0])
+    np.testing.assert_allclose(orc.sentence_feature(np.vstack([B, B])), f, rtol=1e-14, atol=1e-15)
+    np.testing.assert_allclose(orc.sentence_feature(B[::-1]), f, rtol=1e-14, atol=1e-15)
+    # K-Means fixed point: with centroids = means of two well separated sets of sentences, every
+    # sentence is assigned to its own set
+    left = [rng.standard_normal((4, 6)) * 0.1 - 3.0 for _ in range(5)]
+    right = [rng.standard_normal((4, 6)) * 0.1 + 3.0 for _ in range(5)]
+    cents = np.stack([np.mean([orc.sentence_feature(a) for a in left], axis=0),
+                      np.mean([orc.sentence_feature(a) for a in right], axis=0)])
+    assert all(orc.assign_centroid(orc.sentence_feature(a), cents)[0] == 0 for a in left)
+    assert all(orc.assign_centroid(orc.sentence_feature(a), cents)[0] == 1 for a in right)

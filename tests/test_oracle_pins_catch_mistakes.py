@@ -76,6 +76,14 @@ MISTAKES = [
     ("group choice: ties to the higher index", "if best_sim is None or sim > best_sim:",
      "if best_sim is None or sim >= best_sim:", 0),
     ("group choice: least similar", "if best_sim is None or sim > best_sim:", "if best_sim is None or sim < best_sim:", 0),
+    ("feature: sum instead of mean", "return A.sum(axis=0) / A.shape[0]", "return A.sum(axis=0)", 0),
+    ("feature: mean over neurons", "return A.sum(axis=0) / A.shape[0]", "return A.sum(axis=1) / A.shape[1]", 0),
+    ("feature: last token dropped", "return A.sum(axis=0) / A.shape[0]", "return A[:-1].sum(axis=0) / A.shape[0]", 0),
+    ("centroid: farthest", "if d2[g] < d2[best]:", "if d2[g] > d2[best]:", 0),
+    ("centroid: ties to the higher index", "if d2[g] < d2[best]:", "if d2[g] <= d2[best]:", 0),
+    ("centroid: sum of absolute differences", "d2[g] = float(np.dot(diff, diff))", "d2[g] = float(np.abs(diff).sum())", 0),
+    ("centroid: first coordinate skipped", "d2[g] = float(np.dot(diff, diff))", "d2[g] = float(np.dot(diff[1:], diff[1:]))", 0),
+    ("centroid: similarity instead of distance", "d2[g] = float(np.dot(diff, diff))", "d2[g] = -float(np.dot(f, C[g]))", 0),
     ("similarity over the larger set", "return len(a & b) / len(a | b)", "return len(a & b) / max(len(a), len(b))", 0),
 ]
 
