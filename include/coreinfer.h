@@ -187,6 +187,25 @@ int coreinfer_assign_group(const int32_t* set, int64_t K, const int32_t* group_s
                            int32_t* best, int32_t* inter_union, void* stream);
 
 /*
+ * Similarity-guided prediction, choosing the group when the groups are K-Means
+ * clusters of one layer's activation (App. A.2.3): the K-Means assignment
+ * step.  The prompt's feature vector is the mean over its M tokens of the
+ * activation rows act [M, N] (fp32, row stride ld >= N; the same matrix that
+ * coreinfer_select ranks) -- the paper does not say how a sentence's tokens
+ * are summarised, this is a reading.  centroids [G, N] fp32, row-major.
+ * Out (device): dist [G] fp32 = squared Euclidean distance of the feature to
+ * every centroid; best [1] int32 = the nearest centroid, equal distances going
+ * to the lower index (a NaN distance is never nearest; group 0 if all are).
+ * All sums in fp32, in an order that does not depend on scheduling.
+ *   ws: at least coreinfer_assign_centroid_workspace_size(N) bytes (holds the
+ *       feature vector, N floats from its start, readable after the call).
+ * Limits: 1 <= M <= CI_MAX_TOKENS, 1 <= N <= CI_MAX_NEURONS, 1 <= G <= CI_MAX_TOKENS.
+ */
+int coreinfer_assign_centroid_workspace_size(int64_t N, size_t* bytes);
+int coreinfer_assign_centroid(const float* act, int64_t M, int64_t N, int64_t ld, const float* centroids,
+                              int64_t G, int32_t* best, float* dist, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Deploy the core neurons (Sec. 5.3): gather rows S of w_up (and w_gate),
  * entries S of b_up and columns S of w_down into contiguous, neuron-major
  * buffers:

@@ -59,6 +59,8 @@ _SIGNATURES = {
     "coreinfer_group_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_core_similarity": (_int, [_vp, _i64, _vp, _i64, _vp, _vp]),
     "coreinfer_assign_group": (_int, [_vp, _i64, _vp, _i64, _i64, _vp, _vp, _vp]),
+    "coreinfer_assign_centroid_workspace_size": (_int, [_i64, ctypes.POINTER(_sz)]),
+    "coreinfer_assign_centroid": (_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_compact": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64,
                                  _vp, _vp, _vp, _vp, _vp, _vp]),
     "coreinfer_compact_update_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
@@ -211,6 +213,24 @@ def assign_group(prompt_set: torch.Tensor, group_sets: torch.Tensor):
     _check(_lib.coreinfer_assign_group(_ptr(prompt_set), prompt_set.numel(), _ptr(group_sets), G, Kg,
                                        _ptr(best), _ptr(iu), _stream(group_sets)), "coreinfer_assign_group")
     return best, iu
+
+
+def assign_centroid(act: torch.Tensor, centroids: torch.Tensor, ws: Optional[torch.Tensor] = None):
+    """coreinfer_assign_centroid on A [M, N] fp32 and centroids [G, N] fp32 (device).
+    Returns (best [1] int32, dist [G] fp32, feature [N] fp32 = a view of the workspace)."""
+    M, N = act.shape
+    G = centroids.shape[0]
+    if ws is None:
+        b = _sz(0)
+        _check(_lib.coreinfer_assign_centroid_workspace_size(N, ctypes.byref(b)),
+               "coreinfer_assign_centroid_workspace_size")
+        ws = torch.empty(b.value, dtype=torch.uint8, device=act.device)
+    best = torch.empty(1, dtype=torch.int32, device=act.device)
+    dist = torch.empty(G, dtype=torch.float32, device=act.device)
+    _check(_lib.coreinfer_assign_centroid(_ptr(act), M, N, act.stride(0), _ptr(centroids), G, _ptr(best),
+                                          _ptr(dist), _ptr(ws), ws.numel(), _stream(act)),
+           "coreinfer_assign_centroid")
+    return best, dist, ws[:N * 4].view(torch.float32)
 
 
 def compact(w_up, w_gate, b_up, w_down, down_layout: str, act: str, core_idx: torch.Tensor,

@@ -212,6 +212,28 @@ int coreinfer_assign_group(const int32_t* set, int64_t K, const int32_t* group_s
   return launch_assign_group(set, K, group_sets, G, Kg, best, inter_union, (hipStream_t)stream);
 }
 
+int coreinfer_assign_centroid_workspace_size(int64_t N, size_t* bytes) {
+  if (!bytes || N < 1 || N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+  *bytes = round256((size_t)N * sizeof(float));
+  return CI_OK;
+}
+
+int coreinfer_assign_centroid(const float* act, int64_t M, int64_t N, int64_t ld, const float* centroids,
+                              int64_t G, int32_t* best, float* dist, void* ws, size_t ws_bytes, void* stream) {
+  size_t need = 0;
+  if (coreinfer_assign_centroid_workspace_size(N, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (M < 1 || M > CI_MAX_TOKENS || G < 1 || G > CI_MAX_TOKENS) return CI_ERR_INVALID_ARG;
+  if (!act || !centroids || !best || !dist) return CI_ERR_INVALID_ARG;
+  if (ld < N) return CI_ERR_BAD_LAYOUT;
+  if ((reinterpret_cast<uintptr_t>(act) & 3u) || (reinterpret_cast<uintptr_t>(centroids) & 3u) ||
+      (reinterpret_cast<uintptr_t>(best) & 3u) || (reinterpret_cast<uintptr_t>(dist) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
+  return launch_assign_centroid(act, M, N, ld, centroids, G, best, dist, reinterpret_cast<float*>(ws),
+                                (hipStream_t)stream);
+}
+
 int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                       int down_layout, int dtype, int act, int64_t d, int64_t N,
                       const int32_t* core_idx, int64_t K, void* w_up_c, void* w_gate_c,

@@ -162,6 +162,8 @@ int launch_scatter_count(const int32_t* idx, int64_t n_idx, int64_t N, int32_t* 
 int launch_similarity(const int32_t* a, int64_t Ka, const int32_t* b, int64_t Kb, int32_t* out, hipStream_t s);
 int launch_assign_group(const int32_t* set, int64_t K, const int32_t* groups, int64_t G, int64_t Kg,
                         int32_t* best, int32_t* iu, hipStream_t s);
+int launch_assign_centroid(const float* act, int64_t M, int64_t N, int64_t ld, const float* centroids,
+                           int64_t G, int32_t* best, float* dist, float* feature, hipStream_t s);
 int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                    int down_layout, int dtype, int64_t d, int64_t N, const int32_t* core_idx,
                    int64_t K, void* w_up_c, void* w_gate_c, void* b_up_c, void* w_down_c,

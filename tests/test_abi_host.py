@@ -195,6 +195,18 @@ def test_next_row_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert r(F, 4, None, 3, 4, F, F, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 4, F, 3, 4, None, F, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 4, F, 3, 4, F, F + 2, None) == lib.CI_ERR_BAD_LAYOUT
+    r = lib.raw.coreinfer_assign_centroid
+    assert r(None, 4, 64, 64, F, 3, F, F, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 64, None, 3, F, F, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 64, F, 3, None, F, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 64, F, 3, F, None, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 0, 64, 64, F, 3, F, F, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 64, F, 0, F, F, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 0, 64, F, 3, F, F, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 4, 64, 32, F, 3, F, F, F, 1 << 20, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 4, 64, 64, F + 2, 3, F, F, F, 1 << 20, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 4, 64, 64, F, 3, F, F, None, 1 << 20, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 4, 64, 64, F, 3, F, F, F, 100, None) == lib.CI_ERR_WORKSPACE
     r = lib.raw.coreinfer_core_similarity
     assert r(F, 4, F, 4, None, None) == lib.CI_ERR_INVALID_ARG
     assert r(None, 4, F, 4, F, None) == lib.CI_ERR_INVALID_ARG

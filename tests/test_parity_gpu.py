@@ -761,6 +761,39 @@ def test_assign_group_matches_oracle(lib, G, K, Kg, N):
     assert int(best.item()) == g_ref
 
 
+@pytest.mark.parametrize("M,N,G,ld_pad", [(1, 1, 1, 0), (5, 64, 3, 0), (37, 1000, 9, 3), (256, 16384, 40, 0),
+                                          (700, 4100, 300, 0), (64, 36864, 2, 8), (130, 257, 1500, 1)])
+def test_assign_centroid_matches_oracle(lib, M, N, G, ld_pad):
+    """Feature vector and squared distances within fp32 summation error of the fp64 oracle; the
+    chosen group is the oracle's whenever the oracle's margin exceeds that error, and in any
+    case a group whose distance is within it of the smallest."""
+    _say("assign centroid case", M, N, G, ld_pad)
+    rng = np.random.default_rng(M + N + G)
+    centers = rng.standard_normal((G, N)).astype(np.float32) * 0.5
+    own = int(rng.integers(0, G))
+    A = np.maximum(centers[own] + rng.standard_normal((M, N)).astype(np.float32), 0).astype(np.float32)
+    if G >= 3:
+        centers[(own + 1) % G] = centers[own]            # an exact duplicate: the lower index must win
+    buf = torch.zeros(M, N + ld_pad, dtype=torch.float32, device=DEV)
+    buf[:, :N] = torch.from_numpy(A).to(DEV)
+    best, dist, feat = lib.assign_centroid(buf[:, :N], torch.from_numpy(centers).to(DEV))
+    torch.cuda.synchronize()
+    f_ref = orc.sentence_feature(A)
+    g_ref, d_ref = orc.assign_centroid(f_ref, centers)
+    scale = max(float(np.max(np.abs(f_ref))), 1e-30)
+    assert np.max(np.abs(f64(feat) - f_ref)) <= 2e-6 * scale * max(1.0, np.sqrt(M) / 8)
+    tol = 2e-5 * max(float(np.max(d_ref)), 1e-30)
+    assert np.max(np.abs(f64(dist) - d_ref)) <= tol
+    g = int(best.item())
+    assert 0 <= g < G and d_ref[g] <= d_ref[g_ref] + 2 * tol
+    others = np.delete(d_ref, g_ref)
+    if others.size == 0 or np.min(others) > d_ref[g_ref] + 2 * tol:
+        assert g == g_ref
+    # the decision itself is taken on the kernel's own fp32 distances: lowest index among the smallest
+    d_gpu = dist.cpu().numpy()
+    assert g == int(np.flatnonzero(d_gpu == d_gpu.min())[0])
+
+
 def test_decode_graph_replays_match_eager(lib):
     """The decode launches captured in a HIP graph give the eager result on every replay,
     with other work and synchronisations in between."""
