@@ -82,7 +82,9 @@ int coreinfer_version(void);
  *   per reduction workgroup), "decode_nt_store" (0/1), "decode_skip_reduce"
  *   (0/1; 1 launches only the first decode kernel so that it can be timed
  *   alone -- y is then NOT written);
- *   "select_wgs_per_cu" (1..8), "select_debug" (timing only: 1 stops after the
+ *   "select_wgs_per_cu" (1..8; 1 keeps the per-token kernel at one workgroup
+ *   per compute unit also for prompts longer than the chip has compute units),
+ *   "select_debug" (timing only: 1 stops after the
  *   counts, core_idx is then NOT written; 2 runs Def. 2 in one workgroup even
  *   where the parallel kernel applies);
  *   "gemv_wgs_per_cu" (1..32), "gemm_ring" (0/1: register-ring GEMM kernels),
