@@ -776,7 +776,12 @@ int launch_mfma(const GemmArgs& g, hipStream_t s) {
   constexpr int BNO = (EPI == EPI_SWIGLU) ? 128 : 256;
   const int big_tiles = (g.M / GM) * (g.Nn / BNO);
   const bool ring_shape = g.Kk % BK == 0 && g.k_chunk % BK == 0 && params().gemm_ring;
-  const bool big = ring_shape && (EPI == EPI_LINEAR || !BNN) && g.M % GM == 0 && g.Nn % BNO == 0 && g.Kk / BK >= 2 &&
+  // the large-tile kernel addresses an operand through a uniform base and 32-bit byte offsets; a
+  // k-major B is walked along k from one base, so the whole matrix has to stay below 4 GB
+  const bool offsets_fit = (size_t)GM * (size_t)g.lda * 4 + (size_t)g.Kk * 4 < ((size_t)1 << 32) &&
+                           (BNN ? (size_t)g.Kk * (size_t)g.ldb * 4 : (size_t)GM * (size_t)g.ldb * 4 + (size_t)g.Kk * 4) <
+                               ((size_t)1 << 32);
+  const bool big = ring_shape && offsets_fit && (EPI == EPI_LINEAR || !BNN) && g.M % GM == 0 && g.Nn % BNO == 0 && g.Kk / BK >= 2 &&
                    (params().gemm_big == 2 || (params().gemm_big == 1 && big_tiles * splits >= kBigMinWorkgroups));
   if (big) {
     const size_t lds_big = (size_t)2 * 2 * GM * LDK * sizeof(typename D::T);
