@@ -6,7 +6,10 @@
 It launches (a) a plain device-to-device copy of a known size (the calibration
 against which the FETCH_SIZE / WRITE_SIZE readings are scaled) and (b) the
 sparse decode FFN of every layer of the workload, on random compacted buffers
-of the workload's shapes, a few times.  Nothing is timed here.
+of the workload's shapes, a few times.  `--what prefill` runs the prefill side
+instead: the dense FFN of one layer on the workload's prompt, the selection on
+its activations and the deployment of the selected neurons, a few times (for
+instruction-issue and LDS counters of those kernels).  Nothing is timed here.
 """
 
 from __future__ import annotations
@@ -26,12 +29,35 @@ def main():
     p.add_argument("--workload", default="opt6.7b_relu_f16")
     p.add_argument("--layers", type=int, default=8)
     p.add_argument("--reps", type=int, default=3)
+    p.add_argument("--what", choices=["decode", "prefill"], default="decode")
     args = p.parse_args()
     cfg = wl.WORKLOADS[args.workload]
     dev = "cuda:0"
     d, N, B = cfg.d, cfg.N, cfg.sentences
     K = ci.keep_count(cfg.betas[0], N)
     dt = cfg.torch_dtype
+
+    if args.what == "prefill":
+        w = wl.layer_weights(cfg, 0, dev)
+        X = wl.prefill_hidden(cfg, 0, dev)
+        M = X.shape[0]
+        A = torch.empty(M, N, dtype=torch.float32, device=dev)
+        Y = torch.empty(M, d, dtype=dt, device=dev)
+        dws = torch.empty(ci.ffn_dense_workspace_size(M, d, N, dt), dtype=torch.uint8, device=dev)
+        sws = torch.empty(ci.select_workspace_size(M, N), dtype=torch.uint8, device=dev)
+        core = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt = torch.empty(N, dtype=torch.int32, device=dev)
+        bufs = None
+        for _ in range(args.reps):
+            ci.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], cfg.down_layout, cfg.act,
+                         want_y=True, want_a=True, Y=Y, A=A, ws=dws)
+            ci.select(A, cfg.alpha, cfg.betas[0], core_idx=core, counts=cnt, ws=sws)
+            if B == 1:
+                bufs = ci.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act, core,
+                                  out=bufs)
+        torch.cuda.synchronize()
+        print(f"workload {cfg.name}: prefill of one layer, M={M} d={d} N={N} K={K}, {args.reps} times")
+        return
 
     src = torch.empty(COPY_BYTES, dtype=torch.uint8, device=dev).fill_(1)
     dst = torch.empty_like(src)
