@@ -425,6 +425,49 @@ def test_dense_many_tiles_with_split_down_projection(lib, layout):
     assert_close_rms(Y[torch.from_numpy(rows).to(DEV)], Y_ref, torch.float16, "split down projection")
 
 
+@pytest.mark.parametrize("knob,value,default", [("gemm_ring", 0, 1), ("gemm_big", 0, 1), ("select_wgs_per_cu", 1, 2),
+                                                ("select_debug", 2, 0), ("decode_depth", 8, 4), ("decode_depth", 16, 4),
+                                                ("decode_wgs_per_cu", 2, 1), ("decode_nt_store", 0, 1),
+                                                ("reduce_cq", 4, 8), ("reduce_cq", 16, 8), ("union_depth", 16, 8),
+                                                ("union_down_threads", 128, 384)])
+def test_alternative_launch_shapes_give_the_same_results(lib, knob, value, default):
+    """Every tuning knob selects among kernels / launch shapes that must all be correct: one prefill
+    (dense FFN, selection, deployment) and decode (compacted, gathered, union-batched) pass per
+    setting, against the oracle."""
+    _say("knob case", knob, value)
+    M, d, N, B = 300, 512, 2304, 3
+    dt = torch.bfloat16
+    w = rand_weights(d, N, dt, "swiglu", "neuron_major", seed=21, device=DEV)
+    X = torch.randn(M, d, generator=torch.Generator().manual_seed(8)).to(dt).to(DEV)
+    lib.set_param(knob, value)
+    try:
+        Y, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], None, w["w_down"], w["b_down"], "neuron_major", "swiglu",
+                             want_y=True, want_a=True)
+        S, counts = lib.select(A, 0.2, 0.3)
+        c = lib.compact(w["w_up"], w["w_gate"], None, w["w_down"], "neuron_major", "swiglu", S)
+        x = torch.randn(B, d, generator=torch.Generator().manual_seed(9)).to(dt).to(DEV)
+        y_c = lib.ffn_decode(x, lib.make_weights(c["w_up_c"], c["w_gate_c"], None, c["w_down_c"], w["b_down"]), "swiglu")
+        sets = torch.stack([S, S.flip(0).sort().values, S]).contiguous()
+        resident = lib.make_weights(w["w_up"], w["w_gate"], None, w["w_down"], w["b_down"])
+        y_g = lib.ffn_decode(x, lib.make_weights(w["w_up"], w["w_gate"], None, w["w_down"], w["b_down"], core_idx=sets),
+                             "swiglu")
+        uidx, umask, ucount = lib.union_build(sets, N)
+        y_u = lib.ffn_decode_union(x, resident, uidx, umask, ucount, "swiglu")
+        torch.cuda.synchronize()
+    finally:
+        lib.set_param(knob, default)
+    A_ref = orc.score_swiglu(f64(X), f64(w["w_gate"]), f64(w["w_up"]))
+    assert np.max(np.abs(f64(A) - A_ref)) <= 1e-4 * np.sqrt(np.mean(A_ref ** 2))
+    assert_close_rms(Y, _oracle_ffn("swiglu", X, None, w, "neuron_major"), dt, f"{knob}: dense Y")
+    S_ref, c_ref = orc.select(A.cpu().numpy(), 0.2, 0.3)
+    assert S.cpu().numpy().tolist() == S_ref.tolist() and counts.cpu().numpy().tolist() == c_ref.tolist()
+    for b in range(B):
+        ref = _oracle_ffn("swiglu", x[b], S_ref, w, "neuron_major")
+        assert_close_rms(y_c[b], ref, dt, f"{knob}: compacted row {b}")
+        assert_close_rms(y_g[b], ref, dt, f"{knob}: gathered row {b}")
+        assert_close_rms(y_u[b], ref, dt, f"{knob}: union row {b}")
+
+
 def test_tiny_fp32_configuration_end_to_end(lib):
     """The small fp32 configuration, whole: prefill 32 tokens, select, compact,
     16 decode steps; every stage against the oracle."""
