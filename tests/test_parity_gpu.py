@@ -429,7 +429,9 @@ def test_dense_many_tiles_with_split_down_projection(lib, layout):
                                                 ("select_debug", 2, 0), ("decode_depth", 8, 4), ("decode_depth", 16, 4),
                                                 ("decode_wgs_per_cu", 2, 1), ("decode_nt_store", 0, 1),
                                                 ("reduce_cq", 4, 8), ("reduce_cq", 16, 8), ("union_depth", 16, 8),
-                                                ("union_down_threads", 128, 384)])
+                                                ("union_down_threads", 128, 384), ("decode_threads", 512, 0), ("decode_threads", 64, 0),
+                                                ("decode_wgs", 7, 0), ("decode_wgs", 1024, 0), ("union_up_wgs_per_cu", 3, 1),
+                                                ("union_down_wgs_per_cu", 1, 2)])
 def test_alternative_launch_shapes_give_the_same_results(lib, knob, value, default):
     """Every tuning knob selects among kernels / launch shapes that must all be correct: one prefill
     (dense FFN, selection, deployment) and decode (compacted, gathered, union-batched) pass per
