@@ -10,6 +10,8 @@
 //                             LDS so that both the reads (along S, which is
 //                             ascending) and the writes (along j) touch whole
 //                             cache lines.
+//   compact_fused_kernel    : both of the above in one launch (column tiles
+//                             first) when the down matrix is [d, N].
 #include "common.hpp"
 
 namespace ci {
@@ -30,10 +32,8 @@ __device__ __forceinline__ bool index_ok(const int32_t* idx, int k, int N) {
   return n >= 0 && n < N && (k == 0 || idx[k - 1] < n);
 }
 
-__global__ __launch_bounds__(256) void gather_rows_kernel(RowGather g, const int32_t* __restrict__ idx,
-                                                          int K, int N, int vecs_per_row,
-                                                          int32_t* status) {
-  const int k = blockIdx.x, mat = blockIdx.y;
+__device__ __forceinline__ void gather_row(const RowGather& g, const int32_t* __restrict__ idx, int k, int mat,
+                                           int N, int vecs_per_row, int32_t* status) {
   const bool ok = index_ok(idx, k, N);
   const size_t src = ok ? (size_t)idx[k] : 0;
   const uint4* in = reinterpret_cast<const uint4*>(g.in[mat]) + src * vecs_per_row;
@@ -51,13 +51,19 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(RowGather g, const int
   }
 }
 
+__global__ __launch_bounds__(256) void gather_rows_kernel(RowGather g, const int32_t* __restrict__ idx,
+                                                          int K, int N, int vecs_per_row,
+                                                          int32_t* status) {
+  gather_row(g, idx, blockIdx.x, blockIdx.y, N, vecs_per_row, status);
+}
+
+// One 64 x 64 tile of out[k, j] = in[j, S[k]]: tile column block bk, row block bj.
 template <class E>
-__global__ __launch_bounds__(256) void gather_cols_t_kernel(const E* __restrict__ in, E* __restrict__ out,
-                                                            const int32_t* __restrict__ idx, int K,
-                                                            int N, int d) {
-  __shared__ E tile[64][65];
+__device__ __forceinline__ void gather_cols_tile(const E* __restrict__ in, E* __restrict__ out,
+                                                 const int32_t* __restrict__ idx, int K, int N, int d, int bk,
+                                                 int bj, E (*tile)[65]) {
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int k0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  const int k0 = bk * 64, j0 = bj * 64;
   const int k = k0 + tx;
   bool ok = false;
   size_t n = 0;
@@ -84,6 +90,33 @@ __global__ __launch_bounds__(256) void gather_cols_t_kernel(const E* __restrict_
   for (int i = 0; i < 16; ++i) {
     const int kk = ty + 4 * i;
     if (k0 + kk < K && j < d) out[(size_t)(k0 + kk) * d + j] = v[i];
+  }
+}
+
+template <class E>
+__global__ __launch_bounds__(256) void gather_cols_t_kernel(const E* __restrict__ in, E* __restrict__ out,
+                                                            const int32_t* __restrict__ idx, int K,
+                                                            int N, int d) {
+  __shared__ E tile[64][65];
+  gather_cols_tile<E>(in, out, idx, K, N, d, blockIdx.x, blockIdx.y, tile);
+}
+
+// Whole deployment with an nn.Linear ([d, N]) down matrix in one launch: the first n_col_blocks
+// workgroups transpose-gather the down columns (the longer part, so it starts first), the rest copy
+// rows of up / gate.  One launch instead of two, and the two streams overlap.
+template <class E>
+__global__ __launch_bounds__(256) void compact_fused_kernel(RowGather g, const E* __restrict__ w_down,
+                                                            E* __restrict__ w_down_c,
+                                                            const int32_t* __restrict__ idx, int K, int N, int d,
+                                                            int vecs_per_row, int kblocks, int n_col_blocks,
+                                                            int32_t* status) {
+  __shared__ E tile[64][65];
+  const int b = blockIdx.x;
+  if (b < n_col_blocks) {
+    gather_cols_tile<E>(w_down, w_down_c, idx, K, N, d, b % kblocks, b / kblocks, tile);
+  } else {
+    const int r = b - n_col_blocks;
+    gather_row(g, idx, r % K, r / K, N, vecs_per_row, status);
   }
 }
 
@@ -271,6 +304,23 @@ int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const
   g.b_out = b_up_c;
   g.elem = e;
   const int vecs = (int)(d * e / 16);
+  if (down_layout == CI_DOWN_OUT_MAJOR) {
+    const int kblocks = (int)((K + 63) / 64);
+    const int64_t n_col = (int64_t)kblocks * ((d + 63) / 64);
+    const int64_t total = n_col + K * g.n_mat;
+    if (total < ((int64_t)1 << 31)) {
+      if (e == 2)
+        hipLaunchKernelGGL((compact_fused_kernel<uint16_t>), dim3((unsigned)total), dim3(256), 0, s, g,
+                           reinterpret_cast<const uint16_t*>(w_down), reinterpret_cast<uint16_t*>(w_down_c),
+                           core_idx, (int)K, (int)N, (int)d, vecs, kblocks, (int)n_col, status);
+      else
+        hipLaunchKernelGGL((compact_fused_kernel<uint32_t>), dim3((unsigned)total), dim3(256), 0, s, g,
+                           reinterpret_cast<const uint32_t*>(w_down), reinterpret_cast<uint32_t*>(w_down_c),
+                           core_idx, (int)K, (int)N, (int)d, vecs, kblocks, (int)n_col, status);
+      CI_HIP_CHECK_LAUNCH();
+      return CI_OK;
+    }
+  }
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)K, g.n_mat), dim3(256), 0, s, g, core_idx,
                      (int)K, (int)N, vecs, status);
   CI_HIP_CHECK_LAUNCH();
