@@ -876,7 +876,7 @@ int launch_gemm_up(const void* X, int64_t M, const void* w_up, const void* w_gat
 // functions of the shape; the workspace is sized for the larger of the two.
 static int down_splits_small(int64_t M, int64_t d, int64_t N) {
   const int64_t tiles = ((M + BM - 1) / BM) * ((d + BN - 1) / BN);
-  int64_t s = (512 + tiles - 1) / tiles;
+  int64_t s = (256 + tiles - 1) / tiles;
   const int64_t max_by_k = (N + 4 * BK - 1) / (4 * BK);  // at least four k tiles per split
   if (s > max_by_k) s = max_by_k;
   if (s > 8) s = 8;
