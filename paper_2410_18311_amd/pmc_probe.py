@@ -9,7 +9,9 @@ sparse decode FFN of every layer of the workload, on random compacted buffers
 of the workload's shapes, a few times.  `--what prefill` runs the prefill side
 instead: the dense FFN of one layer on the workload's prompt, the selection on
 its activations and the deployment of the selected neurons, a few times (for
-instruction-issue and LDS counters of those kernels).  Nothing is timed here.
+instruction-issue and LDS counters of those kernels); `--what union` runs the
+union-batched decode of the workload's sentences over resident weights after
+the calibration copy.  Nothing is timed here.
 """
 
 from __future__ import annotations
@@ -29,7 +31,7 @@ def main():
     p.add_argument("--workload", default="opt6.7b_relu_f16")
     p.add_argument("--layers", type=int, default=8)
     p.add_argument("--reps", type=int, default=3)
-    p.add_argument("--what", choices=["decode", "prefill"], default="decode")
+    p.add_argument("--what", choices=["decode", "prefill", "union"], default="decode")
     args = p.parse_args()
     cfg = wl.WORKLOADS[args.workload]
     dev = "cuda:0"
@@ -83,6 +85,21 @@ def main():
     x = mk(B, d) * 50
     y = torch.empty_like(x)
     ws = torch.empty(ci.ffn_decode_workspace_size(B, K, d), dtype=torch.uint8, device=dev)
+    if args.what == "union":
+        rows_total = 0
+        for _ in range(args.reps):
+            for desc, (up, gate, bias, down, idx) in layers:
+                sets = idx if idx is not None else torch.sort(torch.randperm(N, generator=g, device=dev)[:K]).values.to(torch.int32).unsqueeze(0)
+                uidx, umask, ucount = ci.union_build(sets.contiguous(), up.shape[0])
+                resident = ci.make_weights(up, gate, bias, down, None)
+                ci.ffn_decode_union(x[:sets.shape[0]], resident, uidx, umask, ucount, cfg.act)
+                rows_total = int(ucount.item())
+        torch.cuda.synchronize()
+        e = 2 if cfg.dtype != "f32" else 4
+        print(f"workload {cfg.name}: union of {B} core sets of {K} = {rows_total} of {N} rows (last layer); "
+              f"algorithmic bytes per union-batched decode = {cfg.n_mat * rows_total * d * e} "
+              f"(each row of up / gate / down once); calibration copy = {COPY_BYTES} bytes read + {COPY_BYTES} bytes written")
+        return
     for _ in range(args.reps):
         for desc, _keep in layers:
             ci.ffn_decode(x, desc, cfg.act, y=y, ws=ws)
