@@ -270,25 +270,63 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
     // index of the last tie that is taken; ties in index order = iteration, then wave, then lane
     if (tid == 0) cut_s = 0x7fffffffu;  // all ties taken (the usual case: need == n_eq)
     if (need != n_eq) {                 // uniform
-      uint32_t base = 0;                // ties seen in earlier iterations
-      for_items<ITEMS>(n_iter, [&](int i) {
-        if (base < need) {  // uniform condition
-          const bool tie = key_at(i) == T;  // T < 2^31, so elements without a key never match
-          const uint64_t bal = __ballot(tie);
-          __syncthreads();
-          if (lane == 0) sh.wave_tot[wave] = (uint32_t)__popcll(bal);
-          __syncthreads();
-          uint32_t before = base, tot = 0;
-          for (int w = 0; w < nw; ++w) {
-            const uint32_t c = sh.wave_tot[w];
-            if (w < wave) before += c;
-            tot += c;
+      if constexpr (ITEMS > 0) {
+        // keys in registers: ties per (iteration, wave) go to LDS (the histograms are done with),
+        // then every thread finds the one iteration that holds the last tie taken and only that
+        // iteration is ranked lane by lane -- three barriers whatever the number of ties
+        uint32_t* cnt = hist;                        // [n_iter][nw]
+        uint32_t* itot = hist + ITEMS * kMaxWaves;   // [n_iter]
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+          if (i < n_iter) {
+            const uint32_t c = wave_count(kc[i] == T);  // T < 2^31, so elements without a key never match
+            if (lane == 0) cnt[i * nw + wave] = c;
           }
-          const uint32_t rank = before + (uint32_t)__popcll(bal & lanemask_lt());
-          if (tie && rank == need - 1) cut_s = (uint32_t)(i * nt + tid);
-          base += tot;
         }
-      });
+        __syncthreads();
+        if (tid < n_iter) {
+          uint32_t t = 0;
+          for (int w = 0; w < nw; ++w) t += cnt[tid * nw + w];
+          itot[tid] = t;
+        }
+        __syncthreads();
+        uint32_t base = 0;  // ties in earlier iterations
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+          if (i < n_iter) {
+            const uint32_t t = itot[i];
+            if (base < need && need <= base + t) {  // uniform: the (need - 1)-th tie lies in this iteration
+              const bool tie = kc[i] == T;
+              const uint64_t bal = __ballot(tie);
+              uint32_t before = base;
+              for (int w = 0; w < wave; ++w) before += cnt[i * nw + w];
+              const uint32_t rank = before + (uint32_t)__popcll(bal & lanemask_lt());
+              if (tie && rank == need - 1) cut_s = (uint32_t)(i * nt + tid);
+            }
+            base += t;
+          }
+        }
+      } else {
+        uint32_t base = 0;                // ties seen in earlier iterations
+        for_items<ITEMS>(n_iter, [&](int i) {
+          if (base < need) {  // uniform condition
+            const bool tie = key_at(i) == T;  // T < 2^31, so elements without a key never match
+            const uint64_t bal = __ballot(tie);
+            __syncthreads();
+            if (lane == 0) sh.wave_tot[wave] = (uint32_t)__popcll(bal);
+            __syncthreads();
+            uint32_t before = base, tot = 0;
+            for (int w = 0; w < nw; ++w) {
+              const uint32_t c = sh.wave_tot[w];
+              if (w < wave) before += c;
+              tot += c;
+            }
+            const uint32_t rank = before + (uint32_t)__popcll(bal & lanemask_lt());
+            if (tie && rank == need - 1) cut_s = (uint32_t)(i * nt + tid);
+            base += tot;
+          }
+        });
+      }
     }
     __syncthreads();
     if (tid == 0) { thr[2 * m] = T; thr[2 * m + 1] = cut_s; }
