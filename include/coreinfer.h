@@ -134,6 +134,25 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld,
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same selection on the hidden matrix as the FFN holds it, in the layer's
+ * element type, so that no fp32 copy of the activations has to be written for
+ * it (Sec. 1 calls the prefill-stage selection free of extra cost; Def. 1
+ * ranks "the activation", and a 16-bit model holds 16-bit activations).
+ *   hidden [M, N] of `dtype` (row stride ld >= N elements), as written by
+ *   coreinfer_ffn_dense_hidden: max(z, 0) for CI_ACT_RELU, SiLU(gate) * up for
+ *   CI_ACT_SWIGLU.  The value ranked is the element itself for CI_ACT_RELU and
+ *   its magnitude for CI_ACT_SWIGLU; 16-bit values are compared exactly (their
+ *   fp32 images).  Everything else -- keep counts, ties towards the lower
+ *   index, outputs, workspace, limits -- as for coreinfer_select; with
+ *   CI_F32 / CI_ACT_RELU the two calls are the same.  Equal activations are far
+ *   more frequent among 16-bit values; they are resolved towards the lower
+ *   neuron index like any other tie.
+ */
+int coreinfer_select_hidden(const void* hidden, int dtype, int act, int64_t M, int64_t N, int64_t ld,
+                            double alpha, double beta, int32_t* core_idx, int32_t* counts, void* ws,
+                            size_t ws_bytes, void* stream);
+
+/*
  * The two halves of coreinfer_select as separate calls, for callers that keep
  * running counts while a sentence grows (Fig. 1 names a "stability estimation"
  * that decides how the set is updated but does not specify it; Eq. 3 is a sum
@@ -335,6 +354,21 @@ int coreinfer_ffn_dense(const void* X, int64_t M,
                         int dtype, int act, int64_t d, int64_t N,
                         void* Y, float* A,
                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dense FFN that hands out the hidden matrix instead of fp32 scores: the
+ * prefill pass for coreinfer_select_hidden.  H [M, N] (caller-allocated, of
+ * `dtype`, 16-byte aligned) receives max(X w_up^T + b_up, 0) or
+ * SiLU(X w_gate^T) * (X w_up^T), rounded once from the fp32 accumulator; Y
+ * (nullable) = H w_down^T + b_down as in coreinfer_ffn_dense.  No fp32 matrix
+ * of size M x N is written.  Arguments, layouts and errors as for
+ * coreinfer_ffn_dense; the workspace only holds split partial products of Y.
+ */
+int coreinfer_ffn_dense_hidden_workspace_size(int64_t M, int64_t d, int64_t N, int dtype, size_t* bytes);
+int coreinfer_ffn_dense_hidden(const void* X, int64_t M, const void* w_up, const void* w_gate,
+                               const void* b_up, const void* w_down, const void* b_down, int down_layout,
+                               int dtype, int act, int64_t d, int64_t N, void* Y, void* H, void* ws,
+                               size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -54,6 +54,7 @@ _SIGNATURES = {
     "coreinfer_keep_count": (_int, [_dbl, _i64, ctypes.POINTER(_i64)]),
     "coreinfer_select_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
+    "coreinfer_select_hidden": (_int, [_vp, _int, _int, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_count_tokens": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _int, _vp, _sz, _vp]),
     "coreinfer_count_select": (_int, [_vp, _i64, _i64, _dbl, _vp, _vp, _sz, _vp]),
     "coreinfer_group_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _vp, _vp, _sz, _vp]),
@@ -74,6 +75,9 @@ _SIGNATURES = {
     "coreinfer_ffn_decode_union_workspace_size": (_int, [_i64, _i64, _i64, _int, _int, ctypes.POINTER(_sz)]),
     "coreinfer_ffn_decode_union": (_int, [_vp, _i64, ctypes.POINTER(ci_ffn_weights), _vp, _vp, _vp, _i64,
                                           _int, _int, _vp, _vp, _sz, _vp]),
+    "coreinfer_ffn_dense_hidden_workspace_size": (_int, [_i64, _i64, _i64, _int, ctypes.POINTER(_sz)]),
+    "coreinfer_ffn_dense_hidden": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _vp,
+                                          _vp, _sz, _vp]),
     "coreinfer_ffn_dense_workspace_size": (_int, [_i64, _i64, _i64, _int, ctypes.POINTER(_sz)]),
     "coreinfer_ffn_dense": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64,
                                    _vp, _vp, _vp, _sz, _vp]),
@@ -148,6 +152,26 @@ def select(act: torch.Tensor, alpha: float, beta: float, core_idx: Optional[torc
     _check(_lib.coreinfer_select(_ptr(act), M, N, act.stride(0), float(alpha), float(beta),
                                  _ptr(core_idx), _ptr(counts), _ptr(ws), ws.numel(), _stream(act)),
            "coreinfer_select")
+    return core_idx, counts
+
+
+def select_hidden(hidden: torch.Tensor, act: str, alpha: float, beta: float,
+                  core_idx: Optional[torch.Tensor] = None, counts: Optional[torch.Tensor] = None,
+                  ws: Optional[torch.Tensor] = None):
+    """coreinfer_select_hidden on H [M, N] of the layer's element type.  Returns (core_idx, counts)."""
+    assert hidden.dim() == 2 and hidden.stride(1) == 1
+    M, N = hidden.shape
+    K = keep_count(beta, N)
+    if core_idx is None:
+        core_idx = torch.empty(K, dtype=torch.int32, device=hidden.device)
+    if counts is None:
+        counts = torch.empty(N, dtype=torch.int32, device=hidden.device)
+    if ws is None:
+        ws = _workspace(select_workspace_size(M, N), hidden)
+    _check(_lib.coreinfer_select_hidden(_ptr(hidden), DTYPE_CODE[hidden.dtype], ACT_CODE[act], M, N,
+                                        hidden.stride(0), float(alpha), float(beta), _ptr(core_idx),
+                                        _ptr(counts), _ptr(ws), ws.numel(), _stream(hidden)),
+           "coreinfer_select_hidden")
     return core_idx, counts
 
 
@@ -377,3 +401,25 @@ def ffn_dense(X: torch.Tensor, w_up, w_gate, b_up, w_down, b_down, down_layout: 
                                     _stream(X)),
            "coreinfer_ffn_dense")
     return Y, A
+
+
+def ffn_dense_hidden(X: torch.Tensor, w_up, w_gate, b_up, w_down, b_down, down_layout: str, act: str,
+                     want_y: bool = True, Y=None, H=None, ws=None):
+    """coreinfer_ffn_dense_hidden on X [M, d].  Returns (Y or None, H [M, N] of X's dtype)."""
+    M, d = X.shape
+    N = w_up.shape[0]
+    if want_y and Y is None:
+        Y = torch.empty((M, d), dtype=X.dtype, device=X.device)
+    if H is None:
+        H = torch.empty((M, N), dtype=X.dtype, device=X.device)
+    if ws is None:
+        b = _sz(0)
+        _check(_lib.coreinfer_ffn_dense_hidden_workspace_size(M, d, N, DTYPE_CODE[X.dtype], ctypes.byref(b)),
+               "coreinfer_ffn_dense_hidden_workspace_size")
+        ws = _workspace(b.value, X)
+    _check(_lib.coreinfer_ffn_dense_hidden(_ptr(X), M, _ptr(w_up), _ptr(w_gate), _ptr(b_up), _ptr(w_down),
+                                           _ptr(b_down), LAYOUT_CODE[down_layout], DTYPE_CODE[X.dtype],
+                                           ACT_CODE[act], d, N, _ptr(Y), _ptr(H), _ptr(ws), ws.numel(),
+                                           _stream(X)),
+           "coreinfer_ffn_dense_hidden")
+    return Y, H

@@ -135,8 +135,29 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld, double 
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
   int32_t* cnt = counts ? counts : ws_counts(ws, M, N);
-  return launch_select(act, M, N, ld, qa, keep(qb, N), M, core_idx, cnt, ws, kSelTokens | kSelFinal,
+  return launch_select(act, CI_F32, 0, M, N, ld, qa, keep(qb, N), M, core_idx, cnt, ws, kSelTokens | kSelFinal,
                        (hipStream_t)stream);
+}
+
+int coreinfer_select_hidden(const void* hidden, int dtype, int act, int64_t M, int64_t N, int64_t ld, double alpha,
+                            double beta, int32_t* core_idx, int32_t* counts, void* ws, size_t ws_bytes,
+                            void* stream) {
+  if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  size_t need = 0;
+  if (coreinfer_select_workspace_size(M, N, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!hidden || !core_idx) return CI_ERR_INVALID_ARG;
+  const int64_t qa = fraction_ppm(alpha), qb = fraction_ppm(beta);
+  if (qa == 0 || qb == 0) return CI_ERR_INVALID_ARG;
+  if (ld < N) return CI_ERR_BAD_LAYOUT;
+  const uintptr_t elem = dtype == CI_F32 ? 4 : 2;
+  if ((reinterpret_cast<uintptr_t>(hidden) & (elem - 1)) || (reinterpret_cast<uintptr_t>(core_idx) & 3u) ||
+      (reinterpret_cast<uintptr_t>(counts) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
+  int32_t* cnt = counts ? counts : ws_counts(ws, M, N);
+  return launch_select(hidden, dtype, act == CI_ACT_SWIGLU ? 1 : 0, M, N, ld, qa, keep(qb, N), M, core_idx, cnt, ws,
+                       kSelTokens | kSelFinal, (hipStream_t)stream);
 }
 
 int coreinfer_count_tokens(const float* act, int64_t M, int64_t N, int64_t ld, double alpha,
@@ -150,7 +171,7 @@ int coreinfer_count_tokens(const float* act, int64_t M, int64_t N, int64_t ld, d
   if ((reinterpret_cast<uintptr_t>(act) & 3u) || (reinterpret_cast<uintptr_t>(counts) & 3u)) return CI_ERR_BAD_LAYOUT;
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
-  return launch_select(act, M, N, ld, qa, 1, M, nullptr, counts, ws,
+  return launch_select(act, CI_F32, 0, M, N, ld, qa, 1, M, nullptr, counts, ws,
                        kSelTokens | (accumulate ? kSelAccumulate : 0), (hipStream_t)stream);
 }
 
@@ -164,7 +185,7 @@ int coreinfer_count_select(const int32_t* counts, int64_t N, int64_t max_count, 
   if (!ws || ws_bytes < 256) return CI_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
   // Def. 2 alone runs in one workgroup and needs no scratch
-  return launch_select(nullptr, 0, N, N, 1, keep(qb, N), max_count, core_idx, const_cast<int32_t*>(counts),
+  return launch_select(nullptr, CI_F32, 0, 0, N, N, 1, keep(qb, N), max_count, core_idx, const_cast<int32_t*>(counts),
                        nullptr, kSelFinal, (hipStream_t)stream);
 }
 
@@ -183,11 +204,11 @@ int coreinfer_group_select(const int32_t* core_sets, int64_t G, int64_t K, int64
   int32_t* cnt = counts ? counts : ws_counts(ws, G, N);
   hipStream_t s = (hipStream_t)stream;
   // clear the counters, count the groups' members, then Def. 2 with gamma on the counters
-  int rc = launch_select(nullptr, 0, N, N, 1, 1, G, nullptr, cnt, nullptr, kSelZero, s);
+  int rc = launch_select(nullptr, CI_F32, 0, 0, N, N, 1, 1, G, nullptr, cnt, nullptr, kSelZero, s);
   if (rc != CI_OK) return rc;
   rc = launch_scatter_count(core_sets, G * K, N, cnt, s);
   if (rc != CI_OK) return rc;
-  return launch_select(nullptr, 0, N, N, 1, keep(qg, N), G, core_idx, cnt, nullptr, kSelFinal, s);
+  return launch_select(nullptr, CI_F32, 0, 0, N, N, 1, keep(qg, N), G, core_idx, cnt, nullptr, kSelFinal, s);
 }
 
 int coreinfer_core_similarity(const int32_t* set_a, int64_t Ka, const int32_t* set_b, int64_t Kb,
@@ -432,6 +453,36 @@ int coreinfer_ffn_dense(const void* X, int64_t M, const void* w_up, const void* 
   float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) +
                                             round256((size_t)M * (size_t)N * sizeof(float)));
   return launch_gemm_down(H, M, w_down, b_down, down_layout, dtype, d, N, Y, partial, s);
+}
+
+int coreinfer_ffn_dense_hidden_workspace_size(int64_t M, int64_t d, int64_t N, int dtype, size_t* bytes) {
+  if (!dtype_ok(dtype)) return CI_ERR_BAD_DTYPE;
+  if (!bytes || M < 1 || M > CI_MAX_TOKENS || d < 1 || d > CI_MAX_DMODEL || N < 1 || N > CI_MAX_NEURONS)
+    return CI_ERR_INVALID_ARG;
+  const int splits = gemm_down_splits_max(M, d, N, dtype);  // split-K partial products of Y
+  *bytes = (splits > 1 ? round256((size_t)splits * (size_t)M * (size_t)d * sizeof(float)) : 0) + 256;
+  return CI_OK;
+}
+
+int coreinfer_ffn_dense_hidden(const void* X, int64_t M, const void* w_up, const void* w_gate, const void* b_up,
+                               const void* w_down, const void* b_down, int down_layout, int dtype, int act,
+                               int64_t d, int64_t N, void* Y, void* H, void* ws, size_t ws_bytes, void* stream) {
+  if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  if (!layout_ok(down_layout)) return CI_ERR_BAD_LAYOUT;
+  size_t need = 0;
+  if (coreinfer_ffn_dense_hidden_workspace_size(M, d, N, dtype, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!X || !w_up || !H || (Y && !w_down)) return CI_ERR_INVALID_ARG;
+  if ((act == CI_ACT_SWIGLU) != (w_gate != nullptr)) return CI_ERR_INVALID_ARG;
+  if (d % vec_of(dtype) != 0 || N % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
+  if (!aligned16(X) || !aligned16(w_up) || !aligned16(w_gate) || !aligned16(w_down) || !aligned16(Y) ||
+      !aligned16(H))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
+  hipStream_t s = (hipStream_t)stream;
+  int rc = launch_gemm_up(X, M, w_up, w_gate, b_up, dtype, act, d, N, H, nullptr, s);
+  if (rc != CI_OK || !Y) return rc;
+  return launch_gemm_down(H, M, w_down, b_down, down_layout, dtype, d, N, Y, reinterpret_cast<float*>(ws), s);
 }
 
 }  // extern "C"

@@ -155,8 +155,8 @@ struct SelectWs {
 };
 void select_ws_layout(int64_t M, int64_t N, SelectWs* w);
 // ws: laid out by select_ws_layout (may be null when only kSelZero is asked for)
-int launch_select(const float* act, int64_t M, int64_t N, int64_t ld, int64_t q_alpha, int64_t K,
-                  int64_t max_count, int32_t* core_idx, int32_t* counts, void* ws, int what,
+int launch_select(const void* act, int act_dtype, int take_abs, int64_t M, int64_t N, int64_t ld, int64_t q_alpha,
+                  int64_t K, int64_t max_count, int32_t* core_idx, int32_t* counts, void* ws, int what,
                   hipStream_t s);
 int launch_scatter_count(const int32_t* idx, int64_t n_idx, int64_t N, int32_t* counts, hipStream_t s);
 int launch_similarity(const int32_t* a, int64_t Ka, const int32_t* b, int64_t Kb, int32_t* out, hipStream_t s);

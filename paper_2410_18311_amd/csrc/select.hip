@@ -42,6 +42,27 @@ constexpr int kCopyStride = kBins + 8;   // words; the +8 spreads the replicas o
 constexpr int kHistWords = kCopies * kCopyStride;
 constexpr int kMaxWaves = 16;
 constexpr uint32_t kNoKey = 0xffffffffu;  // stands for an activation that is not positive
+
+// Element types the activation matrix may have; bits() gives the IEEE fp32 bits of a value (the
+// conversions from the 16-bit types are exact, so ranking the bits ranks the values).
+struct InF32 {
+  using T = float;
+  static __device__ __forceinline__ uint32_t bits(float v) { return f2u(v); }
+};
+struct InF16 {
+  using T = _Float16;
+  static __device__ __forceinline__ uint32_t bits(_Float16 v) { return f2u((float)v); }
+};
+struct InBF16 {
+  using T = uint16_t;
+  static __device__ __forceinline__ uint32_t bits(uint16_t v) { return (uint32_t)v << 16; }
+};
+// Key of an activation: its fp32 bits (of its magnitude when `mask` clears the sign bit) if that is
+// a positive number, +inf included; else `none`.  NaN, zeros and negatives give `none`.
+__device__ __forceinline__ uint32_t act_key(uint32_t bits, uint32_t mask, uint32_t none) {
+  bits &= mask;
+  return (bits - 1u < 0x7f800000u) ? bits : none;
+}
 constexpr int kCountBins = 2048;  // counts below this go to a global histogram for the parallel Def. 2
 constexpr int kHistCopies = 8;    // copies of that histogram, by workgroup: atomics on one address serialise
 
@@ -156,11 +177,12 @@ __device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, 
   __syncthreads();  // sh is reused by the next pass
 }
 
-template <int ITEMS, bool TWO>  // TWO: registers capped so that two workgroups of 16 waves share a compute unit
-__global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(const float* __restrict__ act, int M, int N,
-                                                               int64_t ld, int64_t q_alpha,
-                                                               uint32_t* __restrict__ thr,
+template <int ITEMS, bool TWO, class IN>  // TWO: registers capped so that two workgroups of 16 waves share a compute unit
+__global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(const typename IN::T* __restrict__ act,
+                                                               int M, int N, int64_t ld, int64_t q_alpha,
+                                                               uint32_t sign_mask, uint32_t* __restrict__ thr,
                                                                uint32_t* ghist) {
+  using TI = typename IN::T;
   __shared__ SelShared sh;
   __shared__ uint32_t cut_s;
   constexpr int kCand = 64;
@@ -175,7 +197,7 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
     for (int j = blockIdx.x * nt + tid; j < kCountBins * kHistCopies; j += gridDim.x * nt) ghist[j] = 0u;
 
   for (int m = blockIdx.x; m < M; m += gridDim.x) {
-    const float* row = act + (size_t)m * ld;
+    const TI* row = act + (size_t)m * ld;
     uint32_t kc[ITEMS > 0 ? ITEMS : 1];
     uint32_t npos = 0;
     uint32_t lane_id = (uint32_t)tid;  // thread index within the workgroup
@@ -186,20 +208,20 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
       constexpr int BATCH = ITEMS > 16 ? 8 : (ITEMS > 0 ? ITEMS : 1);
 #pragma unroll
       for (int i0 = 0; i0 < ITEMS; i0 += BATCH) {
-        float av[BATCH];
+        TI av[BATCH];
 #pragma unroll
         for (int j = 0; j < BATCH; ++j) {
           // uniform base of the item + a 32-bit lane offset (clamped inside the row); the lane
           // index is made opaque per token so that the offsets are not all computed ahead of
           // the token loop and kept in two registers each
           const int s0 = ((i0 + j) * nt < N) ? (i0 + j) * nt : 0;
-          const float* item = row + s0;
+          const TI* item = row + s0;
           av[j] = item[min(lane_id, (uint32_t)(N - 1 - s0))];
         }
 #pragma unroll
         for (int j = 0; j < BATCH; ++j) {
           const uint32_t e = (uint32_t)((i0 + j) * nt) + lane_id;
-          kc[i0 + j] = (e < (uint32_t)N && av[j] > 0.f) ? f2u(av[j]) : kNoKey;
+          kc[i0 + j] = e < (uint32_t)N ? act_key(IN::bits(av[j]), sign_mask, kNoKey) : kNoKey;
         }
       }
 #pragma unroll
@@ -207,7 +229,7 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
     } else {
       for (int i = 0; i < n_iter; ++i) {
         const int e = i * nt + tid;
-        npos += wave_count(e < N && row[e] > 0.f);
+        npos += wave_count(e < N && act_key(IN::bits(row[e]), sign_mask, kNoKey) != kNoKey);
       }
     }
     // key of this thread's i-th element.  Elements that are not positive, and those past the end,
@@ -217,8 +239,7 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
       if (ITEMS > 0) return kc[ITEMS > 0 ? i : 0];  // i is a constant after unrolling
       const int e = i * nt + tid;
       if (e >= N) return kNoKey;
-      const float a = row[e];
-      return (a > 0.f) ? f2u(a) : kNoKey;
+      return act_key(IN::bits(row[e]), sign_mask, kNoKey);
     };
     auto key_sel = key_at;
 
@@ -338,24 +359,32 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
 // covers TPW tokens (lane / (64 / TPW) picks the token, the other lane bits the neuron quad); waves
 // take batches of UN * TPW tokens in turn, UN loads per lane in flight.  VEC: one 16-byte load per
 // token, else four clamped 4-byte loads (unaligned rows or the last neurons of the layer).
-template <bool VEC, int TPW>
-__device__ __forceinline__ void count_tokens_of_lane(const float* __restrict__ act, int64_t ld,
-                                                     const uint32_t* __restrict__ thr, int M, int N,
+template <bool VEC, int TPW, class IN>
+__device__ __forceinline__ void count_tokens_of_lane(const typename IN::T* __restrict__ act, int64_t ld,
+                                                     const uint32_t* __restrict__ thr, int M, int N, uint32_t sign_mask,
                                                      int n0, int ts, int wave, int nw, uint32_t (&cnt)[4]) {
+  using TI = typename IN::T;
   constexpr int UN = 8;
   for (int m0 = wave * UN * TPW; m0 < M; m0 += nw * UN * TPW) {
-    float v[UN][4];
+    uint32_t vb[UN][4];  // fp32 bits of the four activations
     uint32_t T[UN], cut[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const int m = min(m0 + u * TPW + ts, M - 1);  // clamped: a repeated token is masked below
-      const float* p = act + (size_t)m * ld;
+      const TI* p = act + (size_t)m * ld;
       if (VEC) {
-        const float4 q = *reinterpret_cast<const float4*>(p + n0);
-        v[u][0] = q.x; v[u][1] = q.y; v[u][2] = q.z; v[u][3] = q.w;
+        if constexpr (sizeof(TI) == 4) {
+          const float4 q = *reinterpret_cast<const float4*>(p + n0);
+          vb[u][0] = f2u(q.x); vb[u][1] = f2u(q.y); vb[u][2] = f2u(q.z); vb[u][3] = f2u(q.w);
+        } else {
+          struct alignas(8) Quad { TI e[4]; };
+          const Quad q = *reinterpret_cast<const Quad*>(p + n0);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) vb[u][c] = IN::bits(q.e[c]);
+        }
       } else {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) v[u][c] = p[min(n0 + c, N - 1)];
+        for (int c = 0; c < 4; ++c) vb[u][c] = IN::bits(p[min(n0 + c, N - 1)]);
       }
       T[u] = thr[2 * m];
       cut[u] = thr[2 * m + 1];
@@ -365,7 +394,7 @@ __device__ __forceinline__ void count_tokens_of_lane(const float* __restrict__ a
       const uint32_t live = (m0 + u * TPW + ts < M) ? 1u : 0u;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const uint32_t key = (n0 + c < N && v[u][c] > 0.f) ? f2u(v[u][c]) : 0u;
+        const uint32_t key = n0 + c < N ? act_key(vb[u][c], sign_mask, 0u) : 0u;
         cnt[c] += (key > T[u] || (key == T[u] && (uint32_t)(n0 + c) <= cut[u])) ? live : 0u;
       }
     }
@@ -376,9 +405,9 @@ __device__ __forceinline__ void count_tokens_of_lane(const float* __restrict__ a
 // the workgroups of NPW = 256: the pass is bound by vector instructions per compute unit, and the
 // layers here have only 43 to 144 blocks of 256 neurons).  With `ghist` it also adds its neurons'
 // final counts to the histogram of count values (integer atomics, commutative).
-template <int NPW>
-__global__ __launch_bounds__(1024) void count_kernel(const float* __restrict__ act, int M, int N, int64_t ld,
-                                                     const uint32_t* __restrict__ thr, int vec_ok,
+template <int NPW, class IN>
+__global__ __launch_bounds__(1024) void count_kernel(const typename IN::T* __restrict__ act, int M, int N, int64_t ld,
+                                                     uint32_t sign_mask, const uint32_t* __restrict__ thr, int vec_ok,
                                                      int32_t* counts, int accumulate, uint32_t* ghist) {
   constexpr int TPW = 256 / NPW;   // tokens per wave instruction
   constexpr int LPR = 64 / TPW;    // lanes per token row
@@ -394,8 +423,8 @@ __global__ __launch_bounds__(1024) void count_kernel(const float* __restrict__ a
   uint32_t cnt[4] = {0, 0, 0, 0};
   // rows of the last, partial block take the element-wise path as a whole (uniform per workgroup
   // would be enough; per lane keeps the full blocks' lanes on the vector path)
-  if (vec_ok && n0 + 3 < N) count_tokens_of_lane<true, TPW>(act, ld, thr, M, N, min(n0, N - 4), ts, wave, nw, cnt);
-  else count_tokens_of_lane<false, TPW>(act, ld, thr, M, N, n0, ts, wave, nw, cnt);
+  if (vec_ok && n0 + 3 < N) count_tokens_of_lane<true, TPW, IN>(act, ld, thr, M, N, sign_mask, min(n0, N - 4), ts, wave, nw, cnt);
+  else count_tokens_of_lane<false, TPW, IN>(act, ld, thr, M, N, sign_mask, n0, ts, wave, nw, cnt);
   // block tallies: integer adds in LDS (commutative), then one plain store per neuron
 #pragma unroll
   for (int c = 0; c < 4; ++c)
@@ -744,17 +773,67 @@ __global__ __launch_bounds__(1024) void best_group_kernel(const int32_t* __restr
   if (threadIdx.x == 0) best[0] = sg[0];
 }
 
-template <int ITEMS, bool TWO = false>
-int launch_threshold(const float* act, int M, int N, int64_t ld, int64_t q_alpha, uint32_t* thr,
-                     uint32_t* ghist, int grid, int nt, hipStream_t s) {
+template <int ITEMS, bool TWO, class IN>
+int launch_threshold(const typename IN::T* act, int M, int N, int64_t ld, int64_t q_alpha, uint32_t sign_mask,
+                     uint32_t* thr, uint32_t* ghist, int grid, int nt, hipStream_t s) {
   static uint64_t attr_seen = 0;  // raise the dynamic-LDS ceiling once (64 KB by default)
   if (first_call_on_device(attr_seen)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS, TWO>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS, TWO, IN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024) != hipSuccess)
       return CI_ERR_HIP;
   }
-  hipLaunchKernelGGL((token_threshold_kernel<ITEMS, TWO>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act, M,
-                     N, ld, q_alpha, thr, ghist);
+  hipLaunchKernelGGL((token_threshold_kernel<ITEMS, TWO, IN>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act,
+                     M, N, ld, q_alpha, sign_mask, thr, ghist);
+  CI_HIP_CHECK_LAUNCH();
+  return CI_OK;
+}
+
+// Def. 1 and Eq. 3 for an activation matrix of element type IN::T.  The fp32 path has a kernel for
+// every keys-per-thread step; the 16-bit types share three of them (16, 40, streaming).
+template <class IN>
+int launch_tokens(const void* act_v, int M, int N, int64_t ld, int64_t q_alpha, uint32_t sign_mask, uint32_t* thr,
+                  uint32_t* ghist, int32_t* counts, int accumulate, int nt, int items, int nblocks, int cus,
+                  hipStream_t s) {
+  using TI = typename IN::T;
+  const TI* act = reinterpret_cast<const TI*>(act_v);
+  // more tokens than compute units and at most 16 keys per thread: two workgroups per compute
+  // unit (a token round is half instruction issue, half barriers and latency; the register cap
+  // this needs costs a single workgroup about 10 %, so it is not used for short prompts)
+  const bool two = M > cus && items <= 16 && params().select_wgs_per_cu >= 2;
+  int grid = cus * (two ? 2 : 1);
+  if (grid > M) grid = M;
+  if (grid < 1) grid = 1;
+  int rc = CI_OK;
+#define CI_THR(I, W) launch_threshold<I, W, IN>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, grid, nt, s)
+  if constexpr (sizeof(TI) == 4) {
+    if (two && items <= 8) rc = CI_THR(8, true);
+    else if (two) rc = CI_THR(16, true);
+    else if (items <= 4) rc = CI_THR(4, false);
+    else if (items <= 8) rc = CI_THR(8, false);
+    else if (items <= 16) rc = CI_THR(16, false);
+    else if (items <= 24) rc = CI_THR(24, false);
+    else if (items <= 32) rc = CI_THR(32, false);
+    else if (items <= 36) rc = CI_THR(36, false);
+    else if (items <= 40) rc = CI_THR(40, false);
+    else rc = CI_THR(0, false);
+  } else {
+    if (two) rc = CI_THR(16, true);
+    else if (items <= 16) rc = CI_THR(16, false);
+    else if (items <= 40) rc = CI_THR(40, false);
+    else rc = CI_THR(0, false);
+  }
+#undef CI_THR
+  if (rc != CI_OK) return rc;
+  // four activations per load: 16 bytes of fp32 or 8 bytes of a 16-bit type
+  const uintptr_t quad = 4 * sizeof(TI);
+  const int vec_ok = ((reinterpret_cast<uintptr_t>(act) & (quad - 1)) == 0 && ld % 4 == 0) ? 1 : 0;
+  // 64 neurons per workgroup when blocks of 256 would leave more than half of the chip idle
+  if (nblocks <= cus / 2)
+    hipLaunchKernelGGL((count_kernel<64, IN>), dim3((N + 63) / 64), dim3(nt), 0, s, act, M, N, ld, sign_mask, thr,
+                       vec_ok, counts, accumulate, ghist);
+  else
+    hipLaunchKernelGGL((count_kernel<256, IN>), dim3(nblocks), dim3(nt), 0, s, act, M, N, ld, sign_mask, thr,
+                       vec_ok, counts, accumulate, ghist);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
@@ -790,8 +869,8 @@ void select_ws_layout(int64_t M, int64_t N, SelectWs* w) {
 //   kSelZero       clear the counters (before members are scattered into them)
 //   kSelTokens     Def. 1 over the M rows of act, then Eq. 3 (kSelAccumulate: added to the counters)
 //   kSelFinal      Def. 2 on the counters (values <= max_count)
-int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_t q_alpha,
-                  int64_t K64, int64_t max_count, int32_t* core_idx, int32_t* counts, void* ws,
+int launch_select(const void* act, int act_dtype, int take_abs, int64_t M64, int64_t N64, int64_t ld,
+                  int64_t q_alpha, int64_t K64, int64_t max_count, int32_t* core_idx, int32_t* counts, void* ws,
                   int what, hipStream_t s) {
   const int M = (what & kSelTokens) ? (int)M64 : 0, N = (int)N64, K = (int)K64;
   DeviceInfo di;
@@ -816,38 +895,15 @@ int launch_select(const float* act, int64_t M64, int64_t N64, int64_t ld, int64_
     char* base = reinterpret_cast<char*>(ws);
     uint32_t* thr = reinterpret_cast<uint32_t*>(base + w.off_thr);
     uint32_t* ghist = parallel_final ? reinterpret_cast<uint32_t*>(base + w.off_hist) : nullptr;
-    // more tokens than compute units and at most 16 keys per thread: two workgroups per compute
-    // unit (a token round is half instruction issue, half barriers and latency; the register cap
-    // this needs costs a single workgroup about 10 %, so it is not used for short prompts)
-    const bool two = M > di.cus && items <= 16 && params().select_wgs_per_cu >= 2;
-    int grid = di.cus * (two ? 2 : 1);
-    if (grid > M) grid = M;
-    if (grid < 1) grid = 1;
-#define CI_THR(I) launch_threshold<I>(act, M, N, ld, q_alpha, thr, ghist, grid, nt, s)
-#define CI_THR2(I) launch_threshold<I, true>(act, M, N, ld, q_alpha, thr, ghist, grid, nt, s)
-    if (two && items <= 8) rc = CI_THR2(8);
-    else if (two) rc = CI_THR2(16);
-    else if (items <= 4) rc = CI_THR(4);
-    else if (items <= 8) rc = CI_THR(8);
-    else if (items <= 16) rc = CI_THR(16);
-    else if (items <= 24) rc = CI_THR(24);
-    else if (items <= 32) rc = CI_THR(32);
-    else if (items <= 36) rc = CI_THR(36);
-    else if (items <= 40) rc = CI_THR(40);
-    else rc = CI_THR(0);
-#undef CI_THR
-#undef CI_THR2
-    if (rc != CI_OK) return rc;
-    const int vec_ok = ((reinterpret_cast<uintptr_t>(act) & 15u) == 0 && ld % 4 == 0) ? 1 : 0;
-    // 64 neurons per workgroup when blocks of 256 would leave more than half of the chip idle
+    const uint32_t sign_mask = take_abs ? 0x7fffffffu : 0xffffffffu;
     const int acc = (what & kSelAccumulate) ? 1 : 0;
-    if (nblocks <= di.cus / 2)
-      hipLaunchKernelGGL(count_kernel<64>, dim3((N + 63) / 64), dim3(nt), 0, s, act, M, N, ld, thr, vec_ok, counts,
-                         acc, ghist);
+    if (act_dtype == CI_F16)
+      rc = launch_tokens<InF16>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, acc, nt, items, nblocks, di.cus, s);
+    else if (act_dtype == CI_BF16)
+      rc = launch_tokens<InBF16>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, acc, nt, items, nblocks, di.cus, s);
     else
-      hipLaunchKernelGGL(count_kernel<256>, dim3(nblocks), dim3(nt), 0, s, act, M, N, ld, thr, vec_ok, counts,
-                         acc, ghist);
-    CI_HIP_CHECK_LAUNCH();
+      rc = launch_tokens<InF32>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, acc, nt, items, nblocks, di.cus, s);
+    if (rc != CI_OK) return rc;
     if (parallel_final) {
       const int cvec = (reinterpret_cast<uintptr_t>(counts) & 15u) == 0 ? 1 : 0;
       hipLaunchKernelGGL(def2_parallel_kernel, dim3(nblocks), dim3(1024), 0, s, counts, ghist, N, K, core_idx, cvec);

@@ -195,6 +195,36 @@ def test_next_row_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert r(F, 4, None, 3, 4, F, F, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 4, F, 3, 4, None, F, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 4, F, 3, 4, F, F + 2, None) == lib.CI_ERR_BAD_LAYOUT
+    r = lib.raw.coreinfer_select_hidden
+    big = 1 << 22
+    assert r(None, 1, 0, 4, 64, 64, 0.2, 0.4, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, 0, 4, 64, 64, 0.2, 0.4, None, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 9, 0, 4, 64, 64, 0.2, 0.4, F, None, F, big, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, 1, 7, 4, 64, 64, 0.2, 0.4, F, None, F, big, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, 1, 0, 0, 64, 64, 0.2, 0.4, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, 0, 4, 64, 64, 0.0, 0.4, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, 0, 4, 64, 32, 0.2, 0.4, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F + 1, 1, 0, 4, 64, 64, 0.2, 0.4, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F + 2, 0, 0, 4, 64, 64, 0.2, 0.4, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT   # fp32 needs 4 bytes
+    assert r(F, 1, 0, 4, 64, 64, 0.2, 0.4, F, None, None, big, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 1, 0, 4, 64, 64, 0.2, 0.4, F, None, F, 16, None) == lib.CI_ERR_WORKSPACE
+    r = lib.raw.coreinfer_ffn_dense_hidden
+    ok = dict(X=F, M=8, up=F, gate=None, bup=None, down=F, bdown=None, layout=0, dt=1, act=0, d=64, N=128, Y=F, H=F,
+              ws=F, wsb=big)
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return r(a["X"], a["M"], a["up"], a["gate"], a["bup"], a["down"], a["bdown"], a["layout"], a["dt"], a["act"],
+                 a["d"], a["N"], a["Y"], a["H"], a["ws"], a["wsb"], None)
+    assert call(H=None) == lib.CI_ERR_INVALID_ARG
+    assert call(X=None) == lib.CI_ERR_INVALID_ARG
+    assert call(down=None) == lib.CI_ERR_INVALID_ARG          # Y wanted without a down matrix
+    assert call(act=1) == lib.CI_ERR_INVALID_ARG              # gated FFN without a gate matrix
+    assert call(dt=5) == lib.CI_ERR_BAD_DTYPE
+    assert call(layout=3) == lib.CI_ERR_BAD_LAYOUT
+    assert call(d=60) == lib.CI_ERR_BAD_LAYOUT
+    assert call(H=F + 8) == lib.CI_ERR_BAD_LAYOUT
+    assert call(ws=None) == lib.CI_ERR_WORKSPACE
+    assert call(M=0) == lib.CI_ERR_INVALID_ARG
     r = lib.raw.coreinfer_assign_centroid
     assert r(None, 4, 64, 64, F, 3, F, F, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 4, 64, 64, None, 3, F, F, F, 1 << 20, None) == lib.CI_ERR_INVALID_ARG

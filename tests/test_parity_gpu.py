@@ -85,6 +85,81 @@ def test_select_random_shapes_and_tie_patterns(lib):
         _select_case(lib, A, alpha, beta, f"random case {case}: {kind}/{levels}")
 
 
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("act", ["relu", "swiglu"])
+@pytest.mark.parametrize("M,N,ld_pad", [(1, 1, 0), (7, 100, 3), (40, 4097, 0), (300, 2048, 4), (9, 16384, 0),
+                                        (270, 11008, 0), (5, 36864, 8), (3, 50000, 1)])
+def test_select_hidden_matches_oracle(lib, dt, act, M, N, ld_pad):
+    """Selection on the hidden matrix in the layer's element type: the oracle ranks the very same
+    values (their fp64 images; magnitudes for the gated FFN).  16-bit values tie all the time."""
+    dtype = DTYPES[dt]
+    _say("select hidden case", dt, act, M, N, ld_pad)
+    g = torch.Generator().manual_seed(M * 7 + N)
+    h = torch.randn(M, N, generator=g) * 1.5
+    if act == "relu":
+        h = h.clamp_min(0)
+    buf = torch.zeros(M, N + ld_pad, dtype=dtype, device=DEV)
+    buf[:, :N] = h.to(dtype).to(DEV)
+    H = buf[:, :N]
+    S, counts = lib.select_hidden(H, act, 0.2, 0.4)
+    torch.cuda.synchronize()
+    ranked = f64(H) if act == "relu" else np.abs(f64(H))
+    S_ref, c_ref = orc.select(ranked, 0.2, 0.4)
+    assert counts.cpu().numpy().tolist() == c_ref.tolist()
+    assert S.cpu().numpy().tolist() == S_ref.tolist()
+
+
+def test_select_hidden_special_values_and_fp32_equivalence(lib):
+    h = torch.tensor([[float("inf"), -float("inf"), float("nan"), -0.0, 0.0, 1.0, -2.0, 6e-8, -6e-8, 65504.0]] * 3,
+                     dtype=torch.float16, device=DEV)
+    for act in ("relu", "swiglu"):
+        S, counts = lib.select_hidden(h, act, 0.5, 0.5)
+        torch.cuda.synchronize()
+        ranked = f64(h) if act == "relu" else np.abs(f64(h))
+        S_ref, c_ref = orc.select(ranked, 0.5, 0.5)
+        assert counts.cpu().numpy().tolist() == c_ref.tolist() and S.cpu().numpy().tolist() == S_ref.tolist()
+    # an fp32 hidden matrix of a ReLU layer: the same call as coreinfer_select
+    A = torch.from_numpy(wl.activation_like(33, 3000, seed=5, kind="relu", levels=6)).to(DEV)
+    S1, c1 = lib.select(A, 0.2, 0.4)
+    S2, c2 = lib.select_hidden(A, "relu", 0.2, 0.4)
+    torch.cuda.synchronize()
+    assert torch.equal(S1, S2) and torch.equal(c1, c2)
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("act,layout", [("relu", "out_major"), ("swiglu", "neuron_major")])
+@pytest.mark.parametrize("M,d,N", [(3, 256, 512), (130, 320, 520), (256, 512, 768), (512, 256, 1024)])
+def test_dense_hidden_then_select_hidden(lib, dt, act, layout, M, d, N):
+    """The prefill pass without an fp32 score matrix: H against the oracle's hidden state within the
+    rounding of the element type, Y against the oracle FFN, and the selection on H bit-exact
+    against the oracle ranking those very values."""
+    _say("dense hidden case", dt, act, layout, M, d, N)
+    dtype = DTYPES[dt]
+    w = rand_weights(d, N, dtype, act, layout, seed=M + d + N + 3, device=DEV)
+    X = torch.randn(M, d, generator=torch.Generator().manual_seed(M + 2)).to(dtype).to(DEV)
+    Y, H = lib.ffn_dense_hidden(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], layout, act)
+    S, counts = lib.select_hidden(H, act, 0.2, 0.4)
+    torch.cuda.synchronize()
+    if act == "relu":
+        H_ref = orc.score_relu(f64(X), f64(w["w_up"]), f64(w["b_up"]))
+    else:
+        H_ref = orc.hidden_swiglu(f64(X), f64(w["w_gate"]), f64(w["w_up"]))
+    # one rounding of an fp32 accumulator: half an ulp of the element type, plus fp32 summation noise
+    ulp = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8, "f32": 2.0 ** -20}[dt]
+    err = np.abs(f64(H) - H_ref)
+    assert np.all(err <= ulp * np.abs(H_ref) * 1.01 + 2e-5 * np.sqrt(np.mean(H_ref ** 2)) + 1e-7)
+    assert_close_rms(Y, _oracle_ffn(act, X, None, w, layout), dtype, "dense hidden Y")
+    ranked = f64(H) if act == "relu" else np.abs(f64(H))
+    S_ref, c_ref = orc.select(ranked, 0.2, 0.4)
+    assert counts.cpu().numpy().tolist() == c_ref.tolist() and S.cpu().numpy().tolist() == S_ref.tolist()
+    # the same H as the dense call that also writes fp32 scores keeps in its workspace -> same Y
+    Y2, _ = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], layout, act,
+                          want_y=True, want_a=True)
+    torch.cuda.synchronize()
+    if M > 4:
+        assert torch.equal(Y, Y2)
+
+
 def test_select_degenerate_rows(lib):
     rng = np.random.default_rng(5)
     N = 3000
