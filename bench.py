@@ -203,6 +203,29 @@ def main():
     scratch_idx = torch.empty(K, dtype=torch.int32, device=dev)   # keeps the real core sets intact
     select_ms = timed(lambda: [ci.select(A_buf[:M], cfg.alpha, beta, core_idx=scratch_idx, counts=counts, ws=sel_ws)
                                for l in range(L)]) / L
+    # the same prefill without an fp32 score matrix: the dense FFN hands out the hidden matrix in the
+    # element type and the selection ranks it (reported beside the default path, never part of `value`)
+    hidden_prefill = None
+    if cfg.dtype != "f32":
+        H_buf = torch.empty((B * M, N), dtype=dtype, device=dev)
+        hws = dense_ws   # large enough: it also holds the split partial products of Y
+        run_h = lambda: [ci.ffn_dense_hidden(X[l], weights[l]["w_up"], weights[l]["w_gate"], weights[l]["b_up"],
+                                             weights[l]["w_down"], weights[l]["b_down"], cfg.down_layout, cfg.act,
+                                             Y=Y_buf, H=H_buf, ws=hws) for l in range(L)]
+        run_h()
+        dense_h_ms = timed(run_h) / L
+        idx_h = torch.empty(K, dtype=torch.int32, device=dev)
+        cnt_h = torch.empty(N, dtype=torch.int32, device=dev)
+        sel_h = lambda: [ci.select_hidden(H_buf[:M], cfg.act, cfg.alpha, beta, core_idx=idx_h, counts=cnt_h, ws=sel_ws)
+                         for l in range(L)]
+        sel_h()
+        select_h_ms = timed(sel_h) / L
+        hidden_prefill = {"dense_ms_per_layer": dense_h_ms, "select_us_per_layer": select_h_ms * 1e3,
+                          "fp32_score_bytes_not_written_per_layer": B * M * N * 4,
+                          "note": "coreinfer_ffn_dense_hidden + coreinfer_select_hidden: the selection ranks the "
+                                  "16-bit hidden matrix the down projection reads; a different reading of which "
+                                  "activation Def. 1 ranks, so its core sets can differ from the default path's"}
+        del H_buf
     compact_ms = None
     if not gathered:
         compact_ms = timed(lambda: [ci.compact(weights[l]["w_up"], weights[l]["w_gate"], weights[l]["b_up"],
@@ -419,6 +442,7 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS,
                      "traffic": traffic, "bytes_per_launch": bytes_per_launch,
                      "us_per_launch": kernel_ms * 1e3},
+        "hidden_ranked_prefill": hidden_prefill,
         "beta_sweep": sweep,
         "union_batched_decode": union,
         "cpu_baseline": cpu,
