@@ -1,6 +1,10 @@
 // Sentence-wise core neuron selection (Sec. 3.1 of arXiv 2410.18311), three
 // short launches per sentence and layer, no floating-point or counter atomics:
 //
+// The activation matrix may be fp32, fp16 or bf16 (the kernels that read it are
+// templated on the element type; a 16-bit value is ranked through its exact
+// fp32 image, and a flag makes the magnitude the ranked value).
+//
 // token_threshold_kernel -- Def. 1 / Eq. 1.  One workgroup per prompt token
 //     (looping when M exceeds the grid).  The token's N activations become
 //     integer keys (the IEEE bits of a positive float are monotone in its
