@@ -970,7 +970,16 @@ def test_prefill_graph_replays_match_eager(lib):
     umask = torch.empty(N, dtype=torch.int32, device=DEV)
     ucount = torch.empty(1, dtype=torch.int32, device=DEV)
 
+    Hh = torch.empty(M, N, dtype=dt, device=DEV)
+    Yh = torch.empty(M, d, dtype=dt, device=DEV)
+    idx_h = torch.empty(K, dtype=torch.int32, device=DEV)
+    cnt_h = torch.empty(N, dtype=torch.int32, device=DEV)
+    sws_h = torch.empty(lib.select_workspace_size(M, N), dtype=torch.uint8, device=DEV)
+
     def run():
+        lib.ffn_dense_hidden(X, w["w_up"], None, w["b_up"], w["w_down"], w["b_down"], "neuron_major", "relu",
+                             Y=Yh, H=Hh, ws=dws)
+        lib.select_hidden(Hh, "relu", 0.2, 0.3, core_idx=idx_h, counts=cnt_h, ws=sws_h)
         lib.ffn_dense(X, w["w_up"], None, w["b_up"], w["w_down"], w["b_down"], "neuron_major", "relu",
                       want_y=True, want_a=True, Y=Y, A=A, ws=dws)
         lib.select(A, 0.2, 0.3, core_idx=idx, counts=cnt, ws=sws)
@@ -983,14 +992,20 @@ def test_prefill_graph_replays_match_eager(lib):
     torch.cuda.synchronize()
     S_ref, c_ref = orc.select(A.cpu().numpy(), 0.2, 0.3)
     assert idx.cpu().numpy().tolist() == S_ref.tolist() and cnt.cpu().numpy().tolist() == c_ref.tolist()
+    Sh_ref, ch_ref = orc.select(f64(Hh), 0.2, 0.3)
+    assert idx_h.cpu().numpy().tolist() == Sh_ref.tolist() and cnt_h.cpu().numpy().tolist() == ch_ref.tolist()
+    want_h = {"idx": idx_h.clone(), "cnt": cnt_h.clone(), "H": Hh.clone(), "Y": Yh.clone()}
     want = {"idx": idx.clone(), "cnt": cnt.clone(), "up": bufs["w_up_c"].clone(), "down": bufs["w_down_c"].clone(),
             "Y": Y.clone(), "uidx": uidx[:int(ucount.item())].clone(), "un": int(ucount.item())}
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         run()
     for i in range(3):
-        for t in (dws, sws, uws):
+        for t in (dws, sws, uws, sws_h):
             t.fill_(0xA5)                                # stale scratch must not matter
+        for t in (idx_h, cnt_h):
+            t.fill_(-7)
+        Hh.zero_(); Yh.zero_()
         for t in (idx, cnt, uidx, ucount):
             t.fill_(-7)
         bufs["w_up_c"].zero_(); bufs["w_down_c"].zero_(); Y.zero_()
@@ -1000,4 +1015,6 @@ def test_prefill_graph_replays_match_eager(lib):
         assert torch.equal(idx, want["idx"]) and torch.equal(cnt, want["cnt"]), f"replay {i}: selection"
         assert torch.equal(bufs["w_up_c"], want["up"]) and torch.equal(bufs["w_down_c"], want["down"]), f"replay {i}"
         assert torch.equal(Y, want["Y"]), f"replay {i}: dense output"
+        assert torch.equal(idx_h, want_h["idx"]) and torch.equal(cnt_h, want_h["cnt"]), f"replay {i}: selection on H"
+        assert torch.equal(Hh, want_h["H"]) and torch.equal(Yh, want_h["Y"]), f"replay {i}: hidden pass"
         assert int(ucount.item()) == want["un"] and torch.equal(uidx[:want["un"]], want["uidx"]), f"replay {i}: union"
