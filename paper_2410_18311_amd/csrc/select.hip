@@ -260,7 +260,10 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
     radix_pass<ITEMS>(key_sel, n_iter, 20, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
     radix_pass<ITEMS>(key_sel, n_iter, 9, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
     uint32_t T;  // the k-th largest key; `need` of the n_eq keys == T are in the top k
-    if (n_eq <= kCand) {  // uniform; the usual case: after 22 bits only a few keys are left
+    if (sizeof(TI) == 2) {
+      // the fp32 image of a 16-bit value has nothing below bit 13: after 22 bits the prefix is the key
+      T = prefix;
+    } else if (n_eq <= kCand) {  // uniform; the usual case: after 22 bits only a few keys are left
       // the candidates go to a short list and are ranked against each other
       if (tid == 0) cand_n = 0;
       __syncthreads();
