@@ -654,6 +654,41 @@ def test_full_size_layer_compacted(lib, name, beta):
         _say(f"  token {i}: max err / rms = {rel:.2e}")
 
 
+@pytest.mark.parametrize("name,beta", [("opt6.7b_relu_f16", 0.4), ("llama2_7b_swiglu_bf16", 0.4),
+                                       ("llama2_13b_swiglu_bf16", 0.2), ("opt66b_relu_f16_8sent", 0.4)])
+def test_full_size_layer_hidden_ranked(lib, name, beta):
+    """The prefill pass without fp32 scores at the workload's full layer shape (for the OPT-66B
+    shape all eight prompts as one matrix, selection on the first prompt's rows): selection
+    bit-exact against the oracle ranking the hidden values; H sampled against the oracle."""
+    cfg = wl.WORKLOADS[name]
+    _say("full-size hidden-ranked layer", name)
+    w = wl.layer_weights(cfg, 0, DEV)
+    X = torch.cat([wl.prefill_hidden(cfg, 0, DEV, sentence=s) for s in range(cfg.sentences)], dim=0).contiguous()
+    Y, H = lib.ffn_dense_hidden(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], cfg.down_layout,
+                                cfg.act)
+    Hs = H[:cfg.M]
+    S, counts = lib.select_hidden(Hs, cfg.act, cfg.alpha, beta)
+    torch.cuda.synchronize()
+    ranked = f64(Hs) if cfg.act == "relu" else np.abs(f64(Hs))
+    S_ref, c_ref = orc.select(ranked, cfg.alpha, beta)
+    assert counts.cpu().numpy().tolist() == c_ref.tolist()
+    assert S.cpu().numpy().tolist() == S_ref.tolist()
+    # sampled rows and columns of H against the oracle's hidden state
+    rng = np.random.default_rng(4)
+    rows = np.unique(rng.integers(0, X.shape[0], size=6))
+    cols = np.unique(rng.integers(0, cfg.N, size=512))
+    ct = torch.from_numpy(cols).to(DEV)
+    Xs = f64(X[torch.from_numpy(rows).to(DEV)])
+    Wu = f64(w["w_up"][ct])
+    if cfg.act == "relu":
+        H_ref = orc.score_relu(Xs, Wu, f64(w["b_up"][ct]))
+    else:
+        H_ref = orc.hidden_swiglu(Xs, f64(w["w_gate"][ct]), Wu)
+    got = f64(H[torch.from_numpy(rows).to(DEV)][:, ct])
+    ulp = 2.0 ** -11 if cfg.dtype == "f16" else 2.0 ** -8
+    assert np.all(np.abs(got - H_ref) <= ulp * np.abs(H_ref) * 1.01 + 2e-5 * np.sqrt(np.mean(H_ref ** 2)) + 1e-7)
+
+
 def test_full_size_layer_gathered_eight_sentences(lib):
     """OPT-66B-shaped layer, eight sentences with their own core sets, rows
     gathered from the resident weights (two sentences checked on the CPU)."""
