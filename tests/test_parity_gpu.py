@@ -160,6 +160,27 @@ def test_dense_hidden_then_select_hidden(lib, dt, act, layout, M, d, N):
         assert torch.equal(Y, Y2)
 
 
+def test_select_ties_at_infinity_and_rows_without_positives(lib):
+    """Several +inf in a row with fewer places than infinities (the threshold is +inf and the cut
+    falls among them), rows with no positive value at all, and a cut inside a lane's four neurons."""
+    N = 300
+    A = np.zeros((6, N), dtype=np.float32)
+    A[0, [3, 17, 18, 19, 250]] = np.inf          # 5 infinities + 5 ones, alpha keeps 2 of 10
+    A[0, [5, 6, 7, 8, 9]] = 1.0
+    A[1] = -1.0                                   # nothing positive
+    A[2] = np.nan
+    A[3, 40:48] = 2.0                             # eight equal values, three kept: the cut is 42
+    A[4, 41:44] = 7.0                             # all kept
+    A[5, [0, 299]] = np.inf
+    for alpha, beta in ((0.2, 0.1), (0.375, 0.05), (1.0, 0.02)):
+        _select_case(lib, A, alpha, beta, "ties at infinity")
+        H = torch.from_numpy(A).to(torch.float16).to(DEV)
+        S, counts = lib.select_hidden(H, "relu", alpha, beta)
+        torch.cuda.synchronize()
+        S_ref, c_ref = orc.select(f64(H), alpha, beta)
+        assert counts.cpu().numpy().tolist() == c_ref.tolist() and S.cpu().numpy().tolist() == S_ref.tolist()
+
+
 def test_select_degenerate_rows(lib):
     rng = np.random.default_rng(5)
     N = 3000
