@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "coreinfer.h"
 
 namespace ci {
@@ -131,16 +133,18 @@ Params& params();
 inline int elem_bytes(int dtype) { return dtype == CI_F32 ? 4 : 2; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// True the first time it is called with this flag word while the current device is current:
-// per-device one-time set-up (kernel attributes) keyed by device ordinal.  Setting an attribute
-// twice is harmless, so no lock.
-inline bool first_call_on_device(uint64_t& seen) {
+// Raises a kernel's dynamic-LDS limit once per device.  `seen` holds one bit per device ordinal;
+// a bit is set only after the call succeeded, so a failure is reported again by the next launch.
+// Ordinals past 63 are not remembered (the attribute is set on every launch there).
+inline int allow_dynamic_lds(std::atomic<uint64_t>& seen, const void* kernel, size_t bytes) {
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return true;
-  const uint64_t bit = 1ull << (dev & 63);
-  if (seen & bit) return false;
-  seen |= bit;
-  return true;
+  if (hipGetDevice(&dev) != hipSuccess) return CI_ERR_HIP;
+  const uint64_t bit = dev < 64 ? 1ull << dev : 0;
+  if (seen.load(std::memory_order_acquire) & bit) return CI_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+    return CI_ERR_HIP;
+  seen.fetch_or(bit, std::memory_order_release);
+  return CI_OK;
 }
 
 #define CI_HIP_CHECK_LAUNCH()                          \

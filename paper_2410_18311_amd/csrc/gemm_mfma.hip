@@ -750,12 +750,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 
 template <class D, int EPI, int RD, bool GUARD>
 int launch_ring(const GemmArgs& g, int tiles, int splits, size_t lds, hipStream_t s) {
-  static uint64_t attr_seen = 0;
-  if (lds > 48 * 1024 && first_call_on_device(attr_seen)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_ring_kernel<D, EPI, RD, GUARD>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return CI_ERR_HIP;
-  }
+  static std::atomic<uint64_t> attr_seen{0};
+  if (lds > 48 * 1024 && allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&gemm_mfma_ring_kernel<D, EPI, RD, GUARD>), lds) != CI_OK)
+    return CI_ERR_HIP;
   hipLaunchKernelGGL((gemm_mfma_ring_kernel<D, EPI, RD, GUARD>), dim3(tiles, splits), dim3(256), lds, s, g);
   return CI_OK;
 }
@@ -764,12 +761,9 @@ template <class D, int EPI, bool BNN>
 int launch_mfma(const GemmArgs& g, hipStream_t s) {
   constexpr int NB = (EPI == EPI_SWIGLU) ? 2 : 1;
   const size_t lds = (size_t)2 * BM * LDK * (1 + NB) * sizeof(typename D::T);
-  static uint64_t attr_seen = 0;
-  if (lds > 48 * 1024 && first_call_on_device(attr_seen)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<D, EPI, BNN>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return CI_ERR_HIP;
-  }
+  static std::atomic<uint64_t> attr_seen{0};
+  if (lds > 48 * 1024 && allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&gemm_mfma_kernel<D, EPI, BNN>), lds) != CI_OK)
+    return CI_ERR_HIP;
   const int tiles = ((g.M + BM - 1) / BM) * ((g.Nn + BN - 1) / BN);
   const int splits = g.partial ? (g.Kk + g.k_chunk - 1) / g.k_chunk : 1;
   const bool ring = !BNN && g.Kk % BK == 0 && g.k_chunk % BK == 0 && params().gemm_ring;
@@ -785,12 +779,9 @@ int launch_mfma(const GemmArgs& g, hipStream_t s) {
                    (params().gemm_big == 2 || (params().gemm_big == 1 && big_tiles * splits >= kBigMinWorkgroups));
   if (big) {
     const size_t lds_big = (size_t)2 * 2 * GM * LDK * sizeof(typename D::T);
-    static uint64_t big_attr_seen = 0;
-    if (first_call_on_device(big_attr_seen)) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_big_kernel<D, EPI, BNN && EPI == EPI_LINEAR>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_big) != hipSuccess)
-        return CI_ERR_HIP;
-    }
+    static std::atomic<uint64_t> big_attr_seen{0};
+    if (allow_dynamic_lds(big_attr_seen, reinterpret_cast<const void*>(&gemm_mfma_big_kernel<D, EPI, BNN && EPI == EPI_LINEAR>), lds_big) != CI_OK)
+      return CI_ERR_HIP;
     hipLaunchKernelGGL((gemm_mfma_big_kernel<D, EPI, BNN && EPI == EPI_LINEAR>), dim3(big_tiles, splits), dim3(512), lds_big, s, g);
   } else if (ring) {
     // deepest ring whose depth divides every split's k-tile count (no padding iterations); else the

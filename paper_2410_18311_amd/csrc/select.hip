@@ -783,12 +783,9 @@ __global__ __launch_bounds__(1024) void best_group_kernel(const int32_t* __restr
 template <int ITEMS, bool TWO, class IN>
 int launch_threshold(const typename IN::T* act, int M, int N, int64_t ld, int64_t q_alpha, uint32_t sign_mask,
                      uint32_t* thr, uint32_t* ghist, int grid, int nt, hipStream_t s) {
-  static uint64_t attr_seen = 0;  // raise the dynamic-LDS ceiling once (64 KB by default)
-  if (first_call_on_device(attr_seen)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS, TWO, IN>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024) != hipSuccess)
-      return CI_ERR_HIP;
-  }
+  static std::atomic<uint64_t> attr_seen{0};  // raise the dynamic-LDS ceiling once (64 KB by default)
+  if (allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS, TWO, IN>), 156 * 1024) != CI_OK)
+    return CI_ERR_HIP;
   hipLaunchKernelGGL((token_threshold_kernel<ITEMS, TWO, IN>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act,
                      M, N, ld, q_alpha, sign_mask, thr, ghist);
   CI_HIP_CHECK_LAUNCH();
@@ -847,12 +844,9 @@ int launch_tokens(const void* act_v, int M, int N, int64_t ld, int64_t q_alpha, 
 
 template <int ITEMS>
 int launch_def2_single(int N, int32_t* counts, int K, int32_t* core_idx, int max_count, int nt, hipStream_t s) {
-  static uint64_t attr_seen = 0;
-  if (first_call_on_device(attr_seen)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&def2_single_kernel<ITEMS>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 156 * 1024) != hipSuccess)
-      return CI_ERR_HIP;
-  }
+  static std::atomic<uint64_t> attr_seen{0};
+  if (allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&def2_single_kernel<ITEMS>), 156 * 1024) != CI_OK)
+    return CI_ERR_HIP;
   hipLaunchKernelGGL((def2_single_kernel<ITEMS>), dim3(1), dim3(nt), (size_t)kHistWords * 4, s, N, counts, K,
                      core_idx, max_count);
   CI_HIP_CHECK_LAUNCH();
