@@ -71,71 +71,151 @@ constexpr int kCountBins = 2048;  // counts below this go to a global histogram 
 constexpr int kHistCopies = 8;    // copies of that histogram, by workgroup: atomics on one address serialise
 
 struct SelShared {
-  uint32_t wave_tot[kMaxWaves];
+  alignas(16) uint32_t wave_tot[kMaxWaves];  // one value per wave; the entries past the workgroup's waves stay zero
   uint32_t bin;      // chosen digit
   uint32_t above;    // keys in higher digits
   uint32_t in_bin;   // keys in the chosen digit
 };
+// Called once at kernel start (the first read of wave_tot comes after a barrier).
+__device__ __forceinline__ void init_shared(SelShared* sh) {
+  const int tid = threadIdx.x, nw = blockDim.x >> 6;
+  if (tid >= nw && tid < kMaxWaves) sh->wave_tot[tid] = 0u;
+}
 
 __device__ __forceinline__ uint32_t wave_count(bool pred) { return (uint32_t)__popcll(__ballot(pred)); }
 
-// Block-wide sum of one wave-uniform value per wave (every thread gets it).
-__device__ __forceinline__ uint32_t block_sum_waves(uint32_t wave_value, SelShared* sh) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  __syncthreads();
-  if (lane == 0) sh->wave_tot[wave] = wave_value;
-  __syncthreads();
-  uint32_t t = 0;
-  for (int w = 0; w < nw; ++w) t += sh->wave_tot[w];
-  return t;
+// ceil(q * n / 10^6) for q <= 10^6 and n <= 2^20 without a 64-bit division:
+// x / 10^6 = (x * ceil(2^62 / 10^6)) >> 62 holds exactly for x < 7.5 * 10^12.
+static_assert(CI_MAX_NEURONS <= (1 << 20), "share_ppm: the product has to stay below 7.5e12");
+__device__ __forceinline__ uint32_t share_ppm(int64_t q, uint32_t n) {
+  const uint64_t x = (uint64_t)q * n + 999999u;
+  constexpr uint64_t kMagic = 4611686018428ull;
+  const uint64_t hi = __umul64hi(x, kMagic), lo = x * kMagic;
+  return (uint32_t)((hi << 2) | (lo >> 62));
 }
 
-// hist holds kCopies replicas of nbins digit counts.  Finds the digit that
-// contains the k-th largest key (1 <= k <= total) and how many keys lie in
-// higher digits.  Result in sh->bin / above / in_bin, visible to all threads on
-// return.
-__device__ __forceinline__ void find_digit(const uint32_t* hist, int nbins, uint32_t k, SelShared* sh) {
-  const int tid = threadIdx.x, nt = blockDim.x;
-  const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
-  const int per = (nbins + nt - 1) / nt;  // digits per thread, contiguous; higher thread = higher digits
-  const int b0 = tid * per;
+// Inclusive prefix sum inside each row of 16 lanes: four DPP shifts (a lane whose source falls
+// outside its row adds zero).  Needs all 64 lanes active.
+__device__ __forceinline__ uint32_t row_prefix_incl(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);  // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);  // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);  // row_shr:8
+  return v;
+}
+// Inclusive prefix sum over the lanes of a wave (lane 0 first): the rows' own prefixes, then the
+// totals of the rows before, read from lanes 15, 31 and 47.
+__device__ __forceinline__ uint32_t wave_prefix_incl(uint32_t v) {
+  v = row_prefix_incl(v);
+  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
+  const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
+  const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 47);
+  const int row = (threadIdx.x & 63) >> 4;
+  return v + (row >= 1 ? r0 : 0u) + (row >= 2 ? r1 : 0u) + (row >= 3 ? r2 : 0u);
+}
+
+// Thread t owns KEEP neighbouring digits counted from the top (digit nbins - 1 - (t * KEEP + j)),
+// so "keys in higher digits" is a prefix sum over threads, and the totals of a thread's digits
+// stay in registers for the search.  PAIR: KEEP = 2 and nbins = 2 * threads, one 8-byte read per
+// replica.  KEEP = 0: any number of digits per thread, totals recomputed in the search.
+template <bool FIRST, int KEEP, bool PAIR>
+__device__ __forceinline__ uint32_t find_digit_impl(const uint32_t* hist, int nbins, uint32_t k, int64_t q_alpha,
+                                                    SelShared* sh) {
+  int tid = threadIdx.x;
+  // opaque: the addresses derived from it are computed here, not ahead of the caller's token loop
+  // (where they would each occupy a register for the whole kernel)
+  asm volatile("" : "+v"(tid));
+  const int nt = blockDim.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int per = KEEP > 0 ? KEEP : (nbins + nt - 1) / nt;
+  const int o0 = tid * per;  // my first digit is nbins - 1 - o0
   auto bin_total = [&](int bidx) {
     uint32_t c = 0;
 #pragma unroll
     for (int r = 0; r < kCopies; ++r) c += hist[r * kCopyStride + bidx];
     return c;
   };
+  uint32_t tot[KEEP > 0 ? KEEP : 1];
   uint32_t mine = 0;
-  for (int j = 0; j < per; ++j)
-    if (b0 + j < nbins) mine += bin_total(b0 + j);
-  uint32_t suf = mine;  // inclusive suffix sum over the wave
+  if constexpr (PAIR) {
+    tot[0] = tot[1] = 0u;
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t o = __shfl_down(suf, off, kWave);
-    if (lane + off < 64) suf += o;
+    for (int r = 0; r < kCopies; ++r) {
+      const uint2 pr = *reinterpret_cast<const uint2*>(hist + r * kCopyStride + nbins - 2 - o0);
+      tot[0] += pr.y;
+      tot[1] += pr.x;
+    }
+    mine = tot[0] + tot[1];
+  } else if constexpr (KEEP > 0) {
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+      tot[j] = (o0 + j < nbins) ? bin_total(nbins - 1 - o0 - j) : 0u;
+      mine += tot[j];
+    }
+  } else {
+    for (int j = 0; j < per; ++j)
+      if (o0 + j < nbins) mine += bin_total(nbins - 1 - o0 - j);
   }
-  if (lane == 0) sh->wave_tot[wave] = suf;
+  const uint32_t incl_w = wave_prefix_incl(mine);
+  if (lane == 63) sh->wave_tot[wave] = incl_w;
   __syncthreads();
-  uint32_t higher = 0;
-  for (int w = wave + 1; w < nw; ++w) higher += sh->wave_tot[w];
-  const uint32_t incl = suf + higher;  // keys in my digits and above
-  const uint32_t excl = incl - mine;   // keys strictly above my digits
-  if (excl < k && k <= incl) {
+  // prefix over the (at most 16) wave totals in the first row of lanes
+  const uint32_t wt = sh->wave_tot[lane & (kMaxWaves - 1)];
+  const uint32_t wp = row_prefix_incl(wt);
+  const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)wp, kMaxWaves - 1);  // keys of all waves
+  const uint32_t upto = (uint32_t)__builtin_amdgcn_readlane((int)wp, wave);
+  const uint32_t own = (uint32_t)__builtin_amdgcn_readlane((int)wt, wave);
+  const uint32_t before = upto - own;  // keys owned by the waves before mine
+  if (FIRST) k = share_ppm(q_alpha, total);
+  const uint32_t incl = incl_w + before;  // keys in my digits and above
+  const uint32_t excl = incl - mine;      // keys strictly above my digits
+  if (k != 0 && excl < k && k <= incl) {
     uint32_t run = excl;
-    for (int j = per - 1; j >= 0; --j) {
-      const int bidx = b0 + j;
-      if (bidx >= nbins) continue;
-      const uint32_t c = bin_total(bidx);
-      if (run + c >= k) {
-        sh->bin = (uint32_t)bidx;
-        sh->above = run;
-        sh->in_bin = c;
-        break;
+    if constexpr (KEEP > 0) {
+      bool found = false;
+#pragma unroll
+      for (int j = 0; j < KEEP; ++j) {
+        const uint32_t c = tot[j];
+        if (!found && run + c >= k) {
+          sh->bin = (uint32_t)(nbins - 1 - o0 - j);
+          sh->above = run;
+          sh->in_bin = c;
+          found = true;
+        }
+        run += c;
       }
-      run += c;
+    } else {
+      for (int j = 0; j < per; ++j) {
+        if (o0 + j >= nbins) break;
+        const uint32_t c = bin_total(nbins - 1 - o0 - j);
+        if (run + c >= k) {
+          sh->bin = (uint32_t)(nbins - 1 - o0 - j);
+          sh->above = run;
+          sh->in_bin = c;
+          break;
+        }
+        run += c;
+      }
     }
   }
   __syncthreads();
+  return k;
+}
+
+// hist holds kCopies replicas of nbins digit counts.  Finds the digit that contains the k-th
+// largest key (1 <= k <= total) and how many keys lie in higher digits; result in sh->bin / above /
+// in_bin, visible to all threads on return.  FIRST: k is not given but derived here as the share
+// q_alpha of all keys in the histogram (the first digit's histogram holds every positive key).
+// Returns k; 0 means there is no key at all and nothing was written.
+template <bool FIRST>
+__device__ __forceinline__ uint32_t find_digit(const uint32_t* hist, int nbins, uint32_t k, int64_t q_alpha,
+                                               SelShared* sh) {
+  const int nt = blockDim.x;  // uniform branches: every thread takes the same one
+  if (nbins == 2 * nt) return find_digit_impl<FIRST, 2, true>(hist, nbins, k, q_alpha, sh);
+  if (nbins <= nt) return find_digit_impl<FIRST, 1, false>(hist, nbins, k, q_alpha, sh);
+  if (nbins <= 8 * nt) return find_digit_impl<FIRST, 8, false>(hist, nbins, k, q_alpha, sh);
+  return find_digit_impl<FIRST, 0, false>(hist, nbins, k, q_alpha, sh);
 }
 
 // Runs f(i) for i in [0, n_iter).  With ITEMS > 0 the loop is unrolled to a
@@ -151,34 +231,42 @@ __device__ __forceinline__ void for_items(int n_iter, F f) {
   }
 }
 
+// Clears the kCopies replicas of an nb-digit histogram, 16 bytes per store (nb is a multiple of 4
+// and the replica stride keeps 16-byte alignment; the padding words are never read).
+__device__ __forceinline__ void clear_hist(uint32_t* hist, int nb) {
+  const int q = nb >> 2;  // 16-byte pieces per replica
+  int first = threadIdx.x;
+  asm volatile("" : "+v"(first));  // opaque: the store addresses are not kept across the caller's loops
+  for (int j = first; j < kCopies * q; j += blockDim.x)
+    *reinterpret_cast<uint4*>(hist + (j / q) * kCopyStride + (j % q) * 4) = make_uint4(0, 0, 0, 0);
+}
+
 // One radix pass: histogram of the digit (key >> shift) & (nb - 1) over the
 // keys that match `prefix` under `prefix_mask`, then the digit holding the
 // k-th largest of them.  Updates prefix / prefix_mask / k; n_eq = keys in it.
-template <int ITEMS, class KeyAt>
+// FIRST: the caller has cleared the histogram (with a barrier since), and k comes out of the pass
+// as the share q_alpha of the keys counted (0: there are none, and nothing else is updated).
+// No barrier at the end: the next writes to *sh or the histogram all follow a barrier of their own.
+template <int ITEMS, bool FIRST = false, class KeyAt>
 __device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, int nb, uint32_t* hist,
                                            SelShared* sh, uint32_t& prefix, uint32_t& prefix_mask,
-                                           uint32_t& k, uint32_t& n_eq) {
-  const int tid = threadIdx.x, nt = blockDim.x;
-  uint32_t* my_hist = hist + (tid & (kCopies - 1)) * kCopyStride;
-  // clear the replicas, 16 bytes per store (nb is a multiple of 4 and the replica stride keeps
-  // 16-byte alignment; the padding words are never read)
-  {
-    const int q = nb >> 2;  // 16-byte pieces per replica
-    for (int j = tid; j < kCopies * q; j += nt)
-      *reinterpret_cast<uint4*>(hist + (j / q) * kCopyStride + (j % q) * 4) = make_uint4(0, 0, 0, 0);
+                                           uint32_t& k, uint32_t& n_eq, int64_t q_alpha = 0) {
+  uint32_t* my_hist = hist + (threadIdx.x & (kCopies - 1)) * kCopyStride;
+  if (!FIRST) {
+    clear_hist(hist, nb);
+    __syncthreads();
   }
-  __syncthreads();
   for_items<ITEMS>(n_iter, [&](int i) {
     const uint32_t key = key_at(i);
     if ((key & prefix_mask) == prefix) atomicAdd(&my_hist[(key >> shift) & (nb - 1)], 1u);
   });
   __syncthreads();
-  find_digit(hist, nb, k, sh);
+  k = find_digit<FIRST>(hist, nb, k, q_alpha, sh);
+  if (FIRST && k == 0) return;
   prefix |= sh->bin << shift;
   prefix_mask |= (uint32_t)(nb - 1) << shift;
   k -= sh->above;
   n_eq = sh->in_bin;
-  __syncthreads();  // sh is reused by the next pass
 }
 
 template <int ITEMS, bool TWO, class IN>  // TWO: registers capped so that two workgroups of 16 waves share a compute unit
@@ -197,13 +285,15 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int n_iter = (N + nt - 1) / nt;
+  init_shared(&sh);
   if (ghist)  // cleared here, a slice per workgroup, for the counting launch that follows
     for (int j = blockIdx.x * nt + tid; j < kCountBins * kHistCopies; j += gridDim.x * nt) ghist[j] = 0u;
 
   for (int m = blockIdx.x; m < M; m += gridDim.x) {
     const TI* row = act + (size_t)m * ld;
+    // the first digit's histogram is cleared while the row is on its way
+    clear_hist(hist, 2048);
     uint32_t kc[ITEMS > 0 ? ITEMS : 1];
-    uint32_t npos = 0;
     uint32_t lane_id = (uint32_t)tid;  // thread index within the workgroup
     asm volatile("" : "+v"(lane_id));
     if (ITEMS > 0) {
@@ -228,13 +318,6 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
           kc[i0 + j] = e < (uint32_t)N ? act_key(IN::bits(av[j]), sign_mask, kNoKey) : kNoKey;
         }
       }
-#pragma unroll
-      for (int i = 0; i < ITEMS; ++i) npos += wave_count(kc[i] != kNoKey);
-    } else {
-      for (int i = 0; i < n_iter; ++i) {
-        const int e = i * nt + tid;
-        npos += wave_count(e < N && act_key(IN::bits(row[e]), sign_mask, kNoKey) != kNoKey);
-      }
     }
     // key of this thread's i-th element.  Elements that are not positive, and those past the end,
     // get all-ones: bit 31 is part of the prefix mask from the start, so they match no prefix, and
@@ -247,17 +330,17 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
     };
     auto key_sel = key_at;
 
-    const uint32_t P = block_sum_waves(npos, &sh);
-    const uint32_t k = (uint32_t)((q_alpha * (int64_t)P + 999999) / 1000000);  // share of the positives
-    if (k == 0) {  // uniform: no positive activation, nothing is selected (no key exceeds all-ones)
+    __syncthreads();  // the histogram is clear
+
+    // 31-bit keys: digits of 11, 11 and 9 bits.  Bit 31 is part of the mask from the start,
+    // so the all-ones stand-in of a zero key never matches.  The first digit's histogram counts
+    // every positive key, and k -- the share alpha of them -- is taken from its total.
+    uint32_t prefix = 0, prefix_mask = 0x80000000u, need = 0, n_eq = 0;
+    radix_pass<ITEMS, true>(key_sel, n_iter, 20, 2048, hist, &sh, prefix, prefix_mask, need, n_eq, q_alpha);
+    if (need == 0) {  // uniform: no positive activation, nothing is selected (no key exceeds all-ones)
       if (tid == 0) { thr[2 * m] = 0xffffffffu; thr[2 * m + 1] = 0u; }
       continue;
     }
-
-    // 31-bit keys: digits of 11, 11 and 9 bits.  Bit 31 is part of the mask from the start,
-    // so the all-ones stand-in of a zero key never matches.
-    uint32_t prefix = 0, prefix_mask = 0x80000000u, need = k, n_eq = 0;
-    radix_pass<ITEMS>(key_sel, n_iter, 20, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
     radix_pass<ITEMS>(key_sel, n_iter, 9, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
     uint32_t T;  // the k-th largest key; `need` of the n_eq keys == T are in the top k
     if (sizeof(TI) == 2) {
@@ -470,6 +553,20 @@ __global__ __launch_bounds__(1024) void def2_parallel_kernel(const int32_t* __re
   __shared__ uint32_t wtot[4], wg[kMaxWaves], we[kMaxWaves];
   __shared__ uint32_t T_s, need_s;
   const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+  // The counts before this block (and its own) do not depend on T: when they fit eight 16-byte
+  // loads per thread they are requested first, so their latency overlaps the histogram's.
+  const int before = blockIdx.x * 256;
+  const int nv = before / 4;
+  const bool early = vec_ok && nv > 0 && nv <= nt * 8;
+  int4 v[8];
+  if (early) {
+    const int4* cv = reinterpret_cast<const int4*>(counts);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = cv[min(tid + u * nt, nv - 1)];
+  }
+  const int n = before + tid;
+  const bool valid = tid < 256 && n < N;
+  const uint32_t c = valid ? (uint32_t)counts[n] : 0u;
   // (1) T: the count value with #(count > T) < K <= #(count >= T); thread t < 256 owns bins 8t .. 8t+7
   uint32_t bins[8], mine = 0;
 #pragma unroll
@@ -510,13 +607,18 @@ __global__ __launch_bounds__(1024) void def2_parallel_kernel(const int32_t* __re
   const uint32_t T = T_s, need = need_s;
   // (2) neurons before this block that are above / at T: all threads, eight loads in flight each
   // (the loop is nothing but latency)
-  const int before = blockIdx.x * 256;
   uint32_t g = 0, e = 0;
-  if (vec_ok) {
+  if (early) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (tid + u * nt < nv) {
+        g += ((uint32_t)v[u].x > T) + ((uint32_t)v[u].y > T) + ((uint32_t)v[u].z > T) + ((uint32_t)v[u].w > T);
+        e += ((uint32_t)v[u].x == T) + ((uint32_t)v[u].y == T) + ((uint32_t)v[u].z == T) + ((uint32_t)v[u].w == T);
+      }
+    }
+  } else if (vec_ok) {
     const int4* cv = reinterpret_cast<const int4*>(counts);
-    const int nv = before / 4;
     for (int i0 = tid; i0 < nv; i0 += nt * 8) {
-      int4 v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) v[u] = cv[min(i0 + u * nt, nv - 1)];
 #pragma unroll
@@ -544,9 +646,6 @@ __global__ __launch_bounds__(1024) void def2_parallel_kernel(const int32_t* __re
   g = (uint32_t)wave_sum((int)g);
   e = (uint32_t)wave_sum((int)e);
   // (3) this block's neurons (threads 0..255), in index order = wave, then lane
-  const int n = before + tid;
-  const bool valid = tid < 256 && n < N;
-  const uint32_t c = valid ? (uint32_t)counts[n] : 0u;
   const bool isg = valid && c > T, ise = valid && c == T;
   const uint64_t bg = __ballot(isg), be = __ballot(ise);
   if (lane == 0) {
@@ -579,6 +678,7 @@ __global__ __launch_bounds__(1024) void def2_single_kernel(int N, int32_t* count
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int n_iter = (N + nt - 1) / nt;
+  init_shared(&sh);
 
   // plain loads: all of a thread's counts are in flight at once
   auto total_count = [&](int e) -> uint32_t { return (uint32_t)counts[e]; };
