@@ -45,6 +45,12 @@ constexpr int kCopies = 8;               // histogram replicas, chosen by lane &
 constexpr int kCopyStride = kBins + 8;   // words; the +8 spreads the replicas over LDS banks
 constexpr int kHistWords = kCopies * kCopyStride;
 constexpr int kMaxWaves = 16;
+constexpr int kThreads = 1024;           // threads of the per-token and the one-workgroup Def. 2 kernels
+// second digit's histogram of the per-token kernel, next to the first one so that both are cleared
+// up front: fp32 keys use one replica of 2048 digits (few keys are left, spread over all digits),
+// 16-bit keys eight replicas of 128 digits
+constexpr int kHist2Words = kBins + 8;
+constexpr int kCopyStride2 = 128 + 8;
 constexpr uint32_t kNoKey = 0xffffffffu;  // stands for an activation that is not positive
 
 // Element types the activation matrix may have; bits() gives the IEEE fp32 bits of a value (the
@@ -118,22 +124,21 @@ __device__ __forceinline__ uint32_t wave_prefix_incl(uint32_t v) {
 // so "keys in higher digits" is a prefix sum over threads, and the totals of a thread's digits
 // stay in registers for the search.  PAIR: KEEP = 2 and nbins = 2 * threads, one 8-byte read per
 // replica.  KEEP = 0: any number of digits per thread, totals recomputed in the search.
-template <bool FIRST, int KEEP, bool PAIR>
+template <bool FIRST, int KEEP, bool PAIR, int COPIES, int STRIDE>
 __device__ __forceinline__ uint32_t find_digit_impl(const uint32_t* hist, int nbins, uint32_t k, int64_t q_alpha,
                                                     SelShared* sh) {
   int tid = threadIdx.x;
   // opaque: the addresses derived from it are computed here, not ahead of the caller's token loop
   // (where they would each occupy a register for the whole kernel)
   asm volatile("" : "+v"(tid));
-  const int nt = blockDim.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int per = KEEP > 0 ? KEEP : (nbins + nt - 1) / nt;
+  const int per = KEEP > 0 ? KEEP : (nbins + kThreads - 1) / kThreads;
   const int o0 = tid * per;  // my first digit is nbins - 1 - o0
   auto bin_total = [&](int bidx) {
     uint32_t c = 0;
 #pragma unroll
-    for (int r = 0; r < kCopies; ++r) c += hist[r * kCopyStride + bidx];
+    for (int r = 0; r < COPIES; ++r) c += hist[r * STRIDE + bidx];
     return c;
   };
   uint32_t tot[KEEP > 0 ? KEEP : 1];
@@ -141,8 +146,8 @@ __device__ __forceinline__ uint32_t find_digit_impl(const uint32_t* hist, int nb
   if constexpr (PAIR) {
     tot[0] = tot[1] = 0u;
 #pragma unroll
-    for (int r = 0; r < kCopies; ++r) {
-      const uint2 pr = *reinterpret_cast<const uint2*>(hist + r * kCopyStride + nbins - 2 - o0);
+    for (int r = 0; r < COPIES; ++r) {
+      const uint2 pr = *reinterpret_cast<const uint2*>(hist + r * STRIDE + nbins - 2 - o0);
       tot[0] += pr.y;
       tot[1] += pr.x;
     }
@@ -203,19 +208,19 @@ __device__ __forceinline__ uint32_t find_digit_impl(const uint32_t* hist, int nb
   return k;
 }
 
-// hist holds kCopies replicas of nbins digit counts.  Finds the digit that contains the k-th
-// largest key (1 <= k <= total) and how many keys lie in higher digits; result in sh->bin / above /
-// in_bin, visible to all threads on return.  FIRST: k is not given but derived here as the share
-// q_alpha of all keys in the histogram (the first digit's histogram holds every positive key).
-// Returns k; 0 means there is no key at all and nothing was written.
-template <bool FIRST>
+// hist holds COPIES replicas (STRIDE words apart) of nbins digit counts.  Finds the digit that
+// contains the k-th largest key (1 <= k <= total) and how many keys lie in higher digits; result in
+// sh->bin / above / in_bin, visible to all threads on return.  FIRST: k is not given but derived
+// here as the share q_alpha of all keys in the histogram (the first digit's histogram holds every
+// positive key).  Returns k; 0 means there is no key at all and nothing was written.
+// For workgroups of kThreads threads; nbins is a constant at every call.
+template <bool FIRST, int COPIES, int STRIDE>
 __device__ __forceinline__ uint32_t find_digit(const uint32_t* hist, int nbins, uint32_t k, int64_t q_alpha,
                                                SelShared* sh) {
-  const int nt = blockDim.x;  // uniform branches: every thread takes the same one
-  if (nbins == 2 * nt) return find_digit_impl<FIRST, 2, true>(hist, nbins, k, q_alpha, sh);
-  if (nbins <= nt) return find_digit_impl<FIRST, 1, false>(hist, nbins, k, q_alpha, sh);
-  if (nbins <= 8 * nt) return find_digit_impl<FIRST, 8, false>(hist, nbins, k, q_alpha, sh);
-  return find_digit_impl<FIRST, 0, false>(hist, nbins, k, q_alpha, sh);
+  if (nbins == 2 * kThreads) return find_digit_impl<FIRST, 2, true, COPIES, STRIDE>(hist, nbins, k, q_alpha, sh);
+  if (nbins <= kThreads) return find_digit_impl<FIRST, 1, false, COPIES, STRIDE>(hist, nbins, k, q_alpha, sh);
+  if (nbins <= 8 * kThreads) return find_digit_impl<FIRST, 8, false, COPIES, STRIDE>(hist, nbins, k, q_alpha, sh);
+  return find_digit_impl<FIRST, 0, false, COPIES, STRIDE>(hist, nbins, k, q_alpha, sh);
 }
 
 // Runs f(i) for i in [0, n_iter).  With ITEMS > 0 the loop is unrolled to a
@@ -231,29 +236,31 @@ __device__ __forceinline__ void for_items(int n_iter, F f) {
   }
 }
 
-// Clears the kCopies replicas of an nb-digit histogram, 16 bytes per store (nb is a multiple of 4
-// and the replica stride keeps 16-byte alignment; the padding words are never read).
+// Clears COPIES replicas (STRIDE words apart) of an nb-digit histogram, 16 bytes per store (nb and
+// STRIDE are multiples of 4; the padding words are never read).
+template <int COPIES, int STRIDE>
 __device__ __forceinline__ void clear_hist(uint32_t* hist, int nb) {
   const int q = nb >> 2;  // 16-byte pieces per replica
   int first = threadIdx.x;
   asm volatile("" : "+v"(first));  // opaque: the store addresses are not kept across the caller's loops
-  for (int j = first; j < kCopies * q; j += blockDim.x)
-    *reinterpret_cast<uint4*>(hist + (j / q) * kCopyStride + (j % q) * 4) = make_uint4(0, 0, 0, 0);
+  for (int j = first; j < COPIES * q; j += kThreads)
+    *reinterpret_cast<uint4*>(hist + (j / q) * STRIDE + (j % q) * 4) = make_uint4(0, 0, 0, 0);
 }
 
 // One radix pass: histogram of the digit (key >> shift) & (nb - 1) over the
 // keys that match `prefix` under `prefix_mask`, then the digit holding the
 // k-th largest of them.  Updates prefix / prefix_mask / k; n_eq = keys in it.
-// FIRST: the caller has cleared the histogram (with a barrier since), and k comes out of the pass
-// as the share q_alpha of the keys counted (0: there are none, and nothing else is updated).
+// CLEARED: the caller has cleared the histogram, with a barrier since.  FIRST: k comes out of the
+// pass as the share q_alpha of the keys counted (0: there are none, and nothing else is updated).
 // No barrier at the end: the next writes to *sh or the histogram all follow a barrier of their own.
-template <int ITEMS, bool FIRST = false, class KeyAt>
+template <int ITEMS, bool FIRST = false, bool CLEARED = false, int COPIES = kCopies, int STRIDE = kCopyStride,
+          class KeyAt>
 __device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, int nb, uint32_t* hist,
                                            SelShared* sh, uint32_t& prefix, uint32_t& prefix_mask,
                                            uint32_t& k, uint32_t& n_eq, int64_t q_alpha = 0) {
-  uint32_t* my_hist = hist + (threadIdx.x & (kCopies - 1)) * kCopyStride;
-  if (!FIRST) {
-    clear_hist(hist, nb);
+  uint32_t* my_hist = hist + (threadIdx.x & (COPIES - 1)) * STRIDE;
+  if (!CLEARED) {
+    clear_hist<COPIES, STRIDE>(hist, nb);
     __syncthreads();
   }
   for_items<ITEMS>(n_iter, [&](int i) {
@@ -261,7 +268,7 @@ __device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, 
     if ((key & prefix_mask) == prefix) atomicAdd(&my_hist[(key >> shift) & (nb - 1)], 1u);
   });
   __syncthreads();
-  k = find_digit<FIRST>(hist, nb, k, q_alpha, sh);
+  k = find_digit<FIRST, COPIES, STRIDE>(hist, nb, k, q_alpha, sh);
   if (FIRST && k == 0) return;
   prefix |= sh->bin << shift;
   prefix_mask |= (uint32_t)(nb - 1) << shift;
@@ -270,20 +277,23 @@ __device__ __forceinline__ void radix_pass(KeyAt key_at, int n_iter, int shift, 
 }
 
 template <int ITEMS, bool TWO, class IN>  // TWO: registers capped so that two workgroups of 16 waves share a compute unit
-__global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(const typename IN::T* __restrict__ act,
+__global__ __launch_bounds__(kThreads, TWO ? 8 : 4) void token_threshold_kernel(const typename IN::T* __restrict__ act,
                                                                int M, int N, int64_t ld, int64_t q_alpha,
                                                                uint32_t sign_mask, uint32_t* __restrict__ thr,
                                                                uint32_t* ghist) {
   using TI = typename IN::T;
+  constexpr bool kNarrow = sizeof(TI) == 2;  // the fp32 image of a 16-bit value has nothing below bit 13
   __shared__ SelShared sh;
   __shared__ uint32_t cut_s;
   constexpr int kCand = 64;
   __shared__ uint32_t cand[kCand];
   __shared__ uint32_t cand_n;
-  extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];  // [kHistWords] histograms, cleared 16 bytes at a time
+  extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];  // [kHistWords + kHist2Words], cleared 16 bytes at a time
   uint32_t* hist = dyn;
-  const int tid = threadIdx.x, nt = blockDim.x;
-  const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+  uint32_t* hist2 = dyn + kHistWords;
+  constexpr int nt = kThreads, nw = kMaxWaves;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const int n_iter = (N + nt - 1) / nt;
   init_shared(&sh);
   if (ghist)  // cleared here, a slice per workgroup, for the counting launch that follows
@@ -291,8 +301,11 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
 
   for (int m = blockIdx.x; m < M; m += gridDim.x) {
     const TI* row = act + (size_t)m * ld;
-    // the first digit's histogram is cleared while the row is on its way
-    clear_hist(hist, 2048);
+    // the histograms of both digits are cleared while the row is on its way
+    clear_hist<kCopies, kCopyStride>(hist, 2048);
+    if (kNarrow) clear_hist<kCopies, kCopyStride2>(hist2, 128);
+    else clear_hist<1, kCopyStride>(hist2, 2048);
+    if (tid == 0) cand_n = 0;
     uint32_t kc[ITEMS > 0 ? ITEMS : 1];
     uint32_t lane_id = (uint32_t)tid;  // thread index within the workgroup
     asm volatile("" : "+v"(lane_id));
@@ -330,92 +343,92 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
     };
     auto key_sel = key_at;
 
-    __syncthreads();  // the histogram is clear
+    __syncthreads();  // the histograms are clear
 
-    // 31-bit keys: digits of 11, 11 and 9 bits.  Bit 31 is part of the mask from the start,
-    // so the all-ones stand-in of a zero key never matches.  The first digit's histogram counts
-    // every positive key, and k -- the share alpha of them -- is taken from its total.
+    // 31-bit keys: digits of 11, 11 and 9 bits (16-bit inputs: 11 and 7, which is all they have).
+    // Bit 31 is part of the mask from the start, so the all-ones stand-in of a zero key never
+    // matches.  The first digit's histogram counts every positive key, and k -- the share alpha of
+    // them -- is taken from its total.
     uint32_t prefix = 0, prefix_mask = 0x80000000u, need = 0, n_eq = 0;
-    radix_pass<ITEMS, true>(key_sel, n_iter, 20, 2048, hist, &sh, prefix, prefix_mask, need, n_eq, q_alpha);
+    radix_pass<ITEMS, true, true>(key_sel, n_iter, 20, 2048, hist, &sh, prefix, prefix_mask, need, n_eq, q_alpha);
     if (need == 0) {  // uniform: no positive activation, nothing is selected (no key exceeds all-ones)
       if (tid == 0) { thr[2 * m] = 0xffffffffu; thr[2 * m + 1] = 0u; }
       continue;
     }
-    radix_pass<ITEMS>(key_sel, n_iter, 9, 2048, hist, &sh, prefix, prefix_mask, need, n_eq);
     uint32_t T;  // the k-th largest key; `need` of the n_eq keys == T are in the top k
-    if (sizeof(TI) == 2) {
-      // the fp32 image of a 16-bit value has nothing below bit 13: after 22 bits the prefix is the key
-      T = prefix;
-    } else if (n_eq <= kCand) {  // uniform; the usual case: after 22 bits only a few keys are left
-      // the candidates go to a short list and are ranked against each other
-      if (tid == 0) cand_n = 0;
-      __syncthreads();
-      for_items<ITEMS>(n_iter, [&](int i) {
-        const uint32_t key = key_sel(i);
-        if ((key & prefix_mask) == prefix) cand[atomicAdd(&cand_n, 1u)] = key;
-      });
-      __syncthreads();
-      if (tid < (int)n_eq) {
-        const uint32_t c = cand[tid];
-        uint32_t g = 0, ge = 0;
-        for (uint32_t j = 0; j < n_eq; ++j) {
-          g += cand[j] > c;
-          ge += cand[j] >= c;
-        }
-        if (g < need && need <= ge) {  // equal candidates write the same three values
-          sh.bin = c;
-          sh.above = g;
-          sh.in_bin = ge - g;
-        }
-      }
-      __syncthreads();
-      T = sh.bin;
-      need -= sh.above;
-      n_eq = sh.in_bin;
-      __syncthreads();  // sh and the list are reused
+    if constexpr (kNarrow) {
+      radix_pass<ITEMS, false, true, kCopies, kCopyStride2>(key_sel, n_iter, 13, 128, hist2, &sh, prefix, prefix_mask,
+                                                            need, n_eq);
+      T = prefix;  // bits 13 .. 30 are all of the key
     } else {
-      radix_pass<ITEMS>(key_sel, n_iter, 0, 512, hist, &sh, prefix, prefix_mask, need, n_eq);
-      T = prefix;
+      radix_pass<ITEMS, false, true, 1, kCopyStride>(key_sel, n_iter, 9, 2048, hist2, &sh, prefix, prefix_mask, need,
+                                                     n_eq);
+      if (n_eq <= kCand) {  // uniform; the usual case: after 22 bits only a few keys are left
+        // the candidates go to a short list and are ranked against each other
+        for_items<ITEMS>(n_iter, [&](int i) {
+          const uint32_t key = key_sel(i);
+          if ((key & prefix_mask) == prefix) cand[atomicAdd(&cand_n, 1u)] = key;
+        });
+        __syncthreads();
+        if (tid < (int)n_eq) {
+          const uint32_t c = cand[tid];
+          uint32_t g = 0, ge = 0;
+          for (uint32_t j = 0; j < n_eq; ++j) {
+            g += cand[j] > c;
+            ge += cand[j] >= c;
+          }
+          if (g < need && need <= ge) {  // equal candidates write the same three values
+            sh.bin = c;
+            sh.above = g;
+            sh.in_bin = ge - g;
+          }
+        }
+        __syncthreads();
+        T = sh.bin;
+        need -= sh.above;
+        n_eq = sh.in_bin;
+        // no barrier: sh and the list are written again only after barriers of the next token
+      } else {
+        radix_pass<ITEMS>(key_sel, n_iter, 0, 512, hist, &sh, prefix, prefix_mask, need, n_eq);
+        T = prefix;
+      }
     }
 
     // index of the last tie that is taken; ties in index order = iteration, then wave, then lane
     if (tid == 0) cut_s = 0x7fffffffu;  // all ties taken (the usual case: need == n_eq)
     if (need != n_eq) {                 // uniform
       if constexpr (ITEMS > 0) {
-        // keys in registers: ties per (iteration, wave) go to LDS (the histograms are done with),
-        // then every thread finds the one iteration that holds the last tie taken and only that
-        // iteration is ranked lane by lane -- three barriers whatever the number of ties
-        uint32_t* cnt = hist;                        // [n_iter][nw]
-        uint32_t* itot = hist + ITEMS * kMaxWaves;   // [n_iter]
+        // keys in registers: ties per (iteration, wave) go to LDS (the histograms are done with);
+        // a row of 16 lanes then turns one iteration's 16 wave tallies into prefixes over the
+        // waves and the iteration's total; every thread finds the one iteration that holds the
+        // last tie taken and only that iteration is ranked lane by lane
+        static_assert(ITEMS % 4 == 0, "the prefix step runs in whole waves");
+        uint32_t* cnt = hist;                        // [ITEMS][16]
+        uint32_t* itot = hist + ITEMS * kMaxWaves;   // [ITEMS]
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-          if (i < n_iter) {
-            const uint32_t c = wave_count(kc[i] == T);  // T < 2^31, so elements without a key never match
-            if (lane == 0) cnt[i * nw + wave] = c;
-          }
+          const uint32_t c = wave_count(kc[i] == T);  // T < 2^31, so elements without a key never match
+          if (lane == 0) cnt[i * nw + wave] = c;
         }
         __syncthreads();
-        if (tid < n_iter) {
-          uint32_t t = 0;
-          for (int w = 0; w < nw; ++w) t += cnt[tid * nw + w];
-          itot[tid] = t;
+        if (tid < ITEMS * kMaxWaves) {
+          const uint32_t c = cnt[tid];
+          const uint32_t inc = row_prefix_incl(c);
+          cnt[tid] = inc - c;  // ties of this iteration in the waves before
+          if ((tid & (kMaxWaves - 1)) == kMaxWaves - 1) itot[tid >> 4] = inc;
         }
         __syncthreads();
         uint32_t base = 0;  // ties in earlier iterations
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-          if (i < n_iter) {
-            const uint32_t t = itot[i];
-            if (base < need && need <= base + t) {  // uniform: the (need - 1)-th tie lies in this iteration
-              const bool tie = kc[i] == T;
-              const uint64_t bal = __ballot(tie);
-              uint32_t before = base;
-              for (int w = 0; w < wave; ++w) before += cnt[i * nw + w];
-              const uint32_t rank = before + (uint32_t)__popcll(bal & lanemask_lt());
-              if (tie && rank == need - 1) cut_s = (uint32_t)(i * nt + tid);
-            }
-            base += t;
+          const uint32_t t = itot[i];
+          if (base < need && need <= base + t) {  // uniform: the (need - 1)-th tie lies in this iteration
+            const bool tie = kc[i] == T;
+            const uint64_t bal = __ballot(tie);
+            const uint32_t rank = base + cnt[i * nw + wave] + (uint32_t)__popcll(bal & lanemask_lt());
+            if (tie && rank == need - 1) cut_s = (uint32_t)(i * nt + tid);
           }
+          base += t;
         }
       } else {
         uint32_t base = 0;                // ties seen in earlier iterations
@@ -438,10 +451,11 @@ __global__ __launch_bounds__(1024, TWO ? 8 : 4) void token_threshold_kernel(cons
           }
         });
       }
+      __syncthreads();  // cut_s is final, and the tables in the histogram's place are done with
     }
-    __syncthreads();
     if (tid == 0) { thr[2 * m] = T; thr[2 * m + 1] = cut_s; }
-    __syncthreads();  // cut_s and the histograms are reused by the next token
+    // no barrier: the next token clears the histograms (last read before a barrier above) and
+    // thread 0 alone resets cut_s; everything else in LDS is written again only after barriers
   }
 }
 
@@ -675,8 +689,9 @@ __global__ __launch_bounds__(1024) void def2_single_kernel(int N, int32_t* count
   __shared__ SelShared sh;
   extern __shared__ __attribute__((aligned(16))) uint32_t dyn[];  // [kHistWords] histograms, cleared 16 bytes at a time
   uint32_t* hist = dyn;
-  const int tid = threadIdx.x, nt = blockDim.x;
-  const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+  constexpr int nt = kThreads, nw = kMaxWaves;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const int n_iter = (N + nt - 1) / nt;
   init_shared(&sh);
 
@@ -886,7 +901,8 @@ int launch_threshold(const typename IN::T* act, int M, int N, int64_t ld, int64_
   static std::atomic<uint64_t> attr_seen{0};  // raise the dynamic-LDS ceiling once (64 KB by default)
   if (allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS, TWO, IN>), 156 * 1024) != CI_OK)
     return CI_ERR_HIP;
-  hipLaunchKernelGGL((token_threshold_kernel<ITEMS, TWO, IN>), dim3(grid), dim3(nt), (size_t)kHistWords * 4, s, act,
+  hipLaunchKernelGGL((token_threshold_kernel<ITEMS, TWO, IN>), dim3(grid), dim3(kThreads),
+                     (size_t)(kHistWords + kHist2Words) * 4, s, act,
                      M, N, ld, q_alpha, sign_mask, thr, ghist);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
@@ -947,7 +963,7 @@ int launch_def2_single(int N, int32_t* counts, int K, int32_t* core_idx, int max
   static std::atomic<uint64_t> attr_seen{0};
   if (allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&def2_single_kernel<ITEMS>), 156 * 1024) != CI_OK)
     return CI_ERR_HIP;
-  hipLaunchKernelGGL((def2_single_kernel<ITEMS>), dim3(1), dim3(nt), (size_t)kHistWords * 4, s, N, counts, K,
+  hipLaunchKernelGGL((def2_single_kernel<ITEMS>), dim3(1), dim3(kThreads), (size_t)kHistWords * 4, s, N, counts, K,
                      core_idx, max_count);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
@@ -984,8 +1000,8 @@ int launch_select(const void* act, int act_dtype, int take_abs, int64_t M64, int
   }
   if (!(what & (kSelTokens | kSelFinal))) return CI_OK;
 
-  const int nt = N >= 4096 ? 1024 : 256;
-  const int items = (N + nt - 1) / nt;
+  const int nt = N >= 4096 ? 1024 : 256;               // threads of the counting launch
+  const int items = (N + kThreads - 1) / kThreads;     // keys per thread in the one-row kernels
   const int nblocks = (N + 255) / 256;
   // Def. 2 in parallel needs the histogram that the counting launch fills
   const bool parallel_final = (what & kSelTokens) && (what & kSelFinal) && !(what & kSelAccumulate) &&
