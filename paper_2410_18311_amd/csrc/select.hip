@@ -5,21 +5,26 @@
 // templated on the element type; a 16-bit value is ranked through its exact
 // fp32 image, and a flag makes the magnitude the ranked value).
 //
-// token_threshold_kernel -- Def. 1 / Eq. 1.  One workgroup per prompt token
-//     (looping when M exceeds the grid).  The token's N activations become
-//     integer keys (the IEEE bits of a positive float are monotone in its
-//     value; everything that is not > 0 becomes key 0), loaded once and kept in
-//     registers.  A most-significant-digit radix select (11 + 11 + 9 bits; the
-//     last digit by ranking the few keys left against each other when there are
-//     at most 64) over LDS histograms finds the value T of the k-th largest key,
-//     k being the share alpha of the positive keys.  The histograms are
-//     replicated eight times by lane so that activations sharing an exponent
-//     do not serialise on one LDS address.  Keys > T are token-wise core
-//     neurons; of the keys == T the lowest indices fill the remaining places:
-//     an ordered ballot / popcount prefix finds the index `cut` of the last tie
-//     that is taken (skipped when all of them are).  The token's result is the
-//     pair (T, cut): neuron n is in its core set iff key > T or (key == T and
-//     n <= cut).
+// token_threshold_kernel -- Def. 1 / Eq. 1.  One workgroup of 1024 threads per
+//     prompt token (looping when M exceeds the grid).  The token's N activations
+//     become integer keys (the IEEE bits of a positive float are monotone in its
+//     value; everything that is not > 0 gets a stand-in that matches nothing),
+//     loaded once and kept in registers.  A most-significant-digit radix select
+//     over LDS histograms (digits of 11 + 11 + 9 bits for fp32 inputs, the last
+//     one by ranking the few keys left against each other when there are at most
+//     64; 11 + 7 bits for 16-bit inputs, which have no more) finds the value T of
+//     the k-th largest key, k being the share alpha of the positive keys -- their
+//     number is the total of the first digit's histogram.  That histogram is
+//     replicated eight times by lane so that activations sharing an exponent do
+//     not serialise on one LDS address; both digits' histograms are cleared
+//     while the row is still on its way from memory.  The digit that holds the
+//     k-th key is found by prefix sums over threads (DPP shifts inside rows of 16
+//     lanes, scalar lane reads across rows and waves).  Keys > T are token-wise
+//     core neurons; of the keys == T the lowest indices fill the remaining
+//     places: an ordered ballot / popcount prefix finds the index `cut` of the
+//     last tie that is taken (skipped when all of them are).  The token's result
+//     is the pair (T, cut): neuron n is in its core set iff key > T or (key == T
+//     and n <= cut).  Ten barriers per token in the usual case.
 // count_kernel -- Eq. 3.  Counting is a second pass over the activations by
 //     neuron: a workgroup owns 256 neurons, walks all tokens, compares every
 //     activation with its token's (T, cut) and keeps the tallies in registers
@@ -564,55 +569,42 @@ __global__ __launch_bounds__(1024) void count_kernel(const typename IN::T* __res
 __global__ __launch_bounds__(1024) void def2_parallel_kernel(const int32_t* __restrict__ counts,
                                                              const uint32_t* __restrict__ ghist, int N, int K,
                                                              int32_t* __restrict__ core_idx, int vec_ok) {
-  __shared__ uint32_t wtot[4], wg[kMaxWaves], we[kMaxWaves];
+  __shared__ __attribute__((aligned(16))) uint32_t wtot[4], wg[kMaxWaves], we[kMaxWaves];
   __shared__ uint32_t T_s, need_s;
-  const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
-  // The counts before this block (and its own) do not depend on T: when they fit eight 16-byte
-  // loads per thread they are requested first, so their latency overlaps the histogram's.
-  const int before = blockIdx.x * 256;
-  const int nv = before / 4;
-  const bool early = vec_ok && nv > 0 && nv <= nt * 8;
-  int4 v[8];
-  if (early) {
-    const int4* cv = reinterpret_cast<const int4*>(counts);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = cv[min(tid + u * nt, nv - 1)];
-  }
-  const int n = before + tid;
-  const bool valid = tid < 256 && n < N;
-  const uint32_t c = valid ? (uint32_t)counts[n] : 0u;
-  // (1) T: the count value with #(count > T) < K <= #(count >= T); thread t < 256 owns bins 8t .. 8t+7
+  const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
+  // (1) T: the count value with #(count > T) < K <= #(count >= T).  Thread t < 256 owns the eight
+  // bins 2047 - 8t - j, highest first, so the keys above a bin are a prefix sum over threads.
   uint32_t bins[8], mine = 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) bins[j] = 0;
-  if (tid < 256) {
+  if (tid < kCountBins / 8) {
 #pragma unroll
     for (int r = 0; r < kHistCopies; ++r) {
-      const uint4* hp = reinterpret_cast<const uint4*>(ghist + r * kCountBins + tid * 8);
+      const uint4* hp = reinterpret_cast<const uint4*>(ghist + r * kCountBins + (kCountBins - 8 - tid * 8));
       const uint4 lo = hp[0], hi = hp[1];
-      bins[0] += lo.x; bins[1] += lo.y; bins[2] += lo.z; bins[3] += lo.w;
-      bins[4] += hi.x; bins[5] += hi.y; bins[6] += hi.z; bins[7] += hi.w;
+      bins[0] += hi.w; bins[1] += hi.z; bins[2] += hi.y; bins[3] += hi.x;
+      bins[4] += lo.w; bins[5] += lo.z; bins[6] += lo.y; bins[7] += lo.x;
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) mine += bins[j];
   }
-  uint32_t suf = mine;  // inclusive suffix sum over the wave
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t o = __shfl_down(suf, off, kWave);
-    if (lane + off < 64) suf += o;
-  }
-  if (lane == 0 && wave < 4) wtot[wave] = suf;
+  const uint32_t incl_w = wave_prefix_incl(mine);
+  if (lane == 63 && wave < 4) wtot[wave] = incl_w;
   __syncthreads();
-  if (tid < 256) {
-    uint32_t higher = 0;
-    for (int w = wave + 1; w < 4; ++w) higher += wtot[w];
-    const uint32_t incl = suf + higher, excl = incl - mine;
+  if (tid < kCountBins / 8) {
+    const uint4 w4 = *reinterpret_cast<const uint4*>(wtot);
+    const uint32_t before = (wave > 0 ? w4.x : 0u) + (wave > 1 ? w4.y : 0u) + (wave > 2 ? w4.z : 0u);
+    const uint32_t incl = incl_w + before, excl = incl - mine;
     if (excl < (uint32_t)K && (uint32_t)K <= incl) {
       uint32_t run = excl;
+      bool found = false;
 #pragma unroll
-      for (int j = 7; j >= 0; --j) {
-        if (run < (uint32_t)K && run + bins[j] >= (uint32_t)K) { T_s = (uint32_t)(tid * 8 + j); need_s = (uint32_t)K - run; }
+      for (int j = 0; j < 8; ++j) {
+        if (!found && run + bins[j] >= (uint32_t)K) {
+          T_s = (uint32_t)(kCountBins - 1 - tid * 8 - j);
+          need_s = (uint32_t)K - run;
+          found = true;
+        }
         run += bins[j];
       }
     }
@@ -621,18 +613,13 @@ __global__ __launch_bounds__(1024) void def2_parallel_kernel(const int32_t* __re
   const uint32_t T = T_s, need = need_s;
   // (2) neurons before this block that are above / at T: all threads, eight loads in flight each
   // (the loop is nothing but latency)
+  const int before = blockIdx.x * 256;
   uint32_t g = 0, e = 0;
-  if (early) {
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (tid + u * nt < nv) {
-        g += ((uint32_t)v[u].x > T) + ((uint32_t)v[u].y > T) + ((uint32_t)v[u].z > T) + ((uint32_t)v[u].w > T);
-        e += ((uint32_t)v[u].x == T) + ((uint32_t)v[u].y == T) + ((uint32_t)v[u].z == T) + ((uint32_t)v[u].w == T);
-      }
-    }
-  } else if (vec_ok) {
+  if (vec_ok) {
     const int4* cv = reinterpret_cast<const int4*>(counts);
+    const int nv = before / 4;
     for (int i0 = tid; i0 < nv; i0 += nt * 8) {
+      int4 v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) v[u] = cv[min(i0 + u * nt, nv - 1)];
 #pragma unroll
@@ -657,24 +644,35 @@ __global__ __launch_bounds__(1024) void def2_parallel_kernel(const int32_t* __re
       }
     }
   }
-  g = (uint32_t)wave_sum((int)g);
-  e = (uint32_t)wave_sum((int)e);
+  // wave totals: lane 63 of the prefix sums
+  g = wave_prefix_incl(g);
+  e = wave_prefix_incl(e);
   // (3) this block's neurons (threads 0..255), in index order = wave, then lane
+  const int n = before + tid;
+  const bool valid = tid < 256 && n < N;
+  const uint32_t c = valid ? (uint32_t)counts[n] : 0u;
   const bool isg = valid && c > T, ise = valid && c == T;
   const uint64_t bg = __ballot(isg), be = __ballot(ise);
-  if (lane == 0) {
+  if (lane == 63) {
     wg[wave] = g;
     we[wave] = e;
     if (wave < 4) wtot[wave] = ((uint32_t)__popcll(bg) << 16) | (uint32_t)__popcll(be);
   }
+  if (tid >= (nt >> 6) && tid < kMaxWaves) { wg[tid] = 0u; we[tid] = 0u; }  // waves that do not exist
   __syncthreads();
   if (tid < 256) {
     uint32_t g_before = 0, e_before = 0;
-    for (int w = 0; w < nw; ++w) {
-      g_before += wg[w];
-      e_before += we[w];
+#pragma unroll
+    for (int q = 0; q < kMaxWaves / 4; ++q) {
+      const uint4 a = *reinterpret_cast<const uint4*>(&wg[4 * q]), b = *reinterpret_cast<const uint4*>(&we[4 * q]);
+      g_before += a.x + a.y + a.z + a.w;
+      e_before += b.x + b.y + b.z + b.w;
     }
-    for (int w = 0; w < wave; ++w) { g_before += wtot[w] >> 16; e_before += wtot[w] & 0xffffu; }
+    const uint4 w4 = *reinterpret_cast<const uint4*>(wtot);
+    const uint32_t wt[3] = {w4.x, w4.y, w4.z};
+#pragma unroll
+    for (int w = 0; w < 3; ++w)
+      if (w < wave) { g_before += wt[w] >> 16; e_before += wt[w] & 0xffffu; }
     g_before += (uint32_t)__popcll(bg & lanemask_lt());
     e_before += (uint32_t)__popcll(be & lanemask_lt());
     const uint32_t pos = g_before + (e_before < need ? e_before : need);
