@@ -51,6 +51,8 @@ def _select_case(lib, A_np, alpha, beta, what):
     (3, 36000, "abs", 6, 0.3, 0.3),
     (3, 40960, "relu", 0, 0.2, 0.4),
     (3, 50000, "abs", 0, 0.05, 0.1),           # beyond the register-cached sizes
+    (2, 70001, "relu", 0, 0.2, 0.4),           # more than 65536 neurons: Def. 2 in one workgroup, streaming
+    (40, 66000, "abs", 4, 0.1, 0.3),
     (9, 13824, "abs", 0, 1.0, 1.0),
     (9, 1000, "relu", 2, 1.0, 0.001),
 ])
