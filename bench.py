@@ -195,14 +195,26 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
+    def timed_graph(fn, reps=3):
+        """GPU time of fn's launches replayed from a HIP graph: for stages of a few tens of
+        microseconds, where launching from Python would otherwise be what is measured."""
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        g.replay()
+        torch.cuda.synchronize()
+        return timed(g.replay, reps)
+
     w0 = weights[0]
     dense_ms = timed(lambda: [ci.ffn_dense(X[l], weights[l]["w_up"], weights[l]["w_gate"], weights[l]["b_up"],
                                            weights[l]["w_down"], weights[l]["b_down"], cfg.down_layout, cfg.act,
                                            want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
                               for l in range(L)]) / L   # per layer, all B sentences together
     scratch_idx = torch.empty(K, dtype=torch.int32, device=dev)   # keeps the real core sets intact
-    select_ms = timed(lambda: [ci.select(A_buf[:M], cfg.alpha, beta, core_idx=scratch_idx, counts=counts, ws=sel_ws)
-                               for l in range(L)]) / L
+    select_ms = timed_graph(lambda: [ci.select(A_buf[:M], cfg.alpha, beta, core_idx=scratch_idx, counts=counts,
+                                               ws=sel_ws) for l in range(L)]) / L
     # the same prefill without an fp32 score matrix: the dense FFN hands out the hidden matrix in the
     # element type and the selection ranks it (reported beside the default path, never part of `value`)
     hidden_prefill = None
@@ -218,8 +230,7 @@ def main():
         cnt_h = torch.empty(N, dtype=torch.int32, device=dev)
         sel_h = lambda: [ci.select_hidden(H_buf[:M], cfg.act, cfg.alpha, beta, core_idx=idx_h, counts=cnt_h, ws=sel_ws)
                          for l in range(L)]
-        sel_h()
-        select_h_ms = timed(sel_h) / L
+        select_h_ms = timed_graph(sel_h) / L
         hidden_prefill = {"dense_ms_per_layer": dense_h_ms, "select_us_per_layer": select_h_ms * 1e3,
                           "fp32_score_bytes_not_written_per_layer": B * M * N * 4,
                           "note": "coreinfer_ffn_dense_hidden + coreinfer_select_hidden: the selection ranks the "
