@@ -24,7 +24,8 @@
 //     places: an ordered ballot / popcount prefix finds the index `cut` of the
 //     last tie that is taken (skipped when all of them are).  The token's result
 //     is the pair (T, cut): neuron n is in its core set iff key > T or (key == T
-//     and n <= cut).  Ten barriers per token in the usual case.
+//     and n <= cut).  Nine barriers per token in the usual fp32 case (no tie
+//     cut, at most 64 keys left after two digits).
 // count_kernel -- Eq. 3.  Counting is a second pass over the activations by
 //     neuron: a workgroup owns 256 neurons, walks all tokens, compares every
 //     activation with its token's (T, cut) and keeps the tallies in registers
