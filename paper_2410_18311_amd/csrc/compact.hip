@@ -52,8 +52,7 @@ __device__ __forceinline__ void gather_row(const RowGather& g, const int32_t* __
 }
 
 __global__ __launch_bounds__(256) void gather_rows_kernel(RowGather g, const int32_t* __restrict__ idx,
-                                                          int K, int N, int vecs_per_row,
-                                                          int32_t* status) {
+                                                          int N, int vecs_per_row, int32_t* status) {
   gather_row(g, idx, blockIdx.x, blockIdx.y, N, vecs_per_row, status);
 }
 
@@ -322,7 +321,7 @@ int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const
     }
   }
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)K, g.n_mat), dim3(256), 0, s, g, core_idx,
-                     (int)K, (int)N, vecs, status);
+                     (int)N, vecs, status);
   CI_HIP_CHECK_LAUNCH();
   if (down_layout == CI_DOWN_OUT_MAJOR) {
     dim3 grid((unsigned)((K + 63) / 64), (unsigned)((d + 63) / 64));

@@ -896,7 +896,7 @@ __global__ __launch_bounds__(1024) void best_group_kernel(const int32_t* __restr
 
 template <int ITEMS, bool TWO, class IN>
 int launch_threshold(const typename IN::T* act, int M, int N, int64_t ld, int64_t q_alpha, uint32_t sign_mask,
-                     uint32_t* thr, uint32_t* ghist, int grid, int nt, hipStream_t s) {
+                     uint32_t* thr, uint32_t* ghist, int grid, hipStream_t s) {
   static std::atomic<uint64_t> attr_seen{0};  // raise the dynamic-LDS ceiling once (64 KB by default)
   if (allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS, TWO, IN>), 156 * 1024) != CI_OK)
     return CI_ERR_HIP;
@@ -923,7 +923,7 @@ int launch_tokens(const void* act_v, int M, int N, int64_t ld, int64_t q_alpha, 
   if (grid > M) grid = M;
   if (grid < 1) grid = 1;
   int rc = CI_OK;
-#define CI_THR(I, W) launch_threshold<I, W, IN>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, grid, nt, s)
+#define CI_THR(I, W) launch_threshold<I, W, IN>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, grid, s)
   if constexpr (sizeof(TI) == 4) {
     if (two && items <= 8) rc = CI_THR(8, true);
     else if (two) rc = CI_THR(16, true);
@@ -958,7 +958,7 @@ int launch_tokens(const void* act_v, int M, int N, int64_t ld, int64_t q_alpha, 
 }
 
 template <int ITEMS>
-int launch_def2_single(int N, int32_t* counts, int K, int32_t* core_idx, int max_count, int nt, hipStream_t s) {
+int launch_def2_single(int N, int32_t* counts, int K, int32_t* core_idx, int max_count, hipStream_t s) {
   static std::atomic<uint64_t> attr_seen{0};
   if (allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&def2_single_kernel<ITEMS>), 156 * 1024) != CI_OK)
     return CI_ERR_HIP;
@@ -1029,7 +1029,7 @@ int launch_select(const void* act, int act_dtype, int take_abs, int64_t M64, int
   }
   if (!(what & kSelFinal) || params().select_debug == 1) return CI_OK;
   const int mc = (int)max_count;
-#define CI_DEF2(I) launch_def2_single<I>(N, counts, K, core_idx, mc, nt, s)
+#define CI_DEF2(I) launch_def2_single<I>(N, counts, K, core_idx, mc, s)
   if (items <= 4) return CI_DEF2(4);
   if (items <= 8) return CI_DEF2(8);
   if (items <= 16) return CI_DEF2(16);
