@@ -87,7 +87,8 @@ int coreinfer_version(void);
  *   "select_debug" (timing only: 1 stops after the
  *   counts, core_idx is then NOT written; 2 runs Def. 2 in one workgroup even
  *   where the parallel kernel applies);
- *   "gemv_wgs_per_cu" (1..32), "gemm_ring" (0/1: register-ring GEMM kernels),
+ *   "gemv_wgs_per_cu" (1..32), "gemm_ring" (0/1: pipelined 128 x 128 GEMM kernels),
+ *   "gemm_direct" (0/1: those tiles loaded straight into LDS, else through a register ring),
  *   "gemm_big" (0 never, 1 when the grid is large enough, 2 whenever the shape
  *   divides: the 256 x 256-tile GEMM kernel);
  *   "union_depth" (8, 16), "union_down_threads" (64..512), "union_up_wgs_per_cu"

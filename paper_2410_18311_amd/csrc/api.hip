@@ -85,6 +85,7 @@ int coreinfer_set_param(const char* name, int value) {
   else if (!strcmp(name, "select_debug") && value >= 0 && value <= 3) p.select_debug = value;
   else if (!strcmp(name, "select_wgs_per_cu") && value >= 1 && value <= 8) p.select_wgs_per_cu = value;
   else if (!strcmp(name, "gemm_ring") && (value == 0 || value == 1)) p.gemm_ring = value;
+  else if (!strcmp(name, "gemm_direct") && (value == 0 || value == 1)) p.gemm_direct = value;
   else if (!strcmp(name, "gemm_big") && value >= 0 && value <= 2) p.gemm_big = value;
   else if (!strcmp(name, "gemv_wgs_per_cu") && value >= 1 && value <= 32) p.gemv_wgs_per_cu = value;
   else if (!strcmp(name, "decode_skip_reduce") && (value == 0 || value == 1)) p.decode_skip_reduce = value;

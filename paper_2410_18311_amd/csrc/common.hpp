@@ -119,6 +119,7 @@ struct Params {
   int select_debug = 0;
   int gemv_wgs_per_cu = 4;
   int gemm_ring = 1;         // register-ring GEMM kernel where it applies
+  int gemm_direct = 1;       // 128 x 128 tiles loaded straight into LDS instead of through the register ring
   int gemm_big = 1;          // 256 x 256 tiles: 0 never, 1 when there are enough of them, 2 whenever the shape divides
   int reduce_cq = 8;        // column quads per reduce workgroup (4, 8, 16)
   int decode_nt_store = 1;  // non-temporal stores for the partial sums

@@ -390,6 +390,158 @@ __global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
 }
 
 // ---------------------------------------------------------------------------
+// The same 128 x 128 tile with the operand tiles copied from global memory
+// straight into LDS (global_load_lds_dwordx4: every lane names its own 16 source
+// bytes, and the 64 pieces of a wave instruction land next to each other in
+// LDS), so that no register ring, no staging store and no wait for a load sits
+// in a wave's instruction stream: the k-tiles in flight live in LDS stages
+// (four of 32 KB; three of 48 KB for SwiGLU), and a wave only waits, once per
+// k-tile and just before the barrier, until the tile after the current one has
+// landed.  As the destination cannot be padded, a tile row is 128 bytes and its
+// eight 16-byte chunks are stored permuted -- chunk j of row r at position
+// j ^ (r & 7), chosen on the global side -- which makes the fragment reads of
+// eight neighbouring rows hit eight different positions (all 32 banks once).
+// The stages are separate LDS arrays, and the waits are written out by hand:
+// loads retire in order, so "at most 8 (S - 2) of my loads outstanding" means
+// that every k-tile up to the next one is complete.
+#define CI_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define CI_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+template <class D, int EPI, bool GUARD>  // GUARD: the k-tile count need not be a multiple of the stage count
+__global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g) {
+  using T = typename D::T;
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  constexpr int NB = DUAL ? 2 : 1;
+  constexpr int S = DUAL ? 3 : 4;                 // LDS stages
+  constexpr int TILE_B = BM * BK * 2;             // bytes of one operand tile: 128 rows of 128 bytes
+  constexpr int STAGE_B = TILE_B * (1 + NB);
+  constexpr int NP = 4 * (1 + NB);                // 16-byte pieces per thread and k-tile
+  __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE_B], st1[STAGE_B], st2[STAGE_B], st3[DUAL ? 16 : STAGE_B];
+  unsigned char* const st[4] = {st0, st1, st2, st3};
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tiles_m = (g.M + BM - 1) / BM;
+  const int t = xcd_swizzle(blockIdx.x, gridDim.x);
+  const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
+  const int k_begin = blockIdx.y * g.k_chunk;
+  const int k_end = min(g.Kk, k_begin + g.k_chunk);
+  const int nk = (k_end - k_begin) / BK;
+
+  // piece i of this thread: rows 32 i + 8 wave + lane / 8 of every operand tile; the lane's chunk
+  // position lane % 8 holds chunk (lane % 8) ^ (row % 8).  Rows past the edge are clamped: they
+  // only feed outputs that are never stored.
+  const T* pa[4];
+  const T* pb[NB][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = 32 * i + 8 * wave + (lane >> 3);
+    const int chunk = (lane & 7) ^ (row & 7);
+    pa[i] = reinterpret_cast<const T*>(g.A) + (size_t)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
+    pb[0][i] = reinterpret_cast<const T*>(g.B0) + (size_t)min(n0 + row, g.Nn - 1) * g.ldb + k_begin + chunk * 8;
+    if (DUAL) pb[NB - 1][i] = reinterpret_cast<const T*>(g.B1) + (size_t)min(n0 + row, g.Nn - 1) * g.ldb + k_begin + chunk * 8;
+  }
+  // piece p (0 .. NP-1) of k-tile `tile` into stage base `sb`: operand p / 4, row group p % 4
+#define CI_DIRECT_PIECE(sb, tile, p)                                                                  \
+  do {                                                                                                \
+    const int kk_ = min((tile), nk - 1) * BK;                                                         \
+    const T* src_ = ((p) < 4) ? pa[(p) & 3] + kk_ : pb[((p) >> 2) - 1][(p) & 3] + kk_;                \
+    __builtin_amdgcn_global_load_lds(CI_GLOBAL_PTR(src_),                                             \
+                                     CI_LDS_PTR((sb) + ((p) >> 2) * TILE_B + (32 * ((p) & 3) + 8 * wave) * 128), \
+                                     16, 0, 0);                                                       \
+  } while (0)
+
+  f32x16 acc[NB][2][2];
+#pragma unroll
+  for (int q = 0; q < NB; ++q)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[q][i][j][v] = 0.f;
+
+  // k-tiles 0 .. S-2 on their way
+#pragma unroll
+  for (int r = 0; r < S - 1; ++r) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) CI_DIRECT_PIECE(st[r], r, p);
+  }
+  // fragment addresses: row l31 (+ 32 i + 64 wm) of the tile, chunk 2 s + lane / 32
+  const int l31 = lane & 31, hi = lane >> 5;
+  uint4 fa[2][2], fb[2][NB][2];
+#define CI_DIRECT_FRAGS(buf, base, s)                                                                 \
+  do {                                                                                                \
+    _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) {                                                \
+      const int r_ = wm * 64 + i_ * 32 + l31;                                                         \
+      fa[buf][i_] = *reinterpret_cast<const uint4*>((base) + r_ * 128 + (((2 * (s) + hi) ^ (r_ & 7)) << 4)); \
+    }                                                                                                 \
+    _Pragma("unroll") for (int q_ = 0; q_ < NB; ++q_)                                                 \
+      _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) {                                              \
+        const int r_ = wn * 64 + j_ * 32 + l31;                                                       \
+        fb[buf][q_][j_] = *reinterpret_cast<const uint4*>((base) + TILE_B * (1 + q_) + r_ * 128 +     \
+                                                          (((2 * (s) + hi) ^ (r_ & 7)) << 4));        \
+      }                                                                                               \
+  } while (0)
+  // vmcnt(NP (S - 2)) and lgkmcnt(0): the next k-tile has landed, and my fragment reads are done.
+  // The barrier is the bare instruction: a fenced one would wait for every load in flight.
+  constexpr int kWaitNext = 0x0070 | ((NP * (S - 2)) & 15) | (((NP * (S - 2)) >> 4) << 14);
+  __builtin_amdgcn_s_waitcnt(kWaitNext);  // k-tile 0 has landed
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  CI_DIRECT_FRAGS(0, st[0], 0);
+
+  constexpr int kPieceLo[4] = {0, (NP + 2) / 3, (2 * NP + 2) / 3, NP};  // 3 + 3 + 2, or 4 + 4 + 4
+  for (int kt0 = 0; kt0 < nk; kt0 += S) {
+#pragma unroll
+    for (int r = 0; r < S; ++r) {
+      const int kt = kt0 + r;
+      const unsigned char* sA = st[r];                  // k-tile kt
+      const unsigned char* sN = st[(r + 1) % S];        // k-tile kt + 1
+      unsigned char* sF = st[(r + S - 1) % S];          // free since the barrier inside k-tile kt - 1: takes k-tile kt + S - 1
+#pragma unroll
+      for (int s = 0; s < BK / 16; ++s) {
+        if (s == BK / 16 - 1) {
+          // my pieces of k-tile kt + 1 have landed; after the barrier everybody's have, and every
+          // wave has read all fragments of k-tile kt
+          __builtin_amdgcn_sched_barrier(0);
+          __builtin_amdgcn_s_waitcnt(kWaitNext);
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          CI_DIRECT_FRAGS(0, sN, 0);
+        } else {
+          CI_DIRECT_FRAGS((s + 1) & 1, sA, s + 1);
+#pragma unroll
+          for (int p = 0; p < NP; ++p) {
+            if (p < kPieceLo[s] || p >= kPieceLo[s + 1]) continue;
+            CI_DIRECT_PIECE(sF, kt + S - 1, p);
+          }
+        }
+        if (!GUARD || kt < nk) {  // padding iterations (nk not a multiple of S) skip the arithmetic only
+#pragma unroll
+          for (int q = 0; q < NB; ++q)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+              for (int j = 0; j < 2; ++j) acc[q][i][j] = mfma32<D>(fa[s & 1][i], fb[s & 1][q][j], acc[q][i][j]);
+        }
+#pragma unroll
+        for (int m = 0; m < 4 * NB; ++m) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keeps the k-steps (and with them the load order) apart
+      }
+    }
+  }
+#undef CI_DIRECT_FRAGS
+#undef CI_DIRECT_PIECE
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // nothing of mine is still on its way into LDS when the workgroup ends
+  gemm_epilogue<D, EPI>(g, acc, m0, n0, wm, wn, lane);
+}
+
+// ---------------------------------------------------------------------------
 // Large-tile kernel for shapes that divide evenly: 256 x 256 outputs per
 // workgroup (SwiGLU: 256 rows x 128 gate + the same 128 up columns), eight waves
 // of 128 x 64 with 8 accumulator tiles each, two waves per SIMD.  What bounds a
@@ -783,6 +935,12 @@ int launch_mfma(const GemmArgs& g, hipStream_t s) {
     if (allow_dynamic_lds(big_attr_seen, reinterpret_cast<const void*>(&gemm_mfma_big_kernel<D, EPI, BNN && EPI == EPI_LINEAR>), lds_big) != CI_OK)
       return CI_ERR_HIP;
     hipLaunchKernelGGL((gemm_mfma_big_kernel<D, EPI, BNN && EPI == EPI_LINEAR>), dim3(big_tiles, splits), dim3(512), lds_big, s, g);
+  } else if (ring && params().gemm_direct) {
+    constexpr int kStages = (EPI == EPI_SWIGLU) ? 3 : 4;
+    const int chunk = g.partial ? g.k_chunk : g.Kk;
+    const bool even = g.Kk % chunk == 0 && (chunk / BK) % kStages == 0;  // every split's k-tile count divides
+    if (even) hipLaunchKernelGGL((gemm_mfma_direct_kernel<D, EPI, false>), dim3(tiles, splits), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((gemm_mfma_direct_kernel<D, EPI, true>), dim3(tiles, splits), dim3(256), 0, s, g);
   } else if (ring) {
     // deepest ring whose depth divides every split's k-tile count (no padding iterations); else the
     // guarded variant.  SwiGLU holds three operand tiles per k-tile, so its ring stays at two.

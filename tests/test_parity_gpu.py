@@ -447,9 +447,19 @@ def test_dense_matches_oracle(lib, dt, act, layout, M, d, N):
     assert torch.equal(A, A2)
 
 
-def test_dense_random_shapes(lib):
+@pytest.mark.parametrize("direct", [1, 0])
+def test_dense_random_shapes(lib, direct):
     """Seeded sweep over prompt lengths and widths around the tile edges of every GEMM variant
-    (ragged and even, reduction lengths that are and are not multiples of the k tile)."""
+    (ragged and even, reduction lengths that are and are not multiples of the k tile), with the
+    128 x 128 tiles loaded straight into LDS (the default) and through the register ring."""
+    lib.set_param("gemm_direct", direct)
+    try:
+        _dense_random_shapes(lib)
+    finally:
+        lib.set_param("gemm_direct", 1)
+
+
+def _dense_random_shapes(lib):
     rng = np.random.default_rng(11)
     for case in range(30):
         dt = ["f16", "bf16", "f32"][case % 3]
@@ -523,7 +533,7 @@ def test_dense_many_tiles_with_split_down_projection(lib, layout):
     assert_close_rms(Y[torch.from_numpy(rows).to(DEV)], Y_ref, torch.float16, "split down projection")
 
 
-@pytest.mark.parametrize("knob,value,default", [("gemm_ring", 0, 1), ("gemm_big", 0, 1), ("select_wgs_per_cu", 1, 2),
+@pytest.mark.parametrize("knob,value,default", [("gemm_ring", 0, 1), ("gemm_direct", 0, 1), ("gemm_big", 0, 1), ("select_wgs_per_cu", 1, 2),
                                                 ("select_debug", 2, 0), ("decode_depth", 8, 4), ("decode_depth", 16, 4),
                                                 ("decode_wgs_per_cu", 2, 1), ("decode_nt_store", 0, 1),
                                                 ("reduce_cq", 4, 8), ("reduce_cq", 16, 8), ("union_depth", 16, 8),
