@@ -399,8 +399,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_ring_kernel(GemmArgs g) {
 // k-tile and just before the barrier, until the tile after the current one has
 // landed.  As the destination cannot be padded, a tile row is 128 bytes and its
 // eight 16-byte chunks are stored permuted -- chunk j of row r at position
-// j ^ (r & 7), chosen on the global side -- which makes the fragment reads of
-// eight neighbouring rows hit eight different positions (all 32 banks once).
+// j ^ ((r / 2) & 7), chosen on the global side.  LDS has 64 banks of 4 bytes:
+// even and odd rows lie in different halves of them, and the 16 lanes that a
+// 16-byte fragment read serves per clock (16 neighbouring rows, one chunk
+// each) then hit eight different positions in either half: every bank once.
 // The stages are separate LDS arrays, and the waits are written out by hand:
 // loads retire in order, so "at most 8 (S - 2) of my loads outstanding" means
 // that every k-tile up to the next one is complete.
@@ -429,14 +431,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g) {
   const int nk = (k_end - k_begin) / BK;
 
   // piece i of this thread: rows 32 i + 8 wave + lane / 8 of every operand tile; the lane's chunk
-  // position lane % 8 holds chunk (lane % 8) ^ (row % 8).  Rows past the edge are clamped: they
+  // position lane % 8 holds chunk (lane % 8) ^ ((row / 2) % 8).  Rows past the edge are clamped: they
   // only feed outputs that are never stored.
   const T* pa[4];
   const T* pb[NB][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = 32 * i + 8 * wave + (lane >> 3);
-    const int chunk = (lane & 7) ^ (row & 7);
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
     pa[i] = reinterpret_cast<const T*>(g.A) + (size_t)min(m0 + row, g.M - 1) * g.lda + k_begin + chunk * 8;
     pb[0][i] = reinterpret_cast<const T*>(g.B0) + (size_t)min(n0 + row, g.Nn - 1) * g.ldb + k_begin + chunk * 8;
     if (DUAL) pb[NB - 1][i] = reinterpret_cast<const T*>(g.B1) + (size_t)min(n0 + row, g.Nn - 1) * g.ldb + k_begin + chunk * 8;
@@ -474,13 +476,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_direct_kernel(GemmArgs g) {
   do {                                                                                                \
     _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) {                                                \
       const int r_ = wm * 64 + i_ * 32 + l31;                                                         \
-      fa[buf][i_] = *reinterpret_cast<const uint4*>((base) + r_ * 128 + (((2 * (s) + hi) ^ (r_ & 7)) << 4)); \
+      fa[buf][i_] = *reinterpret_cast<const uint4*>((base) + r_ * 128 + (((2 * (s) + hi) ^ ((r_ >> 1) & 7)) << 4)); \
     }                                                                                                 \
     _Pragma("unroll") for (int q_ = 0; q_ < NB; ++q_)                                                 \
       _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_) {                                              \
         const int r_ = wn * 64 + j_ * 32 + l31;                                                       \
         fb[buf][q_][j_] = *reinterpret_cast<const uint4*>((base) + TILE_B * (1 + q_) + r_ * 128 +     \
-                                                          (((2 * (s) + hi) ^ (r_ & 7)) << 4));        \
+                                                          (((2 * (s) + hi) ^ ((r_ >> 1) & 7)) << 4));        \
       }                                                                                               \
   } while (0)
   // vmcnt(NP (S - 2)) and lgkmcnt(0): the next k-tile has landed, and my fragment reads are done.
