@@ -29,8 +29,11 @@
  *   - d = d_model, N = d_ff (neurons per layer), M = prompt tokens,
  *     K = |S|, B = sentences decoded together.
  *   - Element types: CI_F32, CI_F16 (IEEE half), CI_BF16.  Every sum is
- *     accumulated in fp32 and the hidden activations stay fp32 (Sec. 5,
- *     "Models": fp16 parameters, fp32 intermediate activations).
+ *     accumulated in fp32.  The decode entry points and the scores A handed
+ *     to the selection keep the hidden activations in fp32 (Sec. 5, "Models":
+ *     fp16 parameters, fp32 intermediate activations); the two places that
+ *     round them to the element type say so (the Y of coreinfer_ffn_dense for
+ *     M > 4, and the H of coreinfer_ffn_dense_hidden).
  *   - Pointers must be 16-byte aligned, and d must be a multiple of
  *     16 / sizeof(element) (8 for 16-bit types, 4 for fp32); otherwise
  *     CI_ERR_BAD_LAYOUT.
@@ -71,33 +74,6 @@ const char* coreinfer_strerror(int status);
 
 /* Library ABI version (increases when a signature changes). */
 int coreinfer_version(void);
-
-/*
- * Development knob for tuning sweeps, never needed for correct use: overrides
- * a launch-shape parameter process-wide.  Names:
- *   "decode_wgs_per_cu" (1..16), "decode_wgs" (0 = use the per-CU rule, else
- *   the number of neuron slices per sentence, up to 1024), "decode_threads"
- *   (0 = derive from d, else a multiple of 64 up to 1024), "decode_depth" (4, 8
- *   or 16 weight rows in flight per thread), "reduce_cq" (4, 8, 16 column quads
- *   per reduction workgroup), "decode_nt_store" (0/1), "decode_skip_reduce"
- *   (0/1; 1 launches only the first decode kernel so that it can be timed
- *   alone -- y is then NOT written);
- *   "select_wgs_per_cu" (1..8; 1 keeps the per-token kernel at one workgroup
- *   per compute unit also for prompts longer than the chip has compute units),
- *   "select_debug" (timing only: 1 stops after the
- *   counts, core_idx is then NOT written; 2 runs Def. 2 in one workgroup even
- *   where the parallel kernel applies);
- *   "gemv_wgs_per_cu" (1..32), "gemm_ring" (0/1: pipelined 128 x 128 GEMM kernels),
- *   "gemm_direct" (0/1: those tiles loaded straight into LDS, else through a register ring),
- *   "gemm_big" (0 never, 1 when the grid is large enough, 2 whenever the shape
- *   divides: the 256 x 256-tile GEMM kernel);
- *   "union_depth" (8, 16), "union_down_threads" (64..512), "union_up_wgs_per_cu"
- *   (1..8), "union_down_wgs_per_cu" (1..16): union-batched decode.
- * Unknown name or value out of range: CI_ERR_INVALID_ARG.  Not thread-safe
- * against running calls; a workspace size must be queried under the setting
- * the call will run with.
- */
-int coreinfer_set_param(const char* name, int value);
 
 /*
  * Size of "the top `frac` share of n items", the rule every selection below
@@ -229,22 +205,30 @@ int coreinfer_assign_centroid(const float* act, int64_t M, int64_t N, int64_t ld
 
 /*
  * Deploy the core neurons (Sec. 5.3): gather rows S of w_up (and w_gate),
- * entries S of b_up and columns S of w_down into contiguous, neuron-major
- * buffers:
+ * entries S of b_up and columns S of w_down into contiguous buffers:
  *   w_up_c   [K, d] = w_up[S, :]        w_gate_c [K, d] = w_gate[S, :]
- *   b_up_c   [K]    = b_up[S]           w_down_c [K, d] = (w_down[:, S])^T
+ *   b_up_c   [K]    = b_up[S]
+ *   w_down_c, by down_c_layout:
+ *     CI_DOWN_NEURON_MAJOR  [K, d]  = (w_down[:, S])^T
+ *     CI_DOWN_OUT_MAJOR     [d, ld] = w_down[:, S], ld = K rounded up to whole
+ *                           16-byte vectors (coreinfer_compact_down_ld); the
+ *                           columns K .. ld-1 are written as zeros.  This is
+ *                           the layout the single-launch decode reads.
  * w_gate / w_gate_c must be non-NULL exactly when act == CI_ACT_SWIGLU;
- * b_up / b_up_c are both NULL or both non-NULL.  core_idx [K] must be strictly
- * ascending with values in [0, N); an entry that violates this yields an
- * all-zero row and sets *status (device int32, may be NULL; the caller zeroes
- * it beforehand) to 1 -- it never causes an out-of-bounds access.
- * Output buffers are caller-allocated and must not overlap the inputs.
+ * b_up / b_up_c are both NULL or both non-NULL, and NULL for CI_ACT_SWIGLU
+ * (the gated FFNs of the paper's models have no biases; CI_ERR_INVALID_ARG).
+ * core_idx [K] must be strictly ascending with values in [0, N); an entry that
+ * violates this yields an all-zero row / column and sets *status (device
+ * int32, may be NULL; the caller zeroes it beforehand) to 1 -- it never causes
+ * an out-of-bounds access.  Output buffers are caller-allocated and must not
+ * overlap the inputs.
  */
+int coreinfer_compact_down_ld(int64_t K, int dtype, int64_t* ld);
 int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up,
                       const void* w_down, int down_layout, int dtype, int act,
                       int64_t d, int64_t N, const int32_t* core_idx, int64_t K,
                       void* w_up_c, void* w_gate_c, void* b_up_c, void* w_down_c,
-                      int32_t* status, void* stream);
+                      int down_c_layout, int32_t* status, void* stream);
 
 /*
  * Re-deploying after the core set changed (Fig. 1 names a stability estimation
@@ -258,35 +242,42 @@ int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up,
  *   the buffers).  slot_idx [K] int32, in/out: the neuron held by each row;
  *   after coreinfer_compact it equals that call's core_idx.  The decode entry
  *   point does not care about the order of the rows.  changed [1] int32
- *   (device, may be NULL): number of rows rewritten.  Weights, layouts and
- *   dtypes as for coreinfer_compact.  ws: coreinfer_compact_update_workspace_size.
+ *   (device, may be NULL): number of rows rewritten.  Weights, layouts
+ *   (down_c_layout names the layout of w_down_c: rows or columns are rewritten
+ *   accordingly) and dtypes as for coreinfer_compact.
+ *   ws: coreinfer_compact_update_workspace_size.
  */
 int coreinfer_compact_update_workspace_size(int64_t N, int64_t K, size_t* bytes);
 int coreinfer_compact_update(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                              int down_layout, int dtype, int act, int64_t d, int64_t N,
                              const int32_t* new_idx, int64_t K, int32_t* slot_idx, void* w_up_c,
-                             void* w_gate_c, void* b_up_c, void* w_down_c, int32_t* changed, void* ws,
-                             size_t ws_bytes, void* stream);
+                             void* w_gate_c, void* b_up_c, void* w_down_c, int down_c_layout,
+                             int32_t* changed, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Weights of one FFN layer as the decode kernel reads them.
  *   core_idx == NULL: compacted -- the buffers written by coreinfer_compact;
- *                     K rows each, shared by all B inputs.
+ *                     K rows each, shared by all B inputs.  down_layout says
+ *                     how w_down_c was written: CI_DOWN_NEURON_MAJOR [K, d], or
+ *                     CI_DOWN_OUT_MAJOR [d, ld_down].
  *   core_idx != NULL: gathered -- the resident dense weights, all neuron-major
- *                     (w_up, w_gate, w_down are [N, d], b_up is [N]);
+ *                     (w_up, w_gate, w_down are [N, d], b_up is [N];
+ *                     down_layout must be CI_DOWN_NEURON_MAJOR);
  *                     core_idx is [B, K], row b naming sentence b's core set.
  *                     Entries outside [0, N) contribute nothing.
  */
 typedef struct {
   const void* w_up;        /* [K, d] or [N, d]                          */
   const void* w_gate;      /* same shape; NULL unless CI_ACT_SWIGLU     */
-  const void* b_up;        /* [K] or [N]; may be NULL                   */
-  const void* w_down;      /* [K, d] or [N, d], neuron-major            */
+  const void* b_up;        /* [K] or [N]; may be NULL; NULL for SwiGLU  */
+  const void* w_down;      /* [K, d] / [N, d], or [d, ld_down]          */
   const void* b_down;      /* [d]; may be NULL                          */
   const int32_t* core_idx; /* NULL (compacted) or [B, K] (gathered)     */
   int64_t K;               /* core neurons per sentence                 */
   int64_t d;               /* d_model                                   */
   int64_t N;               /* rows of the resident weights (gathered)   */
+  int64_t ld_down;         /* row length of an output-major w_down (>= K, whole 16-byte vectors) */
+  int32_t down_layout;     /* ci_down_layout of w_down                  */
 } ci_ffn_weights;
 
 /*
@@ -294,12 +285,33 @@ typedef struct {
  *   ReLU:    y = w_down_c^T max(w_up_c x + b_up_c, 0) + b_down
  *   SwiGLU:  y = w_down_c^T (SiLU(w_gate_c x) * (w_up_c x)) + b_down
  * x [B, d] in, y [B, d] out, element type `dtype`; K = 0 gives y = b_down.
+ * b_up with CI_ACT_SWIGLU: CI_ERR_INVALID_ARG.
  * ws: at least coreinfer_ffn_decode_workspace_size(B, K, d) bytes.
+ *
+ * Two kernel paths, chosen by the layout of the compact down matrix:
+ *   CI_DOWN_NEURON_MAJOR (and every gathered call): neuron slices produce fp32
+ *     partial outputs in ws, a second launch sums them in a fixed order.  ws
+ *     needs no initialisation.
+ *   CI_DOWN_OUT_MAJOR: one launch, no partial outputs; the hidden values cross
+ *     workgroups through ws as self-validating words.  For this path ws must
+ *     have been ZEROED ONCE (hipMemsetAsync) before its first use and must not
+ *     be written by anything else afterwards; every call leaves it ready for
+ *     the next one, also when replayed from a HIP graph.  A workspace is bound
+ *     to the (B, K, d) it was sized for: zero it again before using it with
+ *     other sizes.  The launch needs one workgroup per compute unit resident at
+ *     the same time; if other work keeps compute units busy for long, a
+ *     workgroup gives up waiting after a bounded number of polls, the call's
+ *     output is then unspecified and the int32 at ws + 4 is set to 1 (it is 0
+ *     otherwise; coreinfer_ffn_decode_status copies it out).
+ * Calls that share a workspace must not overlap in time.
  */
 int coreinfer_ffn_decode_workspace_size(int64_t B, int64_t K, int64_t d, size_t* bytes);
 int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w,
                          int dtype, int act, void* y,
                          void* ws, size_t ws_bytes, void* stream);
+/* Enqueues a copy of the workspace's error word (see above) to *status_out, a
+ * device int32; valid after the stream has been synchronised. */
+int coreinfer_ffn_decode_status(const void* ws, int32_t* status_out, void* stream);
 
 /*
  * Union-batched decode.  Several sentences, each with its own frozen core set
@@ -320,7 +332,7 @@ int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w,
  * coreinfer_ffn_decode_union: x [B, d], y [B, d] of `dtype`; w->w_up,
  *   w->w_gate (SwiGLU), w->b_up, w->b_down as for the gathered decode: the full
  *   resident matrices, w_up / w_gate [N, d], w_down NEURON-MAJOR [N, d];
- *   w->core_idx and w->K are ignored.  union_idx / union_mask / union_count as
+ *   w->core_idx, w->K, w->ld_down and w->down_layout are ignored.  union_idx / union_mask / union_count as
  *   written by coreinfer_union_build with the same max_rows; the row count is
  *   read on the device, so no host synchronisation is needed between the two
  *   calls.  ws: coreinfer_ffn_decode_union_workspace_size bytes, 16-byte aligned.
@@ -344,7 +356,8 @@ int coreinfer_ffn_decode_union(const void* x, int64_t B, const ci_ffn_weights* w
  *   SwiGLU:  H = SiLU(X w_gate^T) * (X w_up^T),     A = |H|
  *   Y = H w_down^T + b_down
  * X [M, d]; Y [M, d] (element type `dtype`, may be NULL); A [M, N] fp32 (may
- * be NULL); at least one of Y, A must be given.  For Y, H is rounded to
+ * be NULL); at least one of Y, A must be given.  b_up may be NULL and must be
+ * NULL for CI_ACT_SWIGLU (CI_ERR_INVALID_ARG).  For Y, H is rounded to
  * `dtype` before the second product when M > 4 (matrix-core path).
  * ws: at least coreinfer_ffn_dense_workspace_size(M, d, N, dtype) bytes.
  */

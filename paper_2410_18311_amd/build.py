@@ -15,7 +15,7 @@ INCLUDE = os.path.join(ROOT, "include")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libcoreinfer.so")
 
-SOURCES = ["api.hip", "ffn_decode.hip", "ffn_union.hip", "select.hip", "compact.hip", "centroid.hip", "gemv.hip", "gemm_mfma.hip"]
+SOURCES = ["api.hip", "ffn_decode.hip", "ffn_decode_fused.hip", "ffn_union.hip", "select.hip", "compact.hip", "centroid.hip", "gemv.hip", "gemm_mfma.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -24,6 +24,8 @@ FLAGS = [
     "-Wno-unused-command-line-argument",
     "-I", INCLUDE, "-I", CSRC,
 ]
+# development builds: CI_EXTRA_FLAGS="-DCI_FUSED_STAMPS" adds time stamps to the single-launch decode
+FLAGS += os.environ.get("CI_EXTRA_FLAGS", "").split()
 
 
 def _compile(src: str) -> str:

@@ -44,13 +44,13 @@ _vp, _i64, _int, _dbl, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctyp
 
 class ci_ffn_weights(ctypes.Structure):
     _fields_ = [("w_up", _vp), ("w_gate", _vp), ("b_up", _vp), ("w_down", _vp), ("b_down", _vp),
-                ("core_idx", _vp), ("K", _i64), ("d", _i64), ("N", _i64)]
+                ("core_idx", _vp), ("K", _i64), ("d", _i64), ("N", _i64), ("ld_down", _i64),
+                ("down_layout", ctypes.c_int32)]
 
 
 _SIGNATURES = {
     "coreinfer_strerror": (ctypes.c_char_p, [_int]),
     "coreinfer_version": (_int, []),
-    "coreinfer_set_param": (_int, [ctypes.c_char_p, _int]),
     "coreinfer_keep_count": (_int, [_dbl, _i64, ctypes.POINTER(_i64)]),
     "coreinfer_select_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
@@ -62,14 +62,16 @@ _SIGNATURES = {
     "coreinfer_assign_group": (_int, [_vp, _i64, _vp, _i64, _i64, _vp, _vp, _vp]),
     "coreinfer_assign_centroid_workspace_size": (_int, [_i64, ctypes.POINTER(_sz)]),
     "coreinfer_assign_centroid": (_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "coreinfer_compact_down_ld": (_int, [_i64, _int, ctypes.POINTER(_i64)]),
     "coreinfer_compact": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64,
-                                 _vp, _vp, _vp, _vp, _vp, _vp]),
+                                 _vp, _vp, _vp, _vp, _int, _vp, _vp]),
     "coreinfer_compact_update_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_compact_update": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64, _vp,
-                                        _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+                                        _vp, _vp, _vp, _vp, _int, _vp, _vp, _sz, _vp]),
     "coreinfer_ffn_decode_workspace_size": (_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_ffn_decode": (_int, [_vp, _i64, ctypes.POINTER(ci_ffn_weights), _int, _int, _vp,
                                     _vp, _sz, _vp]),
+    "coreinfer_ffn_decode_status": (_int, [_vp, _vp, _vp]),
     "coreinfer_union_workspace_size": (_int, [_i64, ctypes.POINTER(_sz)]),
     "coreinfer_union_build": (_int, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_ffn_decode_union_workspace_size": (_int, [_i64, _i64, _i64, _int, _int, ctypes.POINTER(_sz)]),
@@ -88,6 +90,10 @@ for _name, (_res, _args) in _SIGNATURES.items():
 
 EXPORTS = tuple(_SIGNATURES)
 raw = _lib  # the bare C entry points, for tests of the error paths
+
+# development hook (csrc/coreinfer_dev.h): launch-shape parameters for sweeps, not part of the interface
+_lib.coreinfer_dev_set_param.restype = _int
+_lib.coreinfer_dev_set_param.argtypes = [ctypes.c_char_p, _int]
 
 
 class CoreInferError(RuntimeError):
@@ -121,8 +127,8 @@ def version() -> int:
     return _lib.coreinfer_version()
 
 
-def set_param(name: str, value: int) -> None:
-    _check(_lib.coreinfer_set_param(name.encode(), int(value)), "coreinfer_set_param")
+def dev_set_param(name: str, value: int) -> None:
+    _check(_lib.coreinfer_dev_set_param(name.encode(), int(value)), "coreinfer_dev_set_param")
 
 
 def keep_count(frac: float, n: int) -> int:
@@ -257,23 +263,44 @@ def assign_centroid(act: torch.Tensor, centroids: torch.Tensor, ws: Optional[tor
     return best, dist, ws[:N * 4].view(torch.float32)
 
 
+def compact_down_ld(K: int, dtype: torch.dtype) -> int:
+    ld = _i64(0)
+    _check(_lib.coreinfer_compact_down_ld(int(K), DTYPE_CODE[dtype], ctypes.byref(ld)), "coreinfer_compact_down_ld")
+    return ld.value
+
+
+def compact_buffers(K: int, d: int, dtype: torch.dtype, device, gate: bool, bias: bool,
+                    down_c_layout: str = "neuron_major") -> dict:
+    """Uninitialised compact buffers for coreinfer_compact; `down_c_layout` is recorded in the dict."""
+    ld = compact_down_ld(K, dtype)
+    down_shape = (K, d) if down_c_layout == "neuron_major" else (d, ld)
+    # with an output-major down matrix the bias buffer is padded to whole 16-byte vectors as well
+    nb = K if down_c_layout == "neuron_major" else ld
+    return {"w_up_c": torch.empty((K, d), dtype=dtype, device=device),
+            "w_gate_c": torch.empty((K, d), dtype=dtype, device=device) if gate else None,
+            "b_up_c": torch.zeros((nb,), dtype=dtype, device=device) if bias else None,
+            "w_down_c": torch.empty(down_shape, dtype=dtype, device=device),
+            "down_c_layout": down_c_layout}
+
+
 def compact(w_up, w_gate, b_up, w_down, down_layout: str, act: str, core_idx: torch.Tensor,
-            out: Optional[dict] = None, status: Optional[torch.Tensor] = None) -> dict:
-    """coreinfer_compact.  Returns the dict of compact buffers (allocated when
-    `out` is not given): w_up_c, w_gate_c, b_up_c, w_down_c, all neuron-major."""
+            out: Optional[dict] = None, status: Optional[torch.Tensor] = None,
+            down_c_layout: Optional[str] = None) -> dict:
+    """coreinfer_compact.  Returns the dict of compact buffers (allocated when `out` is not
+    given): w_up_c, w_gate_c, b_up_c [K, ...] and w_down_c, [K, d] ("neuron_major", the
+    default) or [d, ld] ("out_major"); the dict also records "down_c_layout"."""
     N, d = w_up.shape
     K = core_idx.numel()
     if out is None:
-        out = {
-            "w_up_c": torch.empty((K, d), dtype=w_up.dtype, device=w_up.device),
-            "w_gate_c": None if w_gate is None else torch.empty((K, d), dtype=w_up.dtype, device=w_up.device),
-            "b_up_c": None if b_up is None else torch.empty((K,), dtype=w_up.dtype, device=w_up.device),
-            "w_down_c": torch.empty((K, d), dtype=w_up.dtype, device=w_up.device),
-        }
+        out = compact_buffers(K, d, w_up.dtype, w_up.device, w_gate is not None, b_up is not None,
+                              down_c_layout or "neuron_major")
+    layout_c = out.get("down_c_layout", "neuron_major")
+    assert down_c_layout is None or down_c_layout == layout_c
     _check(_lib.coreinfer_compact(_ptr(w_up), _ptr(w_gate), _ptr(b_up), _ptr(w_down),
                                   LAYOUT_CODE[down_layout], DTYPE_CODE[w_up.dtype], ACT_CODE[act],
                                   d, N, _ptr(core_idx), K, _ptr(out["w_up_c"]), _ptr(out["w_gate_c"]),
-                                  _ptr(out["b_up_c"]), _ptr(out["w_down_c"]), _ptr(status), _stream(w_up)),
+                                  _ptr(out["b_up_c"]), _ptr(out["w_down_c"]), LAYOUT_CODE[layout_c],
+                                  _ptr(status), _stream(w_up)),
            "coreinfer_compact")
     return out
 
@@ -294,6 +321,7 @@ def compact_update(w_up, w_gate, b_up, w_down, down_layout: str, act: str, new_i
                                          LAYOUT_CODE[down_layout], DTYPE_CODE[w_up.dtype], ACT_CODE[act],
                                          d, N, _ptr(new_idx), K, _ptr(slot_idx), _ptr(bufs["w_up_c"]),
                                          _ptr(bufs["w_gate_c"]), _ptr(bufs["b_up_c"]), _ptr(bufs["w_down_c"]),
+                                         LAYOUT_CODE[bufs.get("down_c_layout", "neuron_major")],
                                          _ptr(changed), _ptr(ws), ws.numel(), _stream(w_up)),
            "coreinfer_compact_update")
     return changed
@@ -306,16 +334,37 @@ def ffn_decode_workspace_size(B: int, K: int, d: int) -> int:
     return b.value
 
 
-def make_weights(w_up, w_gate, b_up, w_down, b_down, core_idx=None, K: Optional[int] = None) -> ci_ffn_weights:
-    """Fills the ci_ffn_weights descriptor.  Compacted: pass the [K, d] buffers.
-    Gathered: pass the resident neuron-major [N, d] weights and core_idx [B, K]."""
+def make_weights(w_up, w_gate, b_up, w_down, b_down, core_idx=None, K: Optional[int] = None,
+                 down_layout: str = "neuron_major") -> ci_ffn_weights:
+    """Fills the ci_ffn_weights descriptor.  Compacted: pass the [K, d] buffers and, for an
+    output-major compact down matrix [d, ld], down_layout="out_major".  Gathered: pass the
+    resident neuron-major [N, d] weights and core_idx [B, K]."""
     rows, d = w_up.shape
     if core_idx is None:
         K = rows if K is None else K
     else:
         K = core_idx.shape[-1]
+    ld = w_down.shape[1] if (w_down is not None and down_layout == "out_major") else 0
     return ci_ffn_weights(_ptr(w_up), _ptr(w_gate), _ptr(b_up), _ptr(w_down), _ptr(b_down),
-                          _ptr(core_idx), K, d, rows)
+                          _ptr(core_idx), K, d, rows, ld, LAYOUT_CODE[down_layout])
+
+
+def make_compact_weights(bufs: dict, b_down) -> ci_ffn_weights:
+    """Descriptor over the buffers coreinfer_compact wrote (either layout of w_down_c)."""
+    return make_weights(bufs["w_up_c"], bufs["w_gate_c"], bufs["b_up_c"], bufs["w_down_c"], b_down,
+                        down_layout=bufs.get("down_c_layout", "neuron_major"))
+
+
+def decode_workspace(B: int, K: int, d: int, device) -> torch.Tensor:
+    """A zeroed workspace for coreinfer_ffn_decode (the single-launch path needs it zeroed once)."""
+    return torch.zeros(ffn_decode_workspace_size(B, K, d), dtype=torch.uint8, device=device)
+
+
+def ffn_decode_status(ws: torch.Tensor) -> int:
+    """coreinfer_ffn_decode_status, synchronised: 0, or 1 if a single-launch decode gave up waiting."""
+    out = torch.zeros(1, dtype=torch.int32, device=ws.device)
+    _check(_lib.coreinfer_ffn_decode_status(_ptr(ws), _ptr(out), _stream(ws)), "coreinfer_ffn_decode_status")
+    return int(out.item())
 
 
 def ffn_decode(x: torch.Tensor, weights: ci_ffn_weights, act: str, y: Optional[torch.Tensor] = None,
@@ -326,7 +375,7 @@ def ffn_decode(x: torch.Tensor, weights: ci_ffn_weights, act: str, y: Optional[t
     if y is None:
         y = torch.empty_like(x2)
     if ws is None:
-        ws = _workspace(ffn_decode_workspace_size(B, weights.K, d), x)
+        ws = decode_workspace(B, weights.K, d, x.device)
     _check(_lib.coreinfer_ffn_decode(_ptr(x2), B, ctypes.byref(weights), DTYPE_CODE[x.dtype],
                                      ACT_CODE[act], _ptr(y), _ptr(ws), ws.numel(), _stream(x)),
            "coreinfer_ffn_decode")

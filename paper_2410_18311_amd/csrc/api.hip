@@ -6,6 +6,7 @@
 #include <mutex>
 
 #include "common.hpp"
+#include "coreinfer_dev.h"
 
 namespace ci {
 
@@ -69,11 +70,11 @@ const char* coreinfer_strerror(int status) {
   return "unknown status";
 }
 
-int coreinfer_version(void) { return 1; }
+int coreinfer_version(void) { return 2; }
 
-// Development knob, not part of the documented interface: launch-shape
+// Development hook (coreinfer_dev.h), not part of the installed interface: launch-shape
 // parameters for tuning sweeps.  Returns CI_ERR_INVALID_ARG for unknown names.
-int coreinfer_set_param(const char* name, int value) {
+int coreinfer_dev_set_param(const char* name, int value) {
   if (!name) return CI_ERR_INVALID_ARG;
   Params& p = params();
   if (!strcmp(name, "decode_wgs_per_cu") && value >= 1 && value <= 16) p.decode_wgs_per_cu = value;
@@ -82,13 +83,19 @@ int coreinfer_set_param(const char* name, int value) {
   else if (!strcmp(name, "decode_depth") && (value == 4 || value == 8 || value == 16)) p.decode_depth = value;
   else if (!strcmp(name, "reduce_cq") && (value == 4 || value == 8 || value == 16)) p.reduce_cq = value;
   else if (!strcmp(name, "decode_nt_store") && (value == 0 || value == 1)) p.decode_nt_store = value;
-  else if (!strcmp(name, "select_debug") && value >= 0 && value <= 3) p.select_debug = value;
+  else if (!strcmp(name, "fused_depth") && (value == 4 || value == 8)) p.fused_depth = value;
+  else if (!strcmp(name, "fused_threads") && value >= 0 && value <= 1024) p.fused_threads = value;
+  else if (!strcmp(name, "fused_chunks") && value >= 2 && value <= 64) p.fused_chunks = value;
+  else if (!strcmp(name, "fused_wgs") && value >= 0 && value <= 1024) p.fused_wgs = value;
+  else if (!strcmp(name, "fused_guard_us10") && value >= 0 && value <= 1000) p.fused_guard_us10 = value;
+  else if (!strcmp(name, "fused_ablate") && value >= 0 && value <= 2) p.fused_ablate = value;
+  else if (!strcmp(name, "fused_aux") && (value == -1 || value == -2 || value == 0 || value == 16)) p.fused_aux = value;
+  else if (!strcmp(name, "select_def2_single") && (value == 0 || value == 1)) p.select_def2_single = value;
   else if (!strcmp(name, "select_wgs_per_cu") && value >= 1 && value <= 8) p.select_wgs_per_cu = value;
   else if (!strcmp(name, "gemm_ring") && (value == 0 || value == 1)) p.gemm_ring = value;
   else if (!strcmp(name, "gemm_direct") && (value == 0 || value == 1)) p.gemm_direct = value;
   else if (!strcmp(name, "gemm_big") && value >= 0 && value <= 2) p.gemm_big = value;
   else if (!strcmp(name, "gemv_wgs_per_cu") && value >= 1 && value <= 32) p.gemv_wgs_per_cu = value;
-  else if (!strcmp(name, "decode_skip_reduce") && (value == 0 || value == 1)) p.decode_skip_reduce = value;
   else if (!strcmp(name, "union_depth") && (value == 8 || value == 16)) p.union_depth = value;
   else if (!strcmp(name, "union_down_threads") && value >= 64 && value <= 512) p.union_down_threads = value;
   else if (!strcmp(name, "union_up_wgs_per_cu") && value >= 1 && value <= 8) p.union_up_wgs_per_cu = value;
@@ -256,23 +263,31 @@ int coreinfer_assign_centroid(const float* act, int64_t M, int64_t N, int64_t ld
                                 (hipStream_t)stream);
 }
 
+int coreinfer_compact_down_ld(int64_t K, int dtype, int64_t* ld) {
+  if (!dtype_ok(dtype)) return CI_ERR_BAD_DTYPE;
+  if (!ld || K < 0 || K > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
+  *ld = compact_down_ld(K, dtype);
+  return CI_OK;
+}
+
 int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                       int down_layout, int dtype, int act, int64_t d, int64_t N,
                       const int32_t* core_idx, int64_t K, void* w_up_c, void* w_gate_c,
-                      void* b_up_c, void* w_down_c, int32_t* status, void* stream) {
+                      void* b_up_c, void* w_down_c, int down_c_layout, int32_t* status, void* stream) {
   if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
-  if (!layout_ok(down_layout)) return CI_ERR_BAD_LAYOUT;
+  if (!layout_ok(down_layout) || !layout_ok(down_c_layout)) return CI_ERR_BAD_LAYOUT;
   if (d < 1 || d > CI_MAX_DMODEL || N < 1 || N > CI_MAX_NEURONS || K < 0 || K > N) return CI_ERR_INVALID_ARG;
   if (!w_up || !w_down || !w_up_c || !w_down_c || (K > 0 && !core_idx)) return CI_ERR_INVALID_ARG;
   if ((act == CI_ACT_SWIGLU) != (w_gate != nullptr) || (w_gate != nullptr) != (w_gate_c != nullptr))
     return CI_ERR_INVALID_ARG;
   if ((b_up != nullptr) != (b_up_c != nullptr)) return CI_ERR_INVALID_ARG;
+  if (act == CI_ACT_SWIGLU && b_up) return CI_ERR_INVALID_ARG;  // gated FFNs carry no up bias here
   if (d % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
   if (!aligned16(w_up) || !aligned16(w_gate) || !aligned16(w_down) || !aligned16(w_up_c) ||
       !aligned16(w_gate_c) || !aligned16(w_down_c))
     return CI_ERR_BAD_LAYOUT;
   return launch_compact(w_up, w_gate, b_up, w_down, down_layout, dtype, d, N, core_idx, K, w_up_c,
-                        w_gate_c, b_up_c, w_down_c, status, (hipStream_t)stream);
+                        w_gate_c, b_up_c, w_down_c, down_c_layout, status, (hipStream_t)stream);
 }
 
 int coreinfer_compact_update_workspace_size(int64_t N, int64_t K, size_t* bytes) {
@@ -284,10 +299,10 @@ int coreinfer_compact_update_workspace_size(int64_t N, int64_t K, size_t* bytes)
 int coreinfer_compact_update(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                              int down_layout, int dtype, int act, int64_t d, int64_t N,
                              const int32_t* new_idx, int64_t K, int32_t* slot_idx, void* w_up_c,
-                             void* w_gate_c, void* b_up_c, void* w_down_c, int32_t* changed, void* ws,
-                             size_t ws_bytes, void* stream) {
+                             void* w_gate_c, void* b_up_c, void* w_down_c, int down_c_layout,
+                             int32_t* changed, void* ws, size_t ws_bytes, void* stream) {
   if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
-  if (!layout_ok(down_layout)) return CI_ERR_BAD_LAYOUT;
+  if (!layout_ok(down_layout) || !layout_ok(down_c_layout)) return CI_ERR_BAD_LAYOUT;
   if (d < 1 || d > CI_MAX_DMODEL) return CI_ERR_INVALID_ARG;
   size_t need = 0;
   if (coreinfer_compact_update_workspace_size(N, K, &need) != CI_OK) return CI_ERR_INVALID_ARG;
@@ -295,6 +310,7 @@ int coreinfer_compact_update(const void* w_up, const void* w_gate, const void* b
   if ((act == CI_ACT_SWIGLU) != (w_gate != nullptr) || (w_gate != nullptr) != (w_gate_c != nullptr))
     return CI_ERR_INVALID_ARG;
   if ((b_up != nullptr) != (b_up_c != nullptr)) return CI_ERR_INVALID_ARG;
+  if (act == CI_ACT_SWIGLU && b_up) return CI_ERR_INVALID_ARG;
   if (d % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
   if (!aligned16(w_up) || !aligned16(w_gate) || !aligned16(w_down) || !aligned16(w_up_c) ||
       !aligned16(w_gate_c) || !aligned16(w_down_c) || (reinterpret_cast<uintptr_t>(new_idx) & 3u) ||
@@ -303,15 +319,19 @@ int coreinfer_compact_update(const void* w_up, const void* w_gate, const void* b
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
   return launch_compact_update(w_up, w_gate, b_up, w_down, down_layout, dtype, d, N, new_idx, K, slot_idx,
-                               w_up_c, w_gate_c, b_up_c, w_down_c, changed, reinterpret_cast<uint32_t*>(ws),
-                               (hipStream_t)stream);
+                               w_up_c, w_gate_c, b_up_c, w_down_c, down_c_layout, changed,
+                               reinterpret_cast<uint32_t*>(ws), (hipStream_t)stream);
 }
 
 int coreinfer_ffn_decode_workspace_size(int64_t B, int64_t K, int64_t d, size_t* bytes) {
   if (!bytes || B < 1 || B > 65535 || K < 0 || K > CI_MAX_NEURONS || d < 1 || d > CI_MAX_DMODEL)
     return CI_ERR_INVALID_ARG;
+  // two-launch path: fp32 partial outputs of the neuron slices; single-launch path: a header and
+  // one 8-byte word per neuron.  One size serves both, so the caller need not know the path.
   const int64_t splits = K < kMaxSplits ? K : kMaxSplits;
-  *bytes = round256((size_t)B * (size_t)splits * (size_t)d * sizeof(float)) + 256;
+  const size_t two = round256((size_t)B * (size_t)splits * (size_t)d * sizeof(float)) + 256;
+  const size_t one = round256(fused_decode_ws_bytes(K));
+  *bytes = two > one ? two : one;
   return CI_OK;
 }
 
@@ -319,19 +339,35 @@ int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int 
                          void* y, void* ws, size_t ws_bytes, void* stream) {
   if (!w) return CI_ERR_INVALID_ARG;
   if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  if (!layout_ok(w->down_layout)) return CI_ERR_BAD_LAYOUT;
   size_t need = 0;
   if (coreinfer_ffn_decode_workspace_size(B, w->K, w->d, &need) != CI_OK) return CI_ERR_INVALID_ARG;
   if (!x || !y) return CI_ERR_INVALID_ARG;
   if (w->K > 0 && (!w->w_up || !w->w_down)) return CI_ERR_INVALID_ARG;
   if (w->K > 0 && (act == CI_ACT_SWIGLU) != (w->w_gate != nullptr)) return CI_ERR_INVALID_ARG;
+  if (act == CI_ACT_SWIGLU && w->b_up) return CI_ERR_INVALID_ARG;
   if (w->core_idx && (w->N < 1 || w->N > CI_MAX_NEURONS)) return CI_ERR_INVALID_ARG;
   if (w->d % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
+  const bool out_major = w->down_layout == CI_DOWN_OUT_MAJOR;
+  if (out_major && w->core_idx) return CI_ERR_BAD_LAYOUT;  // gathered rows need the neuron-major matrix
+  if (out_major && w->K > 0 && (w->ld_down < w->K || w->ld_down % vec_of(dtype) != 0 || w->ld_down > CI_MAX_NEURONS))
+    return CI_ERR_BAD_LAYOUT;
   if (!aligned16(x) || !aligned16(y) || !aligned16(w->w_up) || !aligned16(w->w_gate) ||
       !aligned16(w->w_down) || (reinterpret_cast<uintptr_t>(w->core_idx) & 3u))
     return CI_ERR_BAD_LAYOUT;
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
+  if (out_major && w->K > 0) return launch_ffn_decode_fused(x, B, w, dtype, act, y, ws, (hipStream_t)stream);
   return launch_ffn_decode(x, B, w, dtype, act, y, reinterpret_cast<float*>(ws), (hipStream_t)stream);
+}
+
+int coreinfer_ffn_decode_status(const void* ws, int32_t* status_out, void* stream) {
+  if (!ws || !status_out) return CI_ERR_INVALID_ARG;
+  if (!aligned16(ws) || (reinterpret_cast<uintptr_t>(status_out) & 3u)) return CI_ERR_BAD_LAYOUT;
+  if (hipMemcpyAsync(status_out, reinterpret_cast<const char*>(ws) + 4, sizeof(int32_t), hipMemcpyDeviceToDevice,
+                     (hipStream_t)stream) != hipSuccess)
+    return CI_ERR_HIP;
+  return CI_OK;
 }
 
 int coreinfer_union_workspace_size(int64_t N, size_t* bytes) {
@@ -384,6 +420,7 @@ int coreinfer_ffn_decode_union(const void* x, int64_t B, const ci_ffn_weights* w
   if (!x || !y || !union_idx || !union_mask || !union_count) return CI_ERR_INVALID_ARG;
   if (!w->w_up || !w->w_down || w->N < 1 || w->N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
   if ((act == CI_ACT_SWIGLU) != (w->w_gate != nullptr)) return CI_ERR_INVALID_ARG;
+  if (act == CI_ACT_SWIGLU && w->b_up) return CI_ERR_INVALID_ARG;
   if (!aligned16(x) || !aligned16(y) || !aligned16(w->w_up) || !aligned16(w->w_gate) ||
       !aligned16(w->w_down) || (reinterpret_cast<uintptr_t>(union_idx) & 3u) ||
       (reinterpret_cast<uintptr_t>(union_mask) & 3u) || (reinterpret_cast<uintptr_t>(union_count) & 3u))
@@ -421,6 +458,7 @@ int coreinfer_ffn_dense(const void* X, int64_t M, const void* w_up, const void* 
   if (coreinfer_ffn_dense_workspace_size(M, d, N, dtype, &need) != CI_OK) return CI_ERR_INVALID_ARG;
   if (!X || !w_up || (!Y && !A) || (Y && !w_down)) return CI_ERR_INVALID_ARG;
   if ((act == CI_ACT_SWIGLU) != (w_gate != nullptr)) return CI_ERR_INVALID_ARG;
+  if (act == CI_ACT_SWIGLU && b_up) return CI_ERR_INVALID_ARG;
   if (d % vec_of(dtype) != 0 || N % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
   if (!aligned16(X) || !aligned16(w_up) || !aligned16(w_gate) || !aligned16(w_down) ||
       !aligned16(Y) || !aligned16(A))
@@ -440,6 +478,7 @@ int coreinfer_ffn_dense(const void* X, int64_t M, const void* w_up, const void* 
       ci_ffn_weights w;
       w.w_up = w_up; w.w_gate = w_gate; w.b_up = b_up; w.w_down = w_down; w.b_down = b_down;
       w.core_idx = nullptr; w.K = N; w.d = d; w.N = N;
+      w.ld_down = 0; w.down_layout = CI_DOWN_NEURON_MAJOR;
       float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) +
                                                 round256((size_t)M * (size_t)N * sizeof(float)));
       return launch_ffn_decode(X, M, &w, dtype, act, Y, partial, s);
@@ -474,6 +513,7 @@ int coreinfer_ffn_dense_hidden(const void* X, int64_t M, const void* w_up, const
   if (coreinfer_ffn_dense_hidden_workspace_size(M, d, N, dtype, &need) != CI_OK) return CI_ERR_INVALID_ARG;
   if (!X || !w_up || !H || (Y && !w_down)) return CI_ERR_INVALID_ARG;
   if ((act == CI_ACT_SWIGLU) != (w_gate != nullptr)) return CI_ERR_INVALID_ARG;
+  if (act == CI_ACT_SWIGLU && b_up) return CI_ERR_INVALID_ARG;
   if (d % vec_of(dtype) != 0 || N % vec_of(dtype) != 0) return CI_ERR_BAD_LAYOUT;
   if (!aligned16(X) || !aligned16(w_up) || !aligned16(w_gate) || !aligned16(w_down) || !aligned16(Y) ||
       !aligned16(H))

@@ -109,25 +109,38 @@ struct DeviceInfo {
 // Compute-unit count of the current device (queried once per device).
 int device_info(DeviceInfo* out);
 
-// Development knobs (see coreinfer_set_param).
+// Development knobs (see coreinfer_dev.h).  Relaxed atomics: a sweep may change one while
+// another thread is inside an entry point; each reads a consistent value of each knob.
+struct Knob {
+  std::atomic<int> v;
+  explicit Knob(int x) : v(x) {}
+  operator int() const { return v.load(std::memory_order_relaxed); }
+  void operator=(int x) { v.store(x, std::memory_order_relaxed); }
+};
 struct Params {
-  int decode_wgs_per_cu = 1;
-  int decode_wgs = 0;        // absolute number of neuron slices per sentence (0 = per-CU rule)
-  int decode_threads = 0;  // 0 = derived from d
-  int decode_depth = 4;    // weight rows in flight per thread (4, 8 or 16)
-  int select_wgs_per_cu = 2;
-  int select_debug = 0;
-  int gemv_wgs_per_cu = 4;
-  int gemm_ring = 1;         // register-ring GEMM kernel where it applies
-  int gemm_direct = 1;       // 128 x 128 tiles loaded straight into LDS instead of through the register ring
-  int gemm_big = 1;          // 256 x 256 tiles: 0 never, 1 when there are enough of them, 2 whenever the shape divides
-  int reduce_cq = 8;        // column quads per reduce workgroup (4, 8, 16)
-  int decode_nt_store = 1;  // non-temporal stores for the partial sums
-  int decode_skip_reduce = 0;  // timing only: launch the slice kernel without the reduction
-  int union_depth = 8;            // union-batched decode: rows in flight per thread (8 or 16)
-  int union_down_threads = 384;   // threads (= 16-byte column vectors) per down-phase workgroup
-  int union_up_wgs_per_cu = 1;
-  int union_down_wgs_per_cu = 2;
+  Knob decode_wgs_per_cu{1};
+  Knob decode_wgs{0};        // absolute number of neuron slices per sentence (0 = per-CU rule)
+  Knob decode_threads{0};    // 0 = derived from d
+  Knob decode_depth{4};      // weight rows in flight per thread (4, 8 or 16)
+  Knob select_wgs_per_cu{2};
+  Knob select_def2_single{0};  // Def. 2 in one workgroup even where the parallel kernel applies
+  Knob gemv_wgs_per_cu{4};
+  Knob gemm_ring{1};         // register-ring GEMM kernel where it applies
+  Knob gemm_direct{1};       // 128 x 128 tiles loaded straight into LDS instead of through the register ring
+  Knob gemm_big{1};          // 256 x 256 tiles: 0 never, 1 when there are enough of them, 2 whenever the shape divides
+  Knob reduce_cq{8};         // column quads per reduce workgroup (4, 8, 16)
+  Knob decode_nt_store{1};   // non-temporal stores for the partial sums
+  Knob union_depth{8};            // union-batched decode: rows in flight per thread (8 or 16)
+  Knob union_down_threads{384};   // threads (= 16-byte column vectors) per down-phase workgroup
+  Knob union_up_wgs_per_cu{1};
+  Knob union_down_wgs_per_cu{2};
+  Knob fused_depth{4};     // single-launch decode: rows in flight per thread (4, 8 or 16)
+  Knob fused_threads{0};   // 0 = derived from d
+  Knob fused_chunks{2};    // least number of neuron chunks
+  Knob fused_wgs{0};       // 0 = one workgroup per compute unit
+  Knob fused_ablate{0};    // development builds only
+  Knob fused_guard_us10{12}; // tenths of a microsecond after a phase's end at which its hidden values are collected
+  Knob fused_aux{0};       // ring loads: buffer loads with these cache-policy bits (0, 16), or global loads (-1 non-temporal, -2 plain)
 };
 Params& params();
 
@@ -169,19 +182,27 @@ int launch_assign_group(const int32_t* set, int64_t K, const int32_t* groups, in
                         int32_t* best, int32_t* iu, hipStream_t s);
 int launch_assign_centroid(const float* act, int64_t M, int64_t N, int64_t ld, const float* centroids,
                            int64_t G, int32_t* best, float* dist, float* feature, hipStream_t s);
+// Leading dimension of an output-major compact down matrix [d, ld]: K rounded up to whole 16-byte vectors.
+inline int64_t compact_down_ld(int64_t K, int dtype) {
+  const int64_t v = 16 / elem_bytes(dtype);
+  return (K + v - 1) / v * v;
+}
 int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                    int down_layout, int dtype, int64_t d, int64_t N, const int32_t* core_idx,
                    int64_t K, void* w_up_c, void* w_gate_c, void* b_up_c, void* w_down_c,
-                   int32_t* status, hipStream_t s);
+                   int down_c_layout, int32_t* status, hipStream_t s);
 int launch_compact_update(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                           int down_layout, int dtype, int64_t d, int64_t N, const int32_t* new_idx,
                           int64_t K, int32_t* slot_idx, void* w_up_c, void* w_gate_c, void* b_up_c,
-                          void* w_down_c, int32_t* changed, uint32_t* ws, hipStream_t s);
+                          void* w_down_c, int down_c_layout, int32_t* changed, uint32_t* ws, hipStream_t s);
 int decode_splits(int64_t B, int64_t K);
 int launch_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,
                       void* y, float* partial, hipStream_t s);
 int launch_decode_reduce(const float* partial, const void* b_down, void* y, int n_wg, int d, int B,
                          int dtype, hipStream_t s);
+size_t fused_decode_ws_bytes(int64_t K);
+int launch_ffn_decode_fused(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act, void* y,
+                            void* ws, hipStream_t s);
 int union_up_chunks(int64_t vecs);
 int launch_union_build(const int32_t* core_idx, int64_t B, int64_t K, int64_t N, int64_t cap,
                        int32_t* uidx, uint32_t* umask, int32_t* ucount, uint32_t* owners,

@@ -12,6 +12,13 @@
 //                             cache lines.
 //   compact_fused_kernel    : both of the above in one launch (column tiles
 //                             first) when the down matrix is [d, N].
+// For the single-launch decode the down matrix is kept output-major instead,
+// out [d, ld] = w_down[:, S] with the columns K .. ld-1 zero:
+//   gather_cols_kernel      : out[j, k] = in[j, S[k]] from the nn.Linear
+//                             [d, N] matrix: a thread holds the indices of one
+//                             16-byte group of k and walks down the rows.
+//   gather_rows_t_kernel    : out[j, k] = in[S[k], j] from a neuron-major
+//                             [N, d] matrix, 64x64 tiles through LDS.
 #include "common.hpp"
 
 namespace ci {
@@ -116,6 +123,83 @@ __global__ __launch_bounds__(256) void compact_fused_kernel(RowGather g, const E
   } else {
     const int r = b - n_col_blocks;
     gather_row(g, idx, r % K, r / K, N, vecs_per_row, status);
+  }
+}
+
+// out[j, k] = in[j, S[k]] for k < K, 0 for K <= k < ld.  A thread owns VE = 16 / sizeof(E)
+// consecutive k (one 16-byte store per row) and ROWS rows; the indices stay in registers.
+template <class E, int ROWS>
+__global__ __launch_bounds__(256) void gather_cols_kernel(const E* __restrict__ in, E* __restrict__ out,
+                                                          const int32_t* __restrict__ idx, int K, int ld,
+                                                          int N, int d, int32_t* status) {
+  constexpr int VE = 16 / sizeof(E);
+  const int kv = blockIdx.x * 256 + threadIdx.x;  // 16-byte group along k
+  const int k0 = kv * VE;
+  if (k0 >= ld) return;
+  uint32_t src[VE];
+  bool okv[VE];
+  bool bad = false;
+#pragma unroll
+  for (int e = 0; e < VE; ++e) {
+    const int k = k0 + e;
+    okv[e] = k < K && index_ok(idx, k, N);
+    bad |= k < K && !okv[e];
+    src[e] = okv[e] ? (uint32_t)idx[k] : 0u;
+  }
+  if (bad && status && blockIdx.y == 0) *status = 1;
+  const int j0 = blockIdx.y * ROWS;
+#pragma unroll 4
+  for (int r = 0; r < ROWS; ++r) {
+    const int j = j0 + r;
+    if (j >= d) break;
+    const E* row = in + (size_t)j * N;
+    E v[VE];
+#pragma unroll
+    for (int e = 0; e < VE; ++e) v[e] = row[src[e]];
+#pragma unroll
+    for (int e = 0; e < VE; ++e) v[e] = okv[e] ? v[e] : (E)0;
+    uint4 pack;
+    __builtin_memcpy(&pack, v, 16);
+    *reinterpret_cast<uint4*>(out + (size_t)j * ld + k0) = pack;
+  }
+}
+
+// out[j, k] = in[S[k], j] (k < K; 0 up to ld): 64 k x 64 j tiles, reads along j, writes along k.
+template <class E>
+__global__ __launch_bounds__(256) void gather_rows_t_kernel(const E* __restrict__ in, E* __restrict__ out,
+                                                            const int32_t* __restrict__ idx, int K, int ld,
+                                                            int N, int d, int32_t* status) {
+  __shared__ E tile[64][65];
+  __shared__ int srow[64];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int k0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  if (ty == 0) {
+    const int k = k0 + tx;
+    int n = -1;
+    if (k < K) {
+      if (index_ok(idx, k, N)) n = idx[k];
+      else if (status && blockIdx.y == 0) *status = 1;
+    }
+    srow[tx] = n;
+  }
+  __syncthreads();
+  E v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int n = srow[ty + 4 * i];
+    const int j = j0 + tx;
+    const bool take = n >= 0 && j < d;
+    const E t = in[take ? (size_t)n * d + j : (size_t)0];
+    v[i] = take ? t : (E)0;
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) tile[ty + 4 * i][tx] = v[i];
+  __syncthreads();
+  const int k = k0 + tx;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int j = j0 + ty + 4 * i;
+    if (j < d && k < ld) out[(size_t)j * ld + k] = tile[tx][ty + 4 * i];
   }
 }
 
@@ -236,12 +320,27 @@ __global__ __launch_bounds__(256) void delta_cols_t_kernel(const E* __restrict__
   }
 }
 
+// Output-major compact down matrix: column free_list[t] of out [d, ld] takes neuron enter_list[t],
+// from in [d, N] (in_neuron_major == 0) or in [N, d].
+template <class E>
+__global__ __launch_bounds__(256) void delta_cols_kernel(const E* __restrict__ in, E* __restrict__ out,
+                                                         const int32_t* __restrict__ free_list,
+                                                         const int32_t* __restrict__ enter_list,
+                                                         const int32_t* __restrict__ count, int N, int d, int ld,
+                                                         int in_neuron_major) {
+  const int t = blockIdx.x;
+  if (t >= count[0]) return;
+  const size_t dst = (size_t)free_list[t], src = (size_t)enter_list[t];
+  for (int j = blockIdx.y * 256 + threadIdx.x; j < d; j += gridDim.y * 256)
+    out[(size_t)j * ld + dst] = in_neuron_major ? in[src * d + j] : in[(size_t)j * N + src];
+}
+
 }  // namespace
 
 int launch_compact_update(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                           int down_layout, int dtype, int64_t d, int64_t N, const int32_t* new_idx,
                           int64_t K, int32_t* slot_idx, void* w_up_c, void* w_gate_c, void* b_up_c,
-                          void* w_down_c, int32_t* changed, uint32_t* ws, hipStream_t s) {
+                          void* w_down_c, int down_c_layout, int32_t* changed, uint32_t* ws, hipStream_t s) {
   // workspace: flags [N], keep [K], free_list [K], enter_list [K], count [1]
   uint32_t* flags = ws;
   uint32_t* keep = flags + N;
@@ -263,13 +362,27 @@ int launch_compact_update(const void* w_up, const void* w_gate, const void* b_up
   g.n_mat = 0;
   g.in[g.n_mat] = w_up; g.out[g.n_mat++] = w_up_c;
   if (w_gate) { g.in[g.n_mat] = w_gate; g.out[g.n_mat++] = w_gate_c; }
-  if (down_layout == CI_DOWN_NEURON_MAJOR) { g.in[g.n_mat] = w_down; g.out[g.n_mat++] = w_down_c; }
+  const bool down_as_rows = down_layout == CI_DOWN_NEURON_MAJOR && down_c_layout == CI_DOWN_NEURON_MAJOR;
+  if (down_as_rows) { g.in[g.n_mat] = w_down; g.out[g.n_mat++] = w_down_c; }
   for (int i = g.n_mat; i < 3; ++i) { g.in[i] = nullptr; g.out[i] = nullptr; }
   g.b_in = b_up;
   g.b_out = b_up_c;
   g.elem = e;
   // the down columns first: the row kernel rewrites slot_idx, which nothing below reads
-  if (down_layout == CI_DOWN_OUT_MAJOR) {
+  if (down_c_layout == CI_DOWN_OUT_MAJOR) {
+    const int ld = (int)compact_down_ld(K, dtype);
+    dim3 grid((unsigned)K, (unsigned)((d + 1023) / 1024));
+    const int nm = down_layout == CI_DOWN_NEURON_MAJOR ? 1 : 0;
+    if (e == 2)
+      hipLaunchKernelGGL((delta_cols_kernel<uint16_t>), grid, dim3(256), 0, s,
+                         reinterpret_cast<const uint16_t*>(w_down), reinterpret_cast<uint16_t*>(w_down_c),
+                         free_list, enter_list, count, (int)N, (int)d, ld, nm);
+    else
+      hipLaunchKernelGGL((delta_cols_kernel<uint32_t>), grid, dim3(256), 0, s,
+                         reinterpret_cast<const uint32_t*>(w_down), reinterpret_cast<uint32_t*>(w_down_c),
+                         free_list, enter_list, count, (int)N, (int)d, ld, nm);
+    CI_HIP_CHECK_LAUNCH();
+  } else if (down_layout == CI_DOWN_OUT_MAJOR) {
     dim3 grid((unsigned)((K + 63) / 64), (unsigned)((d + 63) / 64));
     if (e == 2)
       hipLaunchKernelGGL((delta_cols_t_kernel<uint16_t>), grid, dim3(256), 0, s,
@@ -290,19 +403,52 @@ int launch_compact_update(const void* w_up, const void* w_gate, const void* b_up
 int launch_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                    int down_layout, int dtype, int64_t d, int64_t N, const int32_t* core_idx,
                    int64_t K, void* w_up_c, void* w_gate_c, void* b_up_c, void* w_down_c,
-                   int32_t* status, hipStream_t s) {
+                   int down_c_layout, int32_t* status, hipStream_t s) {
   if (K == 0) return CI_OK;
   const int e = elem_bytes(dtype);
   RowGather g;
   g.n_mat = 0;
   g.in[g.n_mat] = w_up; g.out[g.n_mat++] = w_up_c;
   if (w_gate) { g.in[g.n_mat] = w_gate; g.out[g.n_mat++] = w_gate_c; }
-  if (down_layout == CI_DOWN_NEURON_MAJOR) { g.in[g.n_mat] = w_down; g.out[g.n_mat++] = w_down_c; }
+  if (down_layout == CI_DOWN_NEURON_MAJOR && down_c_layout == CI_DOWN_NEURON_MAJOR) {
+    g.in[g.n_mat] = w_down; g.out[g.n_mat++] = w_down_c;
+  }
   for (int i = g.n_mat; i < 3; ++i) { g.in[i] = nullptr; g.out[i] = nullptr; }
   g.b_in = b_up;
   g.b_out = b_up_c;
   g.elem = e;
   const int vecs = (int)(d * e / 16);
+  if (down_c_layout == CI_DOWN_OUT_MAJOR) {
+    // output-major compact down matrix [d, ld] first (the larger stream), then the rows of up / gate
+    const int ld = (int)compact_down_ld(K, dtype);
+    if (down_layout == CI_DOWN_OUT_MAJOR) {
+      constexpr int ROWS = 16;
+      dim3 grid((unsigned)((ld / (16 / e) + 255) / 256), (unsigned)((d + ROWS - 1) / ROWS));
+      if (e == 2)
+        hipLaunchKernelGGL((gather_cols_kernel<uint16_t, ROWS>), grid, dim3(256), 0, s,
+                           reinterpret_cast<const uint16_t*>(w_down), reinterpret_cast<uint16_t*>(w_down_c),
+                           core_idx, (int)K, ld, (int)N, (int)d, status);
+      else
+        hipLaunchKernelGGL((gather_cols_kernel<uint32_t, ROWS>), grid, dim3(256), 0, s,
+                           reinterpret_cast<const uint32_t*>(w_down), reinterpret_cast<uint32_t*>(w_down_c),
+                           core_idx, (int)K, ld, (int)N, (int)d, status);
+    } else {
+      dim3 grid((unsigned)((ld + 63) / 64), (unsigned)((d + 63) / 64));
+      if (e == 2)
+        hipLaunchKernelGGL((gather_rows_t_kernel<uint16_t>), grid, dim3(256), 0, s,
+                           reinterpret_cast<const uint16_t*>(w_down), reinterpret_cast<uint16_t*>(w_down_c),
+                           core_idx, (int)K, ld, (int)N, (int)d, status);
+      else
+        hipLaunchKernelGGL((gather_rows_t_kernel<uint32_t>), grid, dim3(256), 0, s,
+                           reinterpret_cast<const uint32_t*>(w_down), reinterpret_cast<uint32_t*>(w_down_c),
+                           core_idx, (int)K, ld, (int)N, (int)d, status);
+    }
+    CI_HIP_CHECK_LAUNCH();
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)K, g.n_mat), dim3(256), 0, s, g, core_idx,
+                       (int)N, vecs, status);
+    CI_HIP_CHECK_LAUNCH();
+    return CI_OK;
+  }
   if (down_layout == CI_DOWN_OUT_MAJOR) {
     const int kblocks = (int)((K + 63) / 64);
     const int64_t n_col = (int64_t)kblocks * ((d + 63) / 64);

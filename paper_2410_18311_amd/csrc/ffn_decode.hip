@@ -92,6 +92,13 @@ __global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(Decode
   const int tid = threadIdx.x, nt = blockDim.x;
   const int lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   const int wg = blockIdx.x, b = blockIdx.y;
+#ifdef CI_FUSED_STAMPS
+  unsigned long long* st = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(a.partial) + (8 << 20));
+#define CI_OSTAMP(i) do { if (tid == 0) st[wg * 8 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define CI_OSTAMP(i) do { } while (0)
+#endif
+  CI_OSTAMP(0);
   const int r0 = (int)(((int64_t)wg * a.K) / a.n_wg);
   const int r1 = (int)(((int64_t)(wg + 1) * a.K) / a.n_wg);
   const int R = r1 - r0;
@@ -196,7 +203,9 @@ __global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(Decode
       const int q = g0 + (lane >> SH) - lead;
       if ((lane & ((1 << SH) - 1)) == 0 && q >= 0) red[wave * NDOT * kSuper + q] = tot;
     }
+    CI_OSTAMP(1);
     __syncthreads();
+    CI_OSTAMP(2);
 
     // ---- hidden value of each neuron of the super-chunk, fp32 ----
     if (tid < Rs) {  // Rs <= kSuper <= blockDim.x
@@ -220,6 +229,7 @@ __global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(Decode
       hbuf[r] = h;
     }
     __syncthreads();
+    CI_OSTAMP(3);
 
     // ---- phase B: y += h_k * W_down_c[k, :] ----
     for (int g0 = QBp; g0 < NQ; g0 += DEPTH) {
@@ -249,6 +259,7 @@ __global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(Decode
 #undef CI_ISSUE
   }
 
+  CI_OSTAMP(4);
   const bool NT_STORE = a.nt_store != 0;
   float* out = a.partial + ((size_t)b * a.n_wg + wg) * a.d;
 #pragma unroll
@@ -264,6 +275,7 @@ __global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(Decode
       }
     }
   }
+  CI_OSTAMP(5);
 }
 
 // y[b, c] = sum_w partial[b, w, c] + b_down[c].  256 threads = CQ column quads
@@ -365,7 +377,6 @@ int launch_typed(const DecodeArgs& a, int B, int nt, int ni, const void* b_down,
     }
     if (rc != CI_OK) return rc;
   }
-  if (params().decode_skip_reduce) return CI_OK;
   return launch_reduce_typed<D>(a.partial, b_down, y, a.n_wg, a.d, B, s);
 }
 

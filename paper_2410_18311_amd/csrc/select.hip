@@ -1004,7 +1004,7 @@ int launch_select(const void* act, int act_dtype, int take_abs, int64_t M64, int
   const int nblocks = (N + 255) / 256;
   // Def. 2 in parallel needs the histogram that the counting launch fills
   const bool parallel_final = (what & kSelTokens) && (what & kSelFinal) && !(what & kSelAccumulate) &&
-                              max_count < kCountBins && nblocks <= 256 && params().select_debug == 0;
+                              max_count < kCountBins && nblocks <= 256 && params().select_def2_single == 0;
   if (what & kSelTokens) {
     SelectWs w;
     select_ws_layout(M, N, &w);
@@ -1027,7 +1027,7 @@ int launch_select(const void* act, int act_dtype, int take_abs, int64_t M64, int
       return CI_OK;
     }
   }
-  if (!(what & kSelFinal) || params().select_debug == 1) return CI_OK;
+  if (!(what & kSelFinal)) return CI_OK;
   const int mc = (int)max_count;
 #define CI_DEF2(I) launch_def2_single<I>(N, counts, K, core_idx, mc, s)
   if (items <= 4) return CI_DEF2(4);

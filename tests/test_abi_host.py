@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol(lib):
     for n in names:
         assert hasattr(lib.raw, n), n
     assert set(names) == set(lib.EXPORTS)
-    assert lib.version() >= 1
+    assert lib.version() >= 2
 
 
 def test_strerror_names_every_status(lib):
@@ -85,20 +85,31 @@ def test_select_rejects_bad_arguments_without_a_gpu(lib):
 def test_compact_rejects_bad_arguments_without_a_gpu(lib):
     r = lib.raw.coreinfer_compact
     F = FAKE
-    # (w_up, w_gate, b_up, w_down, layout, dtype, act, d, N, idx, K, up_c, gate_c, b_c, down_c, status, stream)
-    assert r(F, None, None, F, 0, 7, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_DTYPE
-    assert r(F, None, None, F, 0, 1, 5, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_DTYPE
-    assert r(F, None, None, F, 3, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_LAYOUT
-    assert r(None, None, None, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 200, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, None, F, 0, 1, 0, 64, 128, None, 8, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
+    # (w_up, w_gate, b_up, w_down, layout, dtype, act, d, N, idx, K, up_c, gate_c, b_c, down_c, down_c_layout,
+    #  status, stream)
+    assert r(F, None, None, F, 0, 7, 0, 64, 128, F, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, None, None, F, 0, 1, 5, 64, 128, F, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, None, None, F, 3, 1, 0, 64, 128, F, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(None, None, None, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 200, F, None, None, F, 1, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, None, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_INVALID_ARG
     # gate given for ReLU / missing for SwiGLU; bias in without bias out
-    assert r(F, F, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, F, None, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, None, F, 0, 1, 1, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, F, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, F, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, F, 1, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 1, 64, 128, F, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, F, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_INVALID_ARG
     # d not a multiple of 8 halfs; misaligned pointer
-    assert r(F, None, None, F, 0, 1, 0, 60, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_LAYOUT
-    assert r(F + 8, None, None, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, None, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, None, None, F, 0, 1, 0, 60, 128, F, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F + 8, None, None, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, 1, None, None) == lib.CI_ERR_BAD_LAYOUT
+    # layout of the compact down matrix out of range; up bias with a gated FFN
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F, None, None, F, 2, None, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, F, F, F, 0, 1, 1, 64, 128, F, 8, F, F, F, F, 0, None, None) == lib.CI_ERR_INVALID_ARG
+    ld = ctypes.c_int64(0)
+    assert lib.raw.coreinfer_compact_down_ld(6554, 1, ctypes.byref(ld)) == lib.CI_OK and ld.value == 6560
+    assert lib.raw.coreinfer_compact_down_ld(410, 0, ctypes.byref(ld)) == lib.CI_OK and ld.value == 412
+    assert lib.raw.coreinfer_compact_down_ld(0, 2, ctypes.byref(ld)) == lib.CI_OK and ld.value == 0
+    assert lib.raw.coreinfer_compact_down_ld(8, 5, ctypes.byref(ld)) == lib.CI_ERR_BAD_DTYPE
+    assert lib.raw.coreinfer_compact_down_ld(-1, 1, ctypes.byref(ld)) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_compact_down_ld(8, 1, None) == lib.CI_ERR_INVALID_ARG
 
 
 def test_compact_update_rejects_bad_arguments_without_a_gpu(lib):
@@ -106,18 +117,19 @@ def test_compact_update_rejects_bad_arguments_without_a_gpu(lib):
     F = FAKE
     big = 1 << 24
     # (w_up, w_gate, b_up, w_down, layout, dtype, act, d, N, new_idx, K, slot_idx, w_up_c, w_gate_c, b_up_c,
-    #  w_down_c, changed, ws, ws_bytes, stream)
-    assert r(F, None, None, F, 0, 6, 0, 64, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_BAD_DTYPE
-    assert r(F, None, None, F, 3, 1, 0, 64, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
-    assert r(F, None, None, F, 0, 1, 0, 64, 128, None, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, None, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 200, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, None, F, 0, 1, 1, 64, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, F, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_INVALID_ARG
-    assert r(F, None, None, F, 0, 1, 0, 60, 128, F, 8, F, F, None, None, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
-    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F + 2, F, None, None, F, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
-    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, None, None, big, None) == lib.CI_ERR_WORKSPACE
-    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, None, F, 100, None) == lib.CI_ERR_WORKSPACE
+    #  w_down_c, down_c_layout, changed, ws, ws_bytes, stream)
+    assert r(F, None, None, F, 0, 6, 0, 64, 128, F, 8, F, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, None, None, F, 3, 1, 0, 64, 128, F, 8, F, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, None, 8, F, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, None, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 200, F, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 1, 64, 128, F, 8, F, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, F, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, None, None, F, 0, 1, 0, 60, 128, F, 8, F, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F + 2, F, None, None, F, 1, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, 1, None, None, big, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, 1, None, F, 100, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, None, None, F, 0, 1, 0, 64, 128, F, 8, F, F, None, None, F, 7, None, F, big, None) == lib.CI_ERR_BAD_LAYOUT
     n = ctypes.c_size_t(0)
     assert lib.raw.coreinfer_compact_update_workspace_size(128, 8, ctypes.byref(n)) == lib.CI_OK
     assert n.value >= (128 + 3 * 8 + 1) * 4
@@ -130,7 +142,8 @@ def test_ffn_decode_rejects_bad_arguments_without_a_gpu(lib):
     big = 1 << 30
 
     def W(**kw):
-        base = dict(w_up=F, w_gate=None, b_up=None, w_down=F, b_down=None, core_idx=None, K=16, d=64, N=16)
+        base = dict(w_up=F, w_gate=None, b_up=None, w_down=F, b_down=None, core_idx=None, K=16, d=64, N=16,
+                    ld_down=0, down_layout=1)
         base.update(kw)
         return ctypes.byref(lib.ci_ffn_weights(**base))
 
@@ -149,6 +162,15 @@ def test_ffn_decode_rejects_bad_arguments_without_a_gpu(lib):
     assert r(F, 1, W(core_idx=F, N=0), 1, 0, F, F, big, None) == lib.CI_ERR_INVALID_ARG
     assert r(F, 1, W(), 1, 0, F, None, big, None) == lib.CI_ERR_WORKSPACE
     assert r(F, 1, W(), 1, 0, F, F, 64, None) == lib.CI_ERR_WORKSPACE
+    # up bias with a gated FFN; layout enum; output-major compact matrix: row length, gathered rows
+    assert r(F, 1, W(w_gate=F, b_up=F), 1, 1, F, F, big, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, W(down_layout=2), 1, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 1, W(down_layout=0, ld_down=8), 1, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT     # shorter than K
+    assert r(F, 1, W(down_layout=0, ld_down=20), 1, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT    # not whole vectors
+    assert r(F, 1, W(down_layout=0, ld_down=16, core_idx=F), 1, 0, F, F, big, None) == lib.CI_ERR_BAD_LAYOUT
+    st = lib.raw.coreinfer_ffn_decode_status
+    assert st(None, F, None) == lib.CI_ERR_INVALID_ARG and st(F, None, None) == lib.CI_ERR_INVALID_ARG
+    assert st(F + 4, F, None) == lib.CI_ERR_BAD_LAYOUT
 
 
 def test_ffn_dense_rejects_bad_arguments_without_a_gpu(lib):
@@ -293,11 +315,17 @@ def test_union_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert r(F, 2, W(), F, F, F, 128, 1, 0, F, F, 1024, None) == lib.CI_ERR_WORKSPACE
 
 
-def test_set_param_validation(lib):
-    assert lib.raw.coreinfer_set_param(b"no_such_knob", 1) == lib.CI_ERR_INVALID_ARG
-    assert lib.raw.coreinfer_set_param(b"decode_wgs_per_cu", 0) == lib.CI_ERR_INVALID_ARG
-    assert lib.raw.coreinfer_set_param(None, 1) == lib.CI_ERR_INVALID_ARG
-    assert lib.raw.coreinfer_set_param(b"decode_wgs_per_cu", 2) == lib.CI_OK
+def test_development_hook_validation(lib):
+    """csrc/coreinfer_dev.h: launch-shape parameters, not declared in the installed header."""
+    r = lib.raw.coreinfer_dev_set_param
+    assert r(b"no_such_knob", 1) == lib.CI_ERR_INVALID_ARG
+    assert r(b"decode_wgs_per_cu", 0) == lib.CI_ERR_INVALID_ARG
+    assert r(None, 1) == lib.CI_ERR_INVALID_ARG
+    assert r(b"decode_wgs_per_cu", 2) == lib.CI_OK and r(b"decode_wgs_per_cu", 1) == lib.CI_OK
+    # no setting makes a call skip its output: the two that did are gone
+    assert r(b"decode_skip_reduce", 1) == lib.CI_ERR_INVALID_ARG
+    assert r(b"select_debug", 1) == lib.CI_ERR_INVALID_ARG
+    assert "coreinfer_dev_set_param" not in _declared_symbols()
 
 
 def test_workloads_module_has_the_five_configurations():

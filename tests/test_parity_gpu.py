@@ -452,11 +452,11 @@ def test_dense_random_shapes(lib, direct):
     """Seeded sweep over prompt lengths and widths around the tile edges of every GEMM variant
     (ragged and even, reduction lengths that are and are not multiples of the k tile), with the
     128 x 128 tiles loaded straight into LDS (the default) and through the register ring."""
-    lib.set_param("gemm_direct", direct)
+    lib.dev_set_param("gemm_direct", direct)
     try:
         _dense_random_shapes(lib)
     finally:
-        lib.set_param("gemm_direct", 1)
+        lib.dev_set_param("gemm_direct", 1)
 
 
 def _dense_random_shapes(lib):
@@ -496,13 +496,13 @@ def test_dense_large_tile_kernel_matches_oracle(lib, dt, act, layout, M, d, N):
     dtype = DTYPES[dt]
     w = rand_weights(d, N, dtype, act, layout, seed=M + d + N + 9, device=DEV)
     X = torch.randn(M, d, generator=torch.Generator().manual_seed(M + 1)).to(dtype).to(DEV)
-    lib.set_param("gemm_big", 2)
+    lib.dev_set_param("gemm_big", 2)
     try:
         Y, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], layout, act,
                              want_y=True, want_a=True)
         torch.cuda.synchronize()
     finally:
-        lib.set_param("gemm_big", 1)
+        lib.dev_set_param("gemm_big", 1)
     if act == "relu":
         A_ref = orc.score_relu(f64(X), f64(w["w_up"]), f64(w["b_up"]))
     else:
@@ -534,7 +534,7 @@ def test_dense_many_tiles_with_split_down_projection(lib, layout):
 
 
 @pytest.mark.parametrize("knob,value,default", [("gemm_ring", 0, 1), ("gemm_direct", 0, 1), ("gemm_big", 0, 1), ("select_wgs_per_cu", 1, 2),
-                                                ("select_debug", 2, 0), ("decode_depth", 8, 4), ("decode_depth", 16, 4),
+                                                ("select_def2_single", 1, 0), ("decode_depth", 8, 4), ("decode_depth", 16, 4),
                                                 ("decode_wgs_per_cu", 2, 1), ("decode_nt_store", 0, 1),
                                                 ("reduce_cq", 4, 8), ("reduce_cq", 16, 8), ("union_depth", 16, 8),
                                                 ("union_down_threads", 128, 384), ("decode_threads", 512, 0), ("decode_threads", 64, 0),
@@ -549,7 +549,7 @@ def test_alternative_launch_shapes_give_the_same_results(lib, knob, value, defau
     dt = torch.bfloat16
     w = rand_weights(d, N, dt, "swiglu", "neuron_major", seed=21, device=DEV)
     X = torch.randn(M, d, generator=torch.Generator().manual_seed(8)).to(dt).to(DEV)
-    lib.set_param(knob, value)
+    lib.dev_set_param(knob, value)
     try:
         Y, A = lib.ffn_dense(X, w["w_up"], w["w_gate"], None, w["w_down"], w["b_down"], "neuron_major", "swiglu",
                              want_y=True, want_a=True)
@@ -565,7 +565,7 @@ def test_alternative_launch_shapes_give_the_same_results(lib, knob, value, defau
         y_u = lib.ffn_decode_union(x, resident, uidx, umask, ucount, "swiglu")
         torch.cuda.synchronize()
     finally:
-        lib.set_param(knob, default)
+        lib.dev_set_param(knob, default)
     A_ref = orc.score_swiglu(f64(X), f64(w["w_gate"]), f64(w["w_up"]))
     assert np.max(np.abs(f64(A) - A_ref)) <= 1e-4 * np.sqrt(np.mean(A_ref ** 2))
     assert_close_rms(Y, _oracle_ffn("swiglu", X, None, w, "neuron_major"), dt, f"{knob}: dense Y")
