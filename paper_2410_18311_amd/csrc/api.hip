@@ -88,6 +88,8 @@ int coreinfer_dev_set_param(const char* name, int value) {
   else if (!strcmp(name, "fused_chunks") && value >= 2 && value <= 64) p.fused_chunks = value;
   else if (!strcmp(name, "fused_wgs") && value >= 0 && value <= 1024) p.fused_wgs = value;
   else if (!strcmp(name, "fused_guard_us10") && value >= 0 && value <= 1000) p.fused_guard_us10 = value;
+  else if (!strcmp(name, "fused_chunk_cost10") && value >= 0 && value <= 1000) p.fused_chunk_cost10 = value;
+  else if (!strcmp(name, "fused_window_slots") && value >= 0 && value <= 1000) p.fused_window_slots = value;
   else if (!strcmp(name, "fused_ablate") && value >= 0 && value <= 2) p.fused_ablate = value;
   else if (!strcmp(name, "fused_aux") && (value == -1 || value == -2 || value == 0 || value == 16)) p.fused_aux = value;
   else if (!strcmp(name, "select_def2_single") && (value == 0 || value == 1)) p.select_def2_single = value;

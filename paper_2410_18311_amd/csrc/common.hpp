@@ -139,6 +139,8 @@ struct Params {
   Knob fused_chunks{2};    // least number of neuron chunks
   Knob fused_wgs{0};       // 0 = one workgroup per compute unit
   Knob fused_ablate{0};    // development builds only
+  Knob fused_chunk_cost10{80};  // tenths of a ring slot that a chunk's two barriers are counted as
+  Knob fused_window_slots{13};  // ring slots the exchange of a chunk needs between its publication and its use
   Knob fused_guard_us10{12}; // tenths of a microsecond after a phase's end at which its hidden values are collected
   Knob fused_aux{0};       // ring loads: buffer loads with these cache-policy bits (0, 16), or global loads (-1 non-temporal, -2 plain)
 };

@@ -91,7 +91,9 @@ struct FusedArgs {
 // One phase as the issuing or the consuming side sees it (all fields uniform).
 struct Phase {
   int ngroups;         // ring groups
-  int Q;               // rows to dot: NDOT * Ra (A) or R (B)
+  int Q;               // ring items: NDOT * Ra rows (A), or ceil(R / RG) sets of RG rows (B)
+  int rows;            // rows to dot: NDOT * Ra (A) or R, the outputs of this workgroup (B)
+  int RG, PBw;         // B: RG rows are dotted side by side, each by PBw waves (A: 1 row by all waves)
   int Ra;              // A: neurons of this workgroup in the chunk
   int lim;             // 16-byte positions of a row that exist (others re-read position 0)
   int row0;            // A: first neuron (row of w_up_c); B: first output (row of w_down_o)
@@ -107,8 +109,11 @@ __device__ __forceinline__ float wave_rows(float (&v)[DEPTH], int lane) {
   return v[0];
 }
 
-template <class D, bool SWIGLU, int DEPTH>
-__device__ __forceinline__ void describe(const FusedArgs& a, int ph, int wg, Phase* p) {
+// B phases, one load per thread and row (NI == 1): a chunk row segment has Pn 16-byte positions, often far
+// fewer than the workgroup has compute lanes.  So PBw = ceil(Pn / 64) waves take one row and the
+// nwc / PBw such wave sets work on RG different rows at the same time (one ring item = RG rows).
+template <class D, bool SWIGLU, int DEPTH, int NI>
+__device__ __forceinline__ void describe(const FusedArgs& a, int ph, int wg, int nwc, Phase* p) {
   using T = typename D::T;
   constexpr int VEC = D::VEC;
   constexpr int NDOT = SWIGLU ? 2 : 1;
@@ -122,6 +127,9 @@ __device__ __forceinline__ void describe(const FusedArgs& a, int ph, int wg, Pha
     const int ra1 = k0 + (int)(((uint32_t)(wg + 1) * (uint32_t)Kc) / (uint32_t)a.n_wg);
     p->Ra = ra1 - ra0;
     p->Q = NDOT * p->Ra;
+    p->rows = p->Q;
+    p->RG = 1;
+    p->PBw = nwc;
     p->ngroups = (p->Q + DEPTH - 1) / DEPTH;
 #ifdef CI_FUSED_STAMPS
     if (a.ablate == 2) p->ngroups = 0;
@@ -137,8 +145,12 @@ __device__ __forceinline__ void describe(const FusedArgs& a, int ph, int wg, Pha
     const int R = c1 - c0;
     const int Pn = (Kc + VEC - 1) / VEC;
     p->Ra = 0;
-    p->Q = R;
-    p->ngroups = (R > 0 && Pn > 0) ? (R + DEPTH - 1) / DEPTH : 0;
+    p->PBw = NI == 1 ? max((Pn + 63) >> 6, 1) : nwc;
+    p->RG = 1;
+    for (int t = 2 * p->PBw; t <= nwc; t += p->PBw) ++p->RG;  // nwc / PBw
+    p->rows = R;
+    p->Q = (R + p->RG - 1) / p->RG;
+    p->ngroups = (R > 0 && Pn > 0) ? (p->Q + DEPTH - 1) / DEPTH : 0;
 #ifdef CI_FUSED_STAMPS
     if (a.ablate == 1) p->ngroups = 0;
 #endif
@@ -151,27 +163,34 @@ __device__ __forceinline__ void describe(const FusedArgs& a, int ph, int wg, Pha
 }
 
 // LDS: red  [2][nwc][NDOT * kSuper]  wave partial dots of an A phase (double-buffered by phase parity),
-//      yred [nwc][rmax]              wave partial outputs, summed over the B phases,
+//      yred [2][nwc][rmax]           wave partial outputs of a B phase (double-buffered by phase parity),
+//      ysum [rmax]                   this workgroup's outputs, summed over the B phases (service wave 0 only),
 //      hbuf [2][hcap]                a chunk's hidden values (by chunk parity)
 __host__ __device__ __forceinline__ int lds_red_floats(int nwc, int ndot) { return 2 * nwc * ndot * kSuper; }
-__host__ __device__ __forceinline__ int lds_yred_floats(int nwc, int rmax) { return (nwc * rmax + 3) & ~3; }  // keeps hbuf 16-byte aligned
+__host__ __device__ __forceinline__ int lds_yred_floats(int nwc, int rmax) {
+  return (2 * nwc * rmax + rmax + 3) & ~3;  // yred and ysum; keeps hbuf 16-byte aligned
+}
 
 // ---- the service wave ---------------------------------------------------------
 // After barrier b (the end of phase b), b < C: publishes this workgroup's hidden values of chunk b.
 // Then collects into LDS every chunk j that has been published (j <= b, j < C) and whose buffer
 // (chunk parity) the compute waves no longer read (j < 2, or B(j - 2) has ended: b >= C + j - 2).
 // B(j) starts after barrier C + j - 1, which this wave reaches only when chunk j is in LDS.
-template <class D, bool SWIGLU, int DEPTH>
+template <class D, bool SWIGLU, int DEPTH, int NI>
 __device__ __forceinline__ void service_wave(const FusedArgs& a, float* smem, int nwc, int sv, int lane, int wg,
                                              uint32_t tag) {
   using T = typename D::T;
   constexpr int VEC = D::VEC;
   constexpr int NDOT = SWIGLU ? 2 : 1;
   float* red = smem;
+  const float* yred = smem + lds_red_floats(nwc, NDOT);
+  float* ysum = smem + lds_red_floats(nwc, NDOT) + 2 * nwc * a.rmax;
   float* hbuf = smem + lds_red_floats(nwc, NDOT) + lds_yred_floats(nwc, a.rmax);
   const int hcap = a.hcap;  // floats per chunk buffer
   const int nph = 2 * a.C;
   int failed = 0;
+  if (sv == 0)
+    for (int r = lane; r < a.rmax; r += 64) ysum[r] = 0.f;
   int fetched = 0;  // chunks [0, fetched) are (or have been) in LDS
   __builtin_amdgcn_s_setprio(3);  // few instructions, all on the critical path of the next phase
 #ifdef CI_FUSED_STAMPS
@@ -181,7 +200,7 @@ __device__ __forceinline__ void service_wave(const FusedArgs& a, float* smem, in
   const __amdgpu_buffer_rsrc_t hrsrc = __builtin_amdgcn_make_buffer_rsrc(a.hws, 0, 0x7fffffff, 0x00020000);
   for (int b = 0; b < nph; ++b) {
     Phase p;
-    describe<D, SWIGLU, DEPTH>(a, b, wg, &p);
+    describe<D, SWIGLU, DEPTH, NI>(a, b, wg, nwc, &p);
     // the up bias of "my" neuron of this chunk, asked for before the wait at the barrier
     float bias = 0.f;
     if (!SWIGLU && sv == 0 && b < a.C && a.b_up && lane < p.Ra)
@@ -201,8 +220,19 @@ __device__ __forceinline__ void service_wave(const FusedArgs& a, float* smem, in
       const unsigned long long word = ((unsigned long long)f2u(h) << 32) | (unsigned long long)tag;
       __hip_atomic_store(a.hws + p.row0 + lane, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // red is double-buffered by phase parity: a buffer is rewritten two phases later, after the next
-    // barrier, which this wave reaches only after it has read the buffer
+    if (sv == 0 && b >= a.C && p.ngroups > 0) {
+      // ---- end of a B phase: this chunk's share of the workgroup's outputs.  Row r was item r / RG
+      // of the wave set r % RG; its PBw waves each hold a partial sum. ----
+      const float* yp = yred + (b & 1) * nwc * a.rmax;
+      for (int r = lane; r < p.rows; r += 64) {
+        const int q = r / p.RG, rg = r - q * p.RG;
+        float t = 0.f;
+        for (int wp = 0; wp < p.PBw; ++wp) t += yp[(rg * p.PBw + wp) * a.rmax + q];
+        ysum[r] += t;
+      }
+    }
+    // red and yred are double-buffered by phase parity: a buffer is rewritten two phases later, after
+    // the next barrier, which this wave reaches only after it has read the buffer
     while (fetched < a.C && fetched <= b && (fetched < 2 || b >= a.C + fetched - 2)) {
       const int j = fetched;
       // The other workgroups publish at about the same time as this one; asking right away would
@@ -280,6 +310,19 @@ __device__ __forceinline__ void service_wave(const FusedArgs& a, float* smem, in
     }
   }
   if (failed && lane == 0) __hip_atomic_store(a.hdr + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (sv == 0) {
+    // ---- the workgroup's outputs ----
+    const int c0 = (int)(((uint32_t)wg * (uint32_t)a.d) / (uint32_t)a.n_wg);
+    const int c1 = (int)(((uint32_t)(wg + 1) * (uint32_t)a.d) / (uint32_t)a.n_wg);
+    for (int r = lane; r < c1 - c0; r += 64) {
+      float t = ysum[r];
+      if (a.b_down) t += to_float<D>(reinterpret_cast<const T*>(a.b_down)[c0 + r]);
+      reinterpret_cast<T*>(a.y)[c0 + r] = from_float<D>(t);
+    }
+    CI_STAMP(31);
+    // every workgroup has read the epoch: this one could not have collected its last chunk otherwise
+    if (wg == 0 && lane == 0) __hip_atomic_store(a.hdr, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 // AUX: cache policy of the ring loads.  >= 0: buffer instruction bits (2 = non-temporal, 16 = device
@@ -293,7 +336,8 @@ __global__ __launch_bounds__(1024) void ffn_decode_fused_kernel(FusedArgs a) {
 
   extern __shared__ float smem[];
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: row addresses depend on it
   const int nwc = (blockDim.x >> 6) - kServiceWaves;  // compute waves
   const int ntc = nwc * 64;               // compute threads
   const int wg = blockIdx.x;
@@ -302,7 +346,7 @@ __global__ __launch_bounds__(1024) void ffn_decode_fused_kernel(FusedArgs a) {
   // the call's tag; the epoch word is rewritten only after every workgroup has published with it
   const uint32_t tag = __hip_atomic_load(a.hdr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
   if (wave >= nwc) {
-    service_wave<D, SWIGLU, DEPTH>(a, smem, nwc, wave - nwc, lane, wg, tag);
+    service_wave<D, SWIGLU, DEPTH, NI>(a, smem, nwc, wave - nwc, lane, wg, tag);
     return;
   }
 #ifdef CI_FUSED_STAMPS
@@ -324,38 +368,51 @@ __global__ __launch_bounds__(1024) void ffn_decode_fused_kernel(FusedArgs a) {
     // a position past the end re-reads position 0 (its vector entry is zeroed below)
     xraw[i] = ld16(xrow + (pidx[i] * VEC < a.d ? (size_t)pidx[i] * 16 : (size_t)0));
   }
-  // each (wave, output) slot of yred belongs to one lane for the whole kernel: it clears its own
-  if ((lane & ((1 << SH) - 1)) == 0)
-    for (int q = lane >> SH; q < a.rmax; q += DEPTH) yred[wave * a.rmax + q] = 0.f;
 
   // ---- issue side: one group ahead of the consuming side ----
-  // Per group (uniform): item s of the group reads (s < isel ? ibase0 : ibase1) + s * istride when
-  // s < ivalid, x otherwise; a lane's offset is its position * 16 when the position exists.
+  // Per group and wave (all in scalar registers): item s of the group reads
+  // (s < isel ? ibase0 : ibase1) + s * istride when s < ivalid, x otherwise; a lane adds ioffv, 16 times
+  // its position in the row (0 when it has none), which changes only from phase to phase.
   Phase ip;
   int iph = -1, ig = 0;
   ip.ngroups = 0;
   const char* ibase0 = xrow;
   const char* ibase1 = xrow;
   uint32_t istride = 0;
-  int isel = 0, ivalid = 0, ilim = 0;
+  int isel = 0, ivalid = 0, irg = 0;
+  uint32_t ioffv[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) ioffv[i] = 0;
   auto issue_advance = [&]() {
     ++ig;
     while (ig >= ip.ngroups && iph < nph) {
       ++iph;
       ig = 0;
-      if (iph < nph) describe<D, SWIGLU, DEPTH>(a, iph, wg, &ip);
-      else ip.ngroups = 0;
+      if (iph < nph) {
+        describe<D, SWIGLU, DEPTH, NI>(a, iph, wg, nwc, &ip);
+        // this wave's row set and this lane's position for the whole phase
+        int wp = wave;
+        irg = 0;
+        if (iph >= a.C && NI == 1)
+          while (wp >= ip.PBw) { wp -= ip.PBw; ++irg; }
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          const int pos = (iph >= a.C && NI == 1) ? wp * 64 + lane : pidx[i];
+          ioffv[i] = (pos < ip.lim && irg < ip.RG) ? (uint32_t)pos * 16u : 0u;
+        }
+      } else {
+        ip.ngroups = 0;
+      }
     }
     ivalid = 0;
     if (iph < nph) {
       const bool isB = iph >= a.C;
-      const int q0 = ig * DEPTH;  // first row of the group
-      ilim = ip.lim;
-      istride = ip.stride;
-      ivalid = min(ip.Q - q0, DEPTH);
-      const size_t goff = (size_t)q0 * ip.stride;
+      const int r0 = ig * DEPTH * ip.RG + irg;  // this wave's first row of the group
+      istride = ip.stride * (uint32_t)ip.RG;
+      ivalid = irg < ip.RG ? max(min((ip.rows - r0 + ip.RG - 1) / ip.RG, DEPTH), 0) : 0;
+      const size_t goff = (size_t)r0 * ip.stride;
       // SwiGLU A phase: rows [0, Ra) come from the gate matrix, rows [Ra, 2 Ra) from the up matrix
-      isel = (SWIGLU && !isB) ? max(min(ip.Ra - q0, DEPTH), 0) : 0;
+      isel = (SWIGLU && !isB) ? max(min(ip.Ra - r0, DEPTH), 0) : 0;
       ibase0 = ip.b0 + goff;
       ibase1 = ip.b1 + goff - ((SWIGLU && !isB) ? (size_t)ip.Ra * ip.stride : (size_t)0);
     }
@@ -364,7 +421,7 @@ __global__ __launch_bounds__(1024) void ffn_decode_fused_kernel(FusedArgs a) {
   // Loads of ring position s of the issue cursor's group into slot s.  Every position issues
   // exactly NI 16-byte loads (past the end: of x, which is cache resident) with one and the same
   // instruction and no branch around it, so the number of loads in flight is the same on every
-  // path and the waits can be counted exactly.  Only the base address (uniform) and the lane's
+  // path and the waits can be counted exactly.  Only the base address (scalar) and the lane's
   // offset differ: a row of w_gate_c / w_up_c, a row segment of w_down_o, or x.
   auto issue = [&](int s) {
     const bool valid = s < ivalid;
@@ -372,7 +429,7 @@ __global__ __launch_bounds__(1024) void ffn_decode_fused_kernel(FusedArgs a) {
     const char* base = valid ? rowp : xrow;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const uint32_t off = (valid && pidx[i] < ilim) ? (uint32_t)pidx[i] * 16u : 0u;
+      const uint32_t off = valid ? ioffv[i] : 0u;
       if constexpr (AUX >= 0) {
         const __amdgpu_buffer_rsrc_t rsrc =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, 0x7fffffff, 0x00020000);
@@ -415,27 +472,34 @@ __global__ __launch_bounds__(1024) void ffn_decode_fused_kernel(FusedArgs a) {
   Phase cp;
   int ph = -1, g = 0;
   cp.ngroups = 0;
-  // moves to the next group; a phase that ends meets the service wave at the barrier, and a B phase
+  bool cact = true;  // this wave has rows in the current phase
+  // moves to the next group; a phase that ends meets the service waves at the barrier, and a B phase
   // that begins takes its hidden values out of LDS
   auto consume_advance = [&]() {
     ++g;
     while (g >= cp.ngroups && ph < nph) {
       if (ph >= 0) {
-        __syncthreads();  // end of phase ph (the last one doubles as the barrier before the output)
+        __syncthreads();  // end of phase ph
         CI_STAMP(2 + ph);
       }
       ++ph;
       g = 0;
       if (ph < nph) {
-        describe<D, SWIGLU, DEPTH>(a, ph, wg, &cp);
+        describe<D, SWIGLU, DEPTH, NI>(a, ph, wg, nwc, &cp);
+        cact = true;
         if (ph >= a.C) {
           const float* hb = hbuf + ((ph - a.C) & 1) * hcap;
+          int wp = wave, rg = 0;
+          if (NI == 1)
+            while (wp >= cp.PBw) { wp -= cp.PBw; ++rg; }
+          cact = rg < cp.RG;
 #pragma unroll
           for (int i = 0; i < NI; ++i) {
-            const bool have = pidx[i] < cp.lim;  // the chunk's tail is zero-filled by the service wave
+            const int pos = NI == 1 ? wp * 64 + lane : pidx[i];
+            const bool have = cact && pos < cp.lim;  // the chunk's tail is zero-filled by the service waves
 #pragma unroll
             for (int v = 0; v < VEC; v += 4) {
-              const float4 t = *reinterpret_cast<const float4*>(hb + (have ? pidx[i] * VEC + v : 0));
+              const float4 t = *reinterpret_cast<const float4*>(hb + (have ? pos * VEC + v : 0));
               vr[i][v] = have ? t.x : 0.f;
               vr[i][v + 1] = have ? t.y : 0.f;
               vr[i][v + 2] = have ? t.z : 0.f;
@@ -477,8 +541,8 @@ __global__ __launch_bounds__(1024) void ffn_decode_fused_kernel(FusedArgs a) {
     }
     const float tot = wave_rows<DEPTH>(p, lane);
     const int q = g * DEPTH + (lane >> SH);
-    if ((lane & ((1 << SH) - 1)) == 0 && q < cp.Q) {
-      if (isB) yred[wave * a.rmax + q] += tot;
+    if ((lane & ((1 << SH) - 1)) == 0 && q < cp.Q && cact) {
+      if (isB) yred[((ph & 1) * nwc + wave) * a.rmax + q] = tot;
       else red[(ph & 1) * nwc * NDOT * kSuper + wave * NDOT * kSuper + q] = tot;
     }
 #ifdef CI_FUSED_STAMPS
@@ -490,19 +554,65 @@ __global__ __launch_bounds__(1024) void ffn_decode_fused_kernel(FusedArgs a) {
     consume_advance();
   }
 
-  // the last phase's barrier has been passed: every wave's partial outputs are in LDS
-  {
-    const int c0 = (int)(((uint32_t)wg * (uint32_t)a.d) / (uint32_t)a.n_wg);
-    const int c1 = (int)(((uint32_t)(wg + 1) * (uint32_t)a.d) / (uint32_t)a.n_wg);
-    for (int j = tid; j < c1 - c0; j += ntc) {
-      float s = 0.f;
-      for (int w = 0; w < nwc; ++w) s += yred[w * a.rmax + j];
-      if (a.b_down) s += to_float<D>(reinterpret_cast<const T*>(a.b_down)[c0 + j]);
-      reinterpret_cast<T*>(a.y)[c0 + j] = from_float<D>(s);
+  // the last phase's barrier has been passed: service wave 0 folds the last partial outputs and writes y
+}
+
+// Chooses the chunk size S (and with it the number of chunks C = ceil(K / S)) of a launch.
+// Limits per chunk (cap): one 16-byte position per load of a compute thread, kSuper neurons per
+// workgroup, two chunks of fp32 hidden values in 48 KB of LDS.  Among the sizes that respect them the
+// one with the fewest ring slots on the critical path wins:
+//   A phase of a chunk of Kc neurons: NDOT * ceil(Kc / n_wg) rows, rounded up to whole groups;
+//   B phase: ceil(R / RG) items, RG = nwc / ceil(Pn / 64) rows side by side, rounded up likewise;
+//   + chunk_cost slots per chunk for its two barriers;
+//   + the slots by which the time between a chunk's publication and its use (the phases in between)
+//     falls short of window_slots, the time the exchange needs.
+// Candidates: multiples of U = n_wg * DEPTH / NDOT (every workgroup then owns whole groups of A rows),
+// and equal splits of K in whole positions.  K too small to split: one empty chunk and the rest.
+void plan_chunks(int K, int d, int n_wg, int ndot, int depth, int vec, int ni, int nwc, int64_t cap, int* C_out,
+                 int* S_out, int* hcap_out) {
+  const int R = (d + n_wg - 1) / n_wg;
+  const double chunk_cost = params().fused_chunk_cost10 / 10.0;
+  const int window_slots = params().fused_window_slots;
+  const int min_chunks = params().fused_chunks > 2 ? (int)params().fused_chunks : 2;
+  auto round_up = [](int64_t v, int64_t m) { return (v + m - 1) / m * m; };
+  auto slots = [&](int64_t Kc, int64_t* sa, int64_t* sb) {
+    *sa = round_up(ndot * ((Kc + n_wg - 1) / n_wg), depth);
+    const int64_t Pn = (Kc + vec - 1) / vec;
+    int64_t rg = 1;
+    if (ni == 1) rg = std::max<int64_t>(1, nwc / std::max<int64_t>((Pn + 63) / 64, 1));
+    *sb = round_up((R + rg - 1) / rg, depth);
+  };
+  int64_t U = (int64_t)n_wg * depth / ndot;
+  while (U % vec) U *= 2;
+  double best = -1.0;
+  int64_t best_S = 0, best_C = 0;
+  auto consider = [&](int64_t S) {
+    if (S <= 0 || S >= K || S > cap || S % vec) return;
+    const int64_t C = (K + S - 1) / S, last = K - (C - 1) * S;
+    if (C < min_chunks || C > 4096 || last > cap) return;
+    int64_t a0, b0, a1, b1;
+    slots(S, &a0, &b0);
+    slots(last, &a1, &b1);
+    double cost = (double)((C - 1) * (a0 + b0) + a1 + b1) + chunk_cost * (double)C;
+    // window of chunk j: the A phases after A(j) and the B phases before B(j)
+    for (int64_t j = 0; j < C; ++j) {
+      const int64_t after_a = (C - 2 - j >= 0 ? (C - 2 - j) * a0 : 0) + (j < C - 1 ? a1 : 0);
+      const int64_t before_b = j * b0;
+      if (after_a + before_b < window_slots) cost += (double)(window_slots - after_a - before_b);
     }
+    if (best < 0 || cost < best - 1e-9) { best = cost; best_S = S; best_C = C; }
+  };
+  for (int64_t S = U; S <= cap; S += U) consider(S);
+  for (int64_t C = min_chunks; C <= min_chunks + 6; ++C) consider(round_up((K + C - 1) / C, vec));
+  if (best < 0) {
+    // larger minimum number of chunks than the aligned sizes allow, or K below two positions
+    for (int64_t C = min_chunks; C <= 4096 && best < 0; ++C) consider(round_up((K + C - 1) / C, vec));
   }
-  CI_STAMP(31);
-  if (wg == 0 && tid == 0) __hip_atomic_store(a.hdr, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (best < 0) { best_S = 0; best_C = 2; }  // an empty chunk and one with everything (K <= vec)
+  *C_out = (int)best_C;
+  *S_out = (int)best_S;
+  const int64_t last = K - (best_C - 1) * best_S;
+  *hcap_out = (int)round_up(std::max<int64_t>(best_S, last), vec);
 }
 
 template <class D, int NI, bool SWIGLU, int DEPTH>
@@ -541,33 +651,12 @@ int launch_dtype(FusedArgs a, int act, hipStream_t s) {
     ni = (vecs + want - 1) / want;
   }
   const int nwc = ntc / 64;
-  // Chunks.  All but the last hold S neurons, a multiple of U = n_wg * DEPTH / NDOT (and of VEC): every
-  // workgroup then owns S / n_wg rows of an A phase, a whole number of ring groups, so that only the
-  // last A phase ends in a partly filled group.  The last chunk takes the rest.  Limits per chunk:
-  // one 16-byte position per load of a compute thread, kSuper neurons per workgroup, and two chunks
-  // of fp32 hidden values in 48 KB of LDS.
+  // Chunks: all but the last hold S neurons, the last takes the rest.  S is chosen by counting ring
+  // slots (see plan_chunks).
   const bool swiglu = act == CI_ACT_SWIGLU;
   const int depth = ni >= 2 ? 4 : (params().fused_depth == 8 ? 8 : 4);
-  int64_t U = (int64_t)a.n_wg * depth / (swiglu ? 2 : 1);
-  while (U % VEC) U *= 2;
   const int64_t cap = std::min<int64_t>(std::min<int64_t>((int64_t)ntc * ni * VEC, (int64_t)kSuper * a.n_wg), 6144);
-  const int min_chunks = params().fused_chunks;
-  int64_t C = min_chunks > 2 ? min_chunks : 2;
-  int64_t S = 0, last = 0;
-  for (;; ++C) {
-    // the multiple of U nearest to K / C, at least U when that leaves something for the last chunk
-    S = (a.K + C * U / 2) / (C * U) * U;
-    if (S < U && (C - 1) * U < a.K) S = U;
-    if (S == 0 || (C - 1) * S >= a.K) {  // K too small for aligned chunks: equal parts in whole positions
-      S = (((int64_t)a.K + C - 1) / C + VEC - 1) / VEC * VEC;
-      if ((C - 1) * S >= a.K) S = ((int64_t)a.K / C) / VEC * VEC;
-    }
-    last = a.K - (C - 1) * S;
-    if (S <= cap && last <= cap) break;
-  }
-  a.C = (int)C;
-  a.S = (int)S;
-  a.hcap = (int)((std::max(S, last) + VEC - 1) / VEC * VEC);
+  plan_chunks(a.K, a.d, a.n_wg, swiglu ? 2 : 1, depth, VEC, ni, nwc, cap, &a.C, &a.S, &a.hcap);
   a.rmax = (a.d + a.n_wg - 1) / a.n_wg;
   a.spin_limit = 1 << 16;
   const size_t lds = ((size_t)lds_red_floats(nwc, swiglu ? 2 : 1) + (size_t)lds_yred_floats(nwc, a.rmax) +
