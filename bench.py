@@ -1,18 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of the CoreInfer hot path on one MI355X.
 
-One "step" is one pass of the whole hot path over one batch of synthetic input
-(the OPT-6.7B-shaped stack by default): for every FFN layer the dense prefill
-FFN, the core-neuron selection and the weight compaction, then every decode
-token through every layer's sparse FFN.  Inputs are resident in HBM before the
-timed region.  Prints ONE JSON line (see README / DESIGN for the fields).
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+for every FFN layer the dense prefill FFN, the core-neuron selection and the
+weight compaction, then every decode token through every layer's sparse FFN.
+Inputs are resident in HBM before the timed region.
 
-    python bench.py --gpus 1 --steps 3 --warmup 1 [--workload NAME]
+A run with no --workload times every workload of the build -- the Llama-2-13B
+shape at each of its four keep fractions, the OPT-6.7B and Llama-2-7B shapes
+and the OPT-66B shape with eight sentences -- and prints ONE JSON line: its
+top-level fields are the Llama-2-13B shape at its first keep fraction (timed
+with --steps / --warmup), `workloads` carries the same fields for the others
+(at fewer steps, stated in each record).
+
+    python bench.py --gpus 1 --steps 20 --warmup 5
+    python bench.py --workload opt6.7b_relu_f16 [--beta 0.4] [--layers 8] ...
 """
 
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -21,6 +29,11 @@ import time
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
 ROOT = os.path.dirname(os.path.abspath(__file__))
+TOP_WORKLOAD = "llama2_13b_swiglu_bf16"
+# the other workloads of a default run, with the (steps, warmup) each is timed at
+OTHER_WORKLOADS = (("opt6.7b_relu_f16", None, 3, 1), ("llama2_7b_swiglu_bf16", None, 3, 1),
+                   (TOP_WORKLOAD, 0.3, 2, 1), (TOP_WORKLOAD, 0.4, 2, 1), (TOP_WORKLOAD, 0.6, 2, 1),
+                   ("opt66b_relu_f16_8sent", None, 2, 1))
 
 
 def parse_args():
@@ -28,78 +41,70 @@ def parse_args():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=3)
     p.add_argument("--warmup", type=int, default=1)
-    p.add_argument("--workload", default="opt6.7b_relu_f16")
+    p.add_argument("--workload", default=None, help="time this workload only (default: all of them)")
     p.add_argument("--beta", type=float, default=None, help="sentence keep fraction (default: the workload's first)")
     p.add_argument("--decode-tokens", type=int, default=None, help="override (shorter runs while profiling)")
     p.add_argument("--layers", type=int, default=None, help="override the stack depth (profiling only)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="launch decode kernels directly instead of a HIP graph")
     p.add_argument("--kernel-reps", type=int, default=20, help="replays of the kernel-only timing graph")
+    p.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time of the top-level cpu_baseline sample")
     return p.parse_args()
 
 
-def read_traffic_note(workload: str, algorithmic_bytes: int):
-    """HBM bytes per launch of the dominant kernel measured with rocprofv3
-    --pmc (FETCH_SIZE / WRITE_SIZE), if a summary has been committed for this
-    workload at the same launch size (same keep fraction)."""
-    path = os.path.join(ROOT, "profiles", f"pmc_ffn_decode_{workload}.txt")
-    traffic, alg = None, None
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = float(line.split(":", 1)[1])
-            if line.startswith("algorithmic_bytes_per_launch:"):
-                alg = int(line.split(":", 1)[1])
-    except OSError:
-        return None
-    if alg is None or abs(alg - algorithmic_bytes) > 0.001 * algorithmic_bytes:
-        return None
-    return traffic
+def read_traffic_note(workload: str, beta: float, algorithmic_bytes: int):
+    """HBM-side bytes per decode launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE),
+    if a summary has been committed for this workload at the same launch size."""
+    for name in (f"pmc_ffn_decode_{workload}_beta{beta:g}.txt", f"pmc_ffn_decode_{workload}.txt"):
+        traffic, alg = None, None
+        try:
+            for line in open(os.path.join(ROOT, "profiles", name)):
+                if line.startswith("traffic_bytes_per_launch:"):
+                    traffic = float(line.split(":", 1)[1])
+                if line.startswith("algorithmic_bytes_per_launch:"):
+                    alg = int(line.split(":", 1)[1])
+        except OSError:
+            continue
+        if alg is not None and abs(alg - algorithmic_bytes) <= 0.001 * algorithmic_bytes:
+            return traffic
+    return None
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+class Inputs:
+    """Weights and hidden states of one workload, resident on the GPU (shared by its keep fractions)."""
 
+    def __init__(self, cfg, dev):
+        import torch
+        from paper_2410_18311_amd import workloads as wl
+        L, B = cfg.L, cfg.sentences
+        self.cfg = cfg
+        self.weights = [wl.layer_weights(cfg, l, dev) for l in range(L)]
+        # the sentences of a batch share the layer's weights: their prompts go through the dense prefill
+        # FFN as one [B * M, d] matrix (one pass over the weights), selection then runs per sentence
+        self.X = [torch.cat([wl.prefill_hidden(cfg, l, dev, sentence=s) for s in range(B)], dim=0).contiguous()
+                  for l in range(L)]
+        # decode inputs: x_all[t] is [L, B, d], one fresh hidden state per layer, sentence and step
+        self.x_all = torch.stack([torch.stack([wl.decode_hidden(cfg, l, dev, sentence=s) for s in range(B)], dim=1)
+                                  for l in range(L)], dim=1).contiguous()          # [T, L, B, d]
+        torch.cuda.synchronize()
+
+
+def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_seconds: float) -> dict:
     import numpy as np
     import torch
-
-    from paper_2410_18311_amd import build as _build
-    if not os.path.exists(_build.LIB_PATH):
-        _build.build_library()
     from paper_2410_18311_amd import coreinfer as ci
-    from paper_2410_18311_amd import workloads as wl
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    cfg = wl.WORKLOADS[args.workload]
-    if args.layers:
-        cfg = cfg.scaled(L=args.layers)
-    if args.decode_tokens:
-        cfg = cfg.scaled(decode_tokens=args.decode_tokens)
-    beta = args.beta if args.beta is not None else cfg.betas[0]
+    cfg = inp.cfg
+    dev = inp.x_all.device
+    weights, X, x_all = inp.weights, inp.X, inp.x_all
     L, M, d, N, T, B = cfg.L, cfg.M, cfg.d, cfg.N, cfg.decode_tokens, cfg.sentences
     e = 4 if cfg.dtype == "f32" else 2
     K = ci.keep_count(beta, N)
     gathered = B > 1                      # several sentences: rows gathered from the resident weights
     dtype = cfg.torch_dtype
+    n_mat = cfg.n_mat
 
-    # ------------------------------------------------------------------ inputs (untimed)
-    weights = [wl.layer_weights(cfg, l, dev) for l in range(L)]
-    # the sentences of a batch share the layer's weights: their prompts go through the dense prefill
-    # FFN as one [B * M, d] matrix (one pass over the weights), selection then runs per sentence
-    X = [torch.cat([wl.prefill_hidden(cfg, l, dev, sentence=s) for s in range(B)], dim=0).contiguous()
-         for l in range(L)]
-    # decode inputs: x_all[t] is [L, B, d], one fresh hidden state per layer, sentence and step
-    x_all = torch.stack([torch.stack([wl.decode_hidden(cfg, l, dev, sentence=s) for s in range(B)], dim=1)
-                         for l in range(L)], dim=1).contiguous()          # [T, L, B, d]
+    # ------------------------------------------------------------------ buffers (untimed)
     x_cur = torch.empty((L, B, d), dtype=dtype, device=dev)
     y_out = torch.empty((L, B, d), dtype=dtype, device=dev)
     A_buf = torch.empty((B * M, N), dtype=torch.float32, device=dev)
@@ -107,29 +112,30 @@ def main():
     dense_ws = torch.empty(ci.ffn_dense_workspace_size(B * M, d, N, dtype), dtype=torch.uint8, device=dev)
     sel_ws = torch.empty(ci.select_workspace_size(M, N), dtype=torch.uint8, device=dev)
     counts = torch.empty(N, dtype=torch.int32, device=dev)
-    counts_all = torch.empty((L, N), dtype=torch.int32, device=dev) if (B == 1 and len(cfg.betas) > 1) else None
     core_idx = torch.empty((L, B, K), dtype=torch.int32, device=dev)
-    dec_ws = torch.empty(ci.ffn_decode_workspace_size(B, K, d), dtype=torch.uint8, device=dev)
+    # zeroed once: the single-launch decode exchanges hidden values through tagged words in it
+    dec_ws = ci.decode_workspace(B, K, d, dev)
     if gathered:
         cbuf = None
         descs = [ci.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], core_idx=core_idx[l])
                  for l, w in enumerate(weights)]
     else:
-        cbuf = [{"w_up_c": torch.empty((K, d), dtype=dtype, device=dev),
-                 "w_gate_c": torch.empty((K, d), dtype=dtype, device=dev) if cfg.act == "swiglu" else None,
-                 "b_up_c": torch.empty((K,), dtype=dtype, device=dev) if cfg.b_up is not None else None,
-                 "w_down_c": torch.empty((K, d), dtype=dtype, device=dev)} for _ in range(L)]
-        descs = [ci.make_weights(c["w_up_c"], c["w_gate_c"], c["b_up_c"], c["w_down_c"], w["b_down"])
-                 for c, w in zip(cbuf, weights)]
+        # compact buffers with the down matrix kept output-major: the layout the single-launch decode reads
+        cbuf = [ci.compact_buffers(K, d, dtype, dev, cfg.act == "swiglu", cfg.b_up is not None, "out_major")
+                for _ in range(L)]
+        descs = [ci.make_compact_weights(c, w["b_down"]) for c, w in zip(cbuf, weights)]
     torch.cuda.synchronize()
 
-    def prefill_layer(l):
+    def dense_layer(l):
         w = weights[l]
         ci.ffn_dense(X[l], w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], cfg.down_layout,
                      cfg.act, want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
+
+    def prefill_layer(l):
+        w = weights[l]
+        dense_layer(l)
         for s in range(B):
-            ci.select(A_buf[s * M:(s + 1) * M], cfg.alpha, beta, core_idx=core_idx[l, s],
-                      counts=counts if counts_all is None else counts_all[l], ws=sel_ws)
+            ci.select(A_buf[s * M:(s + 1) * M], cfg.alpha, beta, core_idx=core_idx[l, s], counts=counts, ws=sel_ws)
         if not gathered:
             ci.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act,
                        core_idx[l, 0], out=cbuf[l])
@@ -170,20 +176,21 @@ def main():
         if marks is not None:
             marks[2].record()
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    marks = [[ev(), ev(), ev()] for _ in range(args.steps)]
+    marks = [[ev(), ev(), ev()] for _ in range(steps)]
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(marks[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    prefill_ms = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
-    decode_ms = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
+    ms_per_step = wall * 1e3 / steps
+    prefill_ms = sum(m[0].elapsed_time(m[1]) for m in marks) / steps
+    decode_ms = sum(m[1].elapsed_time(m[2]) for m in marks) / steps
     decode_tokens_per_step = T * B
     tokens_per_s = decode_tokens_per_step / (decode_ms * 1e-3)
+    decode_status = 0 if gathered else ci.ffn_decode_status(dec_ws)
 
     # ---------------------------------------------- per-stage latencies (untimed extra pass)
     def timed(fn, reps=1):
@@ -207,11 +214,7 @@ def main():
         torch.cuda.synchronize()
         return timed(g.replay, reps)
 
-    w0 = weights[0]
-    dense_ms = timed(lambda: [ci.ffn_dense(X[l], weights[l]["w_up"], weights[l]["w_gate"], weights[l]["b_up"],
-                                           weights[l]["w_down"], weights[l]["b_down"], cfg.down_layout, cfg.act,
-                                           want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
-                              for l in range(L)]) / L   # per layer, all B sentences together
+    dense_ms = timed(lambda: [dense_layer(l) for l in range(L)]) / L   # per layer, all B sentences together
     scratch_idx = torch.empty(K, dtype=torch.int32, device=dev)   # keeps the real core sets intact
     select_ms = timed_graph(lambda: [ci.select(A_buf[:M], cfg.alpha, beta, core_idx=scratch_idx, counts=counts,
                                                ws=sel_ws) for l in range(L)]) / L
@@ -220,10 +223,9 @@ def main():
     hidden_prefill = None
     if cfg.dtype != "f32":
         H_buf = torch.empty((B * M, N), dtype=dtype, device=dev)
-        hws = dense_ws   # large enough: it also holds the split partial products of Y
         run_h = lambda: [ci.ffn_dense_hidden(X[l], weights[l]["w_up"], weights[l]["w_gate"], weights[l]["b_up"],
                                              weights[l]["w_down"], weights[l]["b_down"], cfg.down_layout, cfg.act,
-                                             Y=Y_buf, H=H_buf, ws=hws) for l in range(L)]
+                                             Y=Y_buf, H=H_buf, ws=dense_ws) for l in range(L)]
         run_h()
         dense_h_ms = timed(run_h) / L
         idx_h = torch.empty(K, dtype=torch.int32, device=dev)
@@ -245,6 +247,7 @@ def main():
     # dense decode baseline (all N neurons), one token through every layer
     Yd = torch.empty((B, d), dtype=dtype, device=dev)
     dws = torch.empty(ci.ffn_dense_workspace_size(1, d, N, dtype), dtype=torch.uint8, device=dev)
+
     def dense_decode():
         for l in range(L):
             w = weights[l]
@@ -253,54 +256,6 @@ def main():
                              cfg.down_layout, cfg.act, want_y=True, want_a=False, Y=Yd[s:s + 1], ws=dws)
     dense_decode()
     dense_decode_ms = timed(dense_decode, reps=3)
-
-    # ------------- keep-fraction sweep: one prefill and one count set, Def. 2 + deployment + decode per beta
-    sweep = None
-    if counts_all is not None and args.beta is None:
-        sweep = []
-        cs_ws = torch.empty(256, dtype=torch.uint8, device=dev)
-        n_tok = max(1, min(T, 64))
-        for b2 in cfg.betas[1:]:
-            K2 = ci.keep_count(b2, N)
-            idx2 = torch.empty((L, K2), dtype=torch.int32, device=dev)
-            bufs2 = [{"w_up_c": torch.empty((K2, d), dtype=dtype, device=dev),
-                      "w_gate_c": torch.empty((K2, d), dtype=dtype, device=dev) if cfg.act == "swiglu" else None,
-                      "b_up_c": torch.empty((K2,), dtype=dtype, device=dev) if cfg.b_up is not None else None,
-                      "w_down_c": torch.empty((K2, d), dtype=dtype, device=dev)} for _ in range(L)]
-
-            def redeploy():
-                for l in range(L):
-                    w = weights[l]
-                    ci.count_select(counts_all[l], M, b2, core_idx=idx2[l], ws=cs_ws)
-                    ci.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act, idx2[l],
-                               out=bufs2[l])
-            redeploy()
-            redeploy_ms = timed(redeploy) / L
-            descs2 = [ci.make_weights(c["w_up_c"], c["w_gate_c"], c["b_up_c"], c["w_down_c"], w["b_down"])
-                      for c, w in zip(bufs2, weights)]
-            ws2 = torch.empty(ci.ffn_decode_workspace_size(1, K2, d), dtype=torch.uint8, device=dev)
-
-            def layers2():
-                for l in range(L):
-                    ci.ffn_decode(x_cur[l], descs2[l], cfg.act, y=y_out[l], ws=ws2)
-            layers2()
-            torch.cuda.synchronize()
-            g2 = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g2):
-                layers2()
-            torch.cuda.synchronize()
-
-            def tokens2():
-                for t in range(n_tok):
-                    x_cur.copy_(x_all[t])
-                    g2.replay()
-            tokens2()
-            tok_ms = timed(tokens2) / n_tok
-            bytes2 = cfg.n_mat * K2 * d * e + (K2 * e if cfg.b_up is not None else 0) + 2 * d * e
-            sweep.append({"beta": b2, "core_neurons": K2, "tokens_per_s": 1.0 / (tok_ms * 1e-3),
-                          "decode_hbm_gbps_whole_phase": bytes2 * L / (tok_ms * 1e-3) / 1e9,
-                          "count_select_plus_compact_us_per_layer": redeploy_ms * 1e3, "decode_tokens_timed": n_tok})
-            del g2, bufs2, descs2, idx2, ws2
 
     # --------------------- several sentences: the same decode through the union of their core sets
     # (a different algorithm from the gathered decode that `value` reports: every union row is read
@@ -333,36 +288,51 @@ def main():
         union_ms = timed(ugraph.replay, reps=n_rep)
         del ugraph
         rows0 = int(unions[0][2].item())
-        union_bytes = rows0 * d * e * cfg.n_mat
+        union_bytes = rows0 * d * e * n_mat
         union = {"tokens_per_s": B / (union_ms * 1e-3), "us_per_layer_step": union_ms * 1e3 / L,
                  "union_rows_layer0": rows0, "algorithmic_bytes_per_layer_step": union_bytes,
                  "gbps": union_bytes * L / (union_ms * 1e-3) / 1e9,
+                 "frac_of_hbm_peak": union_bytes * L / (union_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                  "union_build_us_per_layer": ubuild_ms * 1e3,
                  "max_abs_diff_vs_gathered_over_rms": union_vs_gathered,
                  "note": "each row of the union of the sentences' core sets is read once; a different "
                          "algorithm from the gathered decode, same result per sentence"}
+        del unions, resident, u_ws
 
-    # ------------------------------- dominant kernel alone: HIP events around a graph of its launches
-    ci.set_param("decode_skip_reduce", 1)
-    try:
+    # ------------- everything coreinfer_ffn_decode launches, alone: HIP events on the launch stream
+    # around a graph of the L dependent calls of one token (no input copies in between)
+    decode_token_layers()
+    torch.cuda.synchronize()
+    kgraph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(kgraph):
         decode_token_layers()
-        torch.cuda.synchronize()
-        kgraph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(kgraph):
-            decode_token_layers()
-        torch.cuda.synchronize()
-        kgraph.replay()
-        kernel_ms = timed(kgraph.replay, reps=args.kernel_reps) / L
-        del kgraph
-    finally:
-        ci.set_param("decode_skip_reduce", 0)
-    n_mat = cfg.n_mat
+    torch.cuda.synchronize()
+    kgraph.replay()
+    kernel_ms = timed(kgraph.replay, reps=args.kernel_reps) / L
+    del kgraph
     bytes_per_launch = B * (n_mat * K * d * e + (K * e if cfg.b_up is not None else 0) + 2 * d * e)
     if gathered:
         bytes_per_launch += B * K * 4
-    achieved_gbps = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
+    traffic = read_traffic_note(cfg.name, beta, bytes_per_launch)
     e2e_gbps = bytes_per_launch * L * T / (decode_ms * 1e-3) / 1e9
-    traffic = read_traffic_note(cfg.name, bytes_per_launch)
+    if gathered:
+        # the sentences' core sets overlap and the rows shared between them are served by the caches:
+        # algorithmic bytes over time would exceed what memory delivered, so the counter bytes are used
+        basis = traffic if traffic is not None else bytes_per_launch
+        achieved_gbps = basis / (kernel_ms * 1e-3) / 1e9
+        roof_note = ("achieved = bytes that missed the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy of "
+                     "known size: requests the L2 passed on, served by the memory-side cache or HBM) / time; "
+                     "not a bandwidth claim for HBM alone" if traffic is not None else
+                     "no committed counter summary for this launch size: algorithmic bytes / time, which counts "
+                     "rows shared between sentences once per sentence; not a bandwidth claim")
+        kernels = "ffn_decode_kernel + decode_reduce_kernel (gathered rows of resident weights)"
+    else:
+        achieved_gbps = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
+        roof_note = "achieved = algorithmic bytes of one layer-token / time of everything coreinfer_ffn_decode launches"
+        kernels = "ffn_decode_fused_kernel (one launch per layer-token)"
+    roofline = {"kernel": kernels, "bound": "hbm", "achieved": achieved_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved_gbps / HBM_PEAK_GBPS, "traffic": traffic, "bytes_per_launch": bytes_per_launch,
+                "us_per_launch": kernel_ms * 1e3, "note": roof_note}
 
     # ------------------------------------------------------------- CPU oracle baseline + parity
     cpu = None
@@ -375,90 +345,157 @@ def main():
         except Exception:
             threads = os.cpu_count() or 1
         f64 = lambda t: None if t is None else t.detach().cpu().to(torch.float64).numpy()
-        # fresh prefill of layer 0, sentence 0 on the GPU, its activations handed to the oracle
-        ci.ffn_dense(X[0], w0["w_up"], w0["w_gate"], w0["b_up"], w0["w_down"], w0["b_down"], cfg.down_layout,
-                     cfg.act, want_y=True, want_a=True, Y=Y_buf, A=A_buf, ws=dense_ws)
-        torch.cuda.synchronize()
-        A_host = A_buf[:M].cpu().numpy()
-        ts = time.perf_counter()
-        S_ref, _ = orc.select(A_host, cfg.alpha, beta)
-        select_cpu_ms = (time.perf_counter() - ts) * 1e3
-        sets_equal = bool(np.array_equal(S_ref, core_idx[0, 0].cpu().numpy().astype(np.int64)))
-        Wu, Wg = f64(w0["w_up"]), f64(w0["w_gate"])
-        Wd = f64(w0["w_down"])
-        if cfg.down_layout == "neuron_major":
-            Wd = Wd.T
-        bu, bd = f64(w0["b_up"]), f64(w0["b_down"])
-        # a bounded sample: decode tokens of layer 0 until about ten seconds of oracle time have gone
+        sample_layers = sorted({0, L // 2, L - 1})
+        sample_sentences = sorted({0, B - 1})
+        per_layer_budget = cpu_seconds / len(sample_layers)
         max_tok = min(64, T)
-        xs = x_all[:max_tok, 0, 0]
-        ts = time.perf_counter()
-        refs = []
-        while len(refs) < max_tok and (len(refs) < 6 or time.perf_counter() - ts < 10.0):
-            xi = f64(xs[len(refs)])
-            if cfg.act == "relu":
-                refs.append(orc.ffn_relu(xi, S_ref, Wu, bu, Wd, bd))
-            else:
-                refs.append(orc.ffn_swiglu(xi, S_ref, Wg, Wu, Wd, bd))
-        n_tok = len(refs)
-        per_layer_token = (time.perf_counter() - ts) / n_tok
-        cpu = {"value": 1.0 / (per_layer_token * L), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-               "sample": f"float64 numpy oracle, layer 0 only, {n_tok} decode tokens, scaled by L={L}; "
-                         f"oracle select of one layer took {select_cpu_ms:.0f} ms",
-               "select_ms_per_layer": select_cpu_ms}
+        sets_equal = True
         worst = 0.0
-        for i in range(n_tok):
-            x1 = xs[i].reshape(1, d).contiguous()
-            if gathered:
-                dsc = ci.make_weights(w0["w_up"], w0["w_gate"], w0["b_up"], w0["w_down"], w0["b_down"],
-                                      core_idx=core_idx[0, :1])
-            else:
-                dsc = descs[0]
-            y = ci.ffn_decode(x1, dsc, cfg.act)
+        oracle_s, oracle_tokens, select_cpu_ms = 0.0, 0, []
+        for l in sample_layers:
+            w = weights[l]
+            dense_layer(l)          # fresh prefill of this layer on the GPU, its activations handed to the oracle
             torch.cuda.synchronize()
-            ref = refs[i]
-            worst = max(worst, float(np.max(np.abs(f64(y[0]) - ref)) / np.sqrt(np.mean(ref ** 2))))
+            S_refs = {}
+            for s in sample_sentences:
+                A_host = A_buf[s * M:(s + 1) * M].cpu().numpy()
+                ts = time.perf_counter()
+                S_refs[s], _ = orc.select(A_host, cfg.alpha, beta)
+                select_cpu_ms.append((time.perf_counter() - ts) * 1e3)
+                sets_equal &= bool(np.array_equal(S_refs[s], core_idx[l, s].cpu().numpy().astype(np.int64)))
+            Wu, Wg = f64(w["w_up"]), f64(w["w_gate"])
+            Wd = f64(w["w_down"])
+            if cfg.down_layout == "neuron_major":
+                Wd = Wd.T
+            bu, bd = f64(w["b_up"]), f64(w["b_down"])
+            # a bounded sample: decode tokens of this layer until its share of the oracle time has gone
+            spent, n_l = 0.0, 0
+            while n_l < max_tok and (n_l < 2 or spent < per_layer_budget):
+                s = sample_sentences[n_l % len(sample_sentences)]
+                xt = x_all[n_l, l, s]
+                xi = f64(xt)
+                ts = time.perf_counter()
+                if cfg.act == "relu":
+                    ref = orc.ffn_relu(xi, S_refs[s], Wu, bu, Wd, bd)
+                else:
+                    ref = orc.ffn_swiglu(xi, S_refs[s], Wg, Wu, Wd, bd)
+                spent += time.perf_counter() - ts
+                if gathered:
+                    dsc = ci.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"],
+                                          core_idx=core_idx[l, s:s + 1])
+                    y = ci.ffn_decode(xt.reshape(1, d).contiguous(), dsc, cfg.act)
+                else:
+                    y = ci.ffn_decode(xt.reshape(1, d).contiguous(), descs[l], cfg.act, ws=dec_ws)
+                torch.cuda.synchronize()
+                worst = max(worst, float(np.max(np.abs(f64(y[0]) - ref)) / np.sqrt(np.mean(ref ** 2))))
+                n_l += 1
+            oracle_s += spent
+            oracle_tokens += n_l
+            del Wu, Wg, Wd
+        per_layer_token = oracle_s / oracle_tokens
+        cpu = {"value": 1.0 / (per_layer_token * L), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+               "sample": f"float64 numpy oracle, layers {sample_layers}, {oracle_tokens} layer-tokens in "
+                         f"{oracle_s:.1f} s, scaled by L={L}; oracle select of one layer and sentence took "
+                         f"{np.mean(select_cpu_ms):.0f} ms",
+               "select_ms_per_layer": float(np.mean(select_cpu_ms))}
         parity = {"core_set_bit_exact": sets_equal, "decode_max_abs_err_over_rms": worst,
-                  "tolerance": 1e-5 if cfg.dtype == "f32" else 2e-2}
+                  "tolerance": 1e-5 if cfg.dtype == "f32" else 2e-2, "layers": sample_layers,
+                  "sentences": sample_sentences, "layer_tokens_checked": oracle_tokens}
 
-    out = {
+    dense_flops = 2.0 * B * M * d * N * n_mat
+    return {
         "metric": "decode_sparse_ffn_tokens_per_s",
         "value": tokens_per_s,
         "unit": "tokens/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
         "dtype": cfg.dtype,
-        "data": "synthetic",
         "config": {"workload": cfg.name, "act": cfg.act, "d_model": d, "d_ff": N, "layers": L,
                    "prefill_tokens": M, "decode_tokens": T, "sentences": B, "alpha": cfg.alpha, "beta": beta,
-                   "core_neurons": K, "decode_mode": "gathered" if gathered else "compacted",
+                   "core_neurons": K, "decode_mode": "gathered" if gathered else "compacted, single launch",
                    "decode_launch": "direct" if args.no_graph else "hip_graph_per_token",
                    "value_definition": "decode tokens of a step / GPU time of the step's decode phase (HIP events)"},
         "step_breakdown_ms": {"prefill_select_compact": prefill_ms, "decode": decode_ms,
                               "tokens_per_s_whole_step": decode_tokens_per_step / (ms_per_step * 1e-3)},
         "decode_hbm_gbps_whole_phase": e2e_gbps,
         "decode_hbm_frac_whole_phase": e2e_gbps / HBM_PEAK_GBPS,
+        "decode_status_word": decode_status,
         "select_us_per_layer": select_ms * 1e3,
         "compact_us_per_layer": None if compact_ms is None else compact_ms * 1e3,
         "dense_prefill_ms_per_layer": dense_ms,
-        "dense_prefill_tflops": 2.0 * B * M * d * N * n_mat / (dense_ms * 1e-3) / 1e12,
-        "dense_prefill_mfma_frac": 2.0 * B * M * d * N * n_mat / (dense_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype],
+        "dense_prefill_tflops": dense_flops / (dense_ms * 1e-3) / 1e12,
+        "dense_prefill_mfma_frac": dense_flops / (dense_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype],
         "dense_decode_tokens_per_s": B / (dense_decode_ms * 1e-3),
-        "roofline": {"kernel": "ffn_decode_kernel", "bound": "hbm", "achieved": achieved_gbps,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved_gbps / HBM_PEAK_GBPS,
-                     "traffic": traffic, "bytes_per_launch": bytes_per_launch,
-                     "us_per_launch": kernel_ms * 1e3},
+        "roofline": roofline,
         "hidden_ranked_prefill": hidden_prefill,
-        "beta_sweep": sweep,
         "union_batched_decode": union,
         "cpu_baseline": cpu,
         "parity": parity,
     }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2410_18311_amd import build as _build
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build_library()
+    from paper_2410_18311_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def config_of(name):
+        cfg = wl.WORKLOADS[name]
+        if args.layers:
+            cfg = cfg.scaled(L=args.layers)
+        if args.decode_tokens:
+            cfg = cfg.scaled(decode_tokens=args.decode_tokens)
+        return cfg
+
+    def note(msg):
+        print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+    if args.workload is not None:
+        cfg = config_of(args.workload)
+        beta = args.beta if args.beta is not None else cfg.betas[0]
+        top = run_workload(Inputs(cfg, dev), beta, args.steps, args.warmup, args, args.cpu_seconds)
+        others = None
+    else:
+        t_start = time.perf_counter()
+        cfg = config_of(TOP_WORKLOAD)
+        inputs = Inputs(cfg, dev)
+        note(f"{cfg.name} beta {cfg.betas[0]}: {args.steps} steps")
+        top = run_workload(inputs, cfg.betas[0], args.steps, args.warmup, args, args.cpu_seconds)
+        others = []
+        for name, beta, steps, warmup in OTHER_WORKLOADS:
+            cfg = config_of(name)
+            if inputs.cfg.name != cfg.name:
+                del inputs
+                gc.collect()
+                torch.cuda.empty_cache()
+                inputs = Inputs(cfg, dev)
+            beta = cfg.betas[0] if beta is None else beta
+            note(f"{cfg.name} beta {beta}: {steps} steps ({time.perf_counter() - t_start:.0f} s so far)")
+            others.append(run_workload(inputs, beta, steps, warmup, args, min(args.cpu_seconds, 4.0)))
+            gc.collect()
+            torch.cuda.empty_cache()
+        note(f"done in {time.perf_counter() - t_start:.0f} s")
+
+    out = dict(top)
+    out.update({"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"})
+    if others is not None:
+        out["workloads"] = others
     print(json.dumps(out))
 
 

@@ -350,11 +350,20 @@ def assign_centroid(feature, centroids):
     for g in range(C.shape[0]):
         diff = f - C[g]
         d2[g] = float(np.dot(diff, diff))
+    return nearest_group(d2), d2
+
+
+def nearest_group(d2) -> int:
+    """The decision of the K-Means assignment step (App. A.2.3) on given squared
+    distances: the smallest one, the lower group index among equal ones."""
+    d2 = np.asarray(d2, dtype=np.float64)
+    if d2.ndim != 1 or d2.shape[0] < 1:
+        raise ValueError("squared distances [G] with G >= 1")
     best = 0
-    for g in range(1, C.shape[0]):
+    for g in range(1, d2.shape[0]):
         if d2[g] < d2[best]:
             best = g
-    return best, d2
+    return best
 
 
 def core_similarity(S1, S2) -> float:

@@ -14,6 +14,26 @@ def f64(t):
     return t.detach().to("cpu").to(torch.float64).numpy()
 
 
+def score_bound(dtype, act, A_ref, X=None, w=None):
+    """Largest absolute error allowed on the fp32 prefill scores.  fp32 layers: the fp32 bar,
+    max(1e-5, 8 sqrt(d) 2^-24) (the second term is the rounding of a length-d fp32 sum, which
+    passes 1e-5 beyond d = 440), times the scale of what is rounded -- the RMS of the scores for
+    ReLU; for SwiGLU, whose score is the product of two rounded dots (its error grows with the
+    dots, and the RMS of a SiLU-gated product is several times smaller than theirs),
+    RMS(gate dot) * RMS(up dot).  16-bit inputs: 1e-4 of the scores' RMS."""
+    rms = float(np.sqrt(np.mean(np.asarray(A_ref, dtype=np.float64) ** 2)))
+    if dtype != torch.float32:
+        return 1e-4 * rms
+    d = X.shape[-1]
+    bar = max(1e-5, 8.0 * np.sqrt(d) * 2.0 ** -24)
+    if act == "swiglu":
+        Xd = f64(X)
+        g = Xd @ f64(w["w_gate"]).T
+        u = Xd @ f64(w["w_up"]).T
+        return bar * max(rms, float(np.sqrt(np.mean(g ** 2)) * np.sqrt(np.mean(u ** 2))))
+    return bar * rms
+
+
 def assert_close_rms(got, want, dtype, what=""):
     got = f64(got) if isinstance(got, torch.Tensor) else np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)

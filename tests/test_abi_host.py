@@ -359,6 +359,6 @@ def test_bench_line_fields_are_built_from_the_documented_pieces():
     spec = importlib.util.spec_from_file_location("bench_module", os.path.join(root, "bench.py"))
     bench = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(bench)
-    assert bench.read_traffic_note("opt6.7b_relu_f16", 107410228) is not None
-    assert bench.read_traffic_note("opt6.7b_relu_f16", 2 * 107410228) is None
-    assert bench.read_traffic_note("no_such_workload", 1) is None
+    assert bench.read_traffic_note("opt6.7b_relu_f16", 0.4, 107410228) is not None
+    assert bench.read_traffic_note("opt6.7b_relu_f16", 0.4, 2 * 107410228) is None
+    assert bench.read_traffic_note("no_such_workload", 0.4, 1) is None
