@@ -46,6 +46,8 @@ def parse_args():
     p.add_argument("--decode-tokens", type=int, default=None, help="override (shorter runs while profiling)")
     p.add_argument("--layers", type=int, default=None, help="override the stack depth (profiling only)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--down-layout", choices=["auto", "out_major", "neuron_major"], default="auto",
+                   help="layout of the compact down matrix (auto: the library's preference for the shape)")
     p.add_argument("--no-graph", action="store_true", help="launch decode kernels directly instead of a HIP graph")
     p.add_argument("--kernel-reps", type=int, default=20, help="replays of the kernel-only timing graph")
     p.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time of the top-level cpu_baseline sample")
@@ -120,8 +122,11 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
         descs = [ci.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], core_idx=core_idx[l])
                  for l, w in enumerate(weights)]
     else:
-        # compact buffers with the down matrix kept output-major: the layout the single-launch decode reads
-        cbuf = [ci.compact_buffers(K, d, dtype, dev, cfg.act == "swiglu", cfg.b_up is not None, "out_major")
+        # compact buffers in the layout the library prefers for this shape: output-major down matrix
+        # (single-launch decode) for large layers, neuron-major (two launches) for small ones
+        down_c_layout = (ci.compact_preferred_layout(K, d, dtype, cfg.act) if args.down_layout == "auto"
+                         else args.down_layout)
+        cbuf = [ci.compact_buffers(K, d, dtype, dev, cfg.act == "swiglu", cfg.b_up is not None, down_c_layout)
                 for _ in range(L)]
         descs = [ci.make_compact_weights(c, w["b_down"]) for c, w in zip(cbuf, weights)]
     torch.cuda.synchronize()
@@ -190,7 +195,7 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
     decode_ms = sum(m[1].elapsed_time(m[2]) for m in marks) / steps
     decode_tokens_per_step = T * B
     tokens_per_s = decode_tokens_per_step / (decode_ms * 1e-3)
-    decode_status = 0 if gathered else ci.ffn_decode_status(dec_ws)
+    decode_status = ci.ffn_decode_status(dec_ws) if (not gathered and down_c_layout == "out_major") else 0
 
     # ---------------------------------------------- per-stage latencies (untimed extra pass)
     def timed(fn, reps=1):
@@ -329,7 +334,8 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
     else:
         achieved_gbps = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
         roof_note = "achieved = algorithmic bytes of one layer-token / time of everything coreinfer_ffn_decode launches"
-        kernels = "ffn_decode_fused_kernel (one launch per layer-token)"
+        kernels = ("ffn_decode_fused_kernel (one launch per layer-token)" if down_c_layout == "out_major" else
+                   "ffn_decode_kernel + decode_reduce_kernel (two launches per layer-token)")
     roofline = {"kernel": kernels, "bound": "hbm", "achieved": achieved_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": achieved_gbps / HBM_PEAK_GBPS, "traffic": traffic, "bytes_per_launch": bytes_per_launch,
                 "us_per_launch": kernel_ms * 1e3, "note": roof_note}
@@ -413,7 +419,7 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
         "dtype": cfg.dtype,
         "config": {"workload": cfg.name, "act": cfg.act, "d_model": d, "d_ff": N, "layers": L,
                    "prefill_tokens": M, "decode_tokens": T, "sentences": B, "alpha": cfg.alpha, "beta": beta,
-                   "core_neurons": K, "decode_mode": "gathered" if gathered else "compacted, single launch",
+                   "core_neurons": K, "decode_mode": "gathered" if gathered else f"compacted, w_down_c {down_c_layout}",
                    "decode_launch": "direct" if args.no_graph else "hip_graph_per_token",
                    "value_definition": "decode tokens of a step / GPU time of the step's decode phase (HIP events)"},
         "step_breakdown_ms": {"prefill_select_compact": prefill_ms, "decode": decode_ms,

@@ -221,9 +221,19 @@ int coreinfer_assign_centroid(const float* act, int64_t M, int64_t N, int64_t ld
  * violates this yields an all-zero row / column and sets *status (device
  * int32, may be NULL; the caller zeroes it beforehand) to 1 -- it never causes
  * an out-of-bounds access.  Output buffers are caller-allocated and must not
- * overlap the inputs.
+ * overlap the inputs.  With CI_DOWN_OUT_MAJOR b_up_c holds ld elements (the
+ * entries K .. ld-1 are left as they are).
+ *
+ * coreinfer_compact_preferred_layout names, in *down_c_layout (host), the
+ * layout of w_down_c that decodes faster for K core neurons of a layer of width
+ * d: both are correct for every shape; small layers decode faster through the
+ * neuron-major path (two launches), large ones through the output-major path
+ * (one launch), and where the single-launch path does not apply
+ * (coreinfer_ffn_decode would return CI_ERR_UNSUPPORTED) the answer is
+ * CI_DOWN_NEURON_MAJOR.
  */
 int coreinfer_compact_down_ld(int64_t K, int dtype, int64_t* ld);
+int coreinfer_compact_preferred_layout(int64_t K, int64_t d, int dtype, int act, int* down_c_layout);
 int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up,
                       const void* w_down, int down_layout, int dtype, int act,
                       int64_t d, int64_t N, const int32_t* core_idx, int64_t K,

@@ -63,6 +63,7 @@ _SIGNATURES = {
     "coreinfer_assign_centroid_workspace_size": (_int, [_i64, ctypes.POINTER(_sz)]),
     "coreinfer_assign_centroid": (_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_compact_down_ld": (_int, [_i64, _int, ctypes.POINTER(_i64)]),
+    "coreinfer_compact_preferred_layout": (_int, [_i64, _i64, _int, _int, ctypes.POINTER(_int)]),
     "coreinfer_compact": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _i64, _i64, _vp, _i64,
                                  _vp, _vp, _vp, _vp, _int, _vp, _vp]),
     "coreinfer_compact_update_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
@@ -94,6 +95,8 @@ raw = _lib  # the bare C entry points, for tests of the error paths
 # development hook (csrc/coreinfer_dev.h): launch-shape parameters for sweeps, not part of the interface
 _lib.coreinfer_dev_set_param.restype = _int
 _lib.coreinfer_dev_set_param.argtypes = [ctypes.c_char_p, _int]
+_lib.coreinfer_dev_fused_plan.restype = _int
+_lib.coreinfer_dev_fused_plan.argtypes = [_i64, _i64, _int, _int, ctypes.POINTER(_int)]
 
 
 class CoreInferError(RuntimeError):
@@ -129,6 +132,13 @@ def version() -> int:
 
 def dev_set_param(name: str, value: int) -> None:
     _check(_lib.coreinfer_dev_set_param(name.encode(), int(value)), "coreinfer_dev_set_param")
+
+
+def dev_fused_plan(K: int, d: int, dtype: torch.dtype, act: str) -> dict:
+    """Launch shape of the single-launch decode under the current development settings."""
+    out = (_int * 5)()
+    _check(_lib.coreinfer_dev_fused_plan(K, d, DTYPE_CODE[dtype], ACT_CODE[act], out), "coreinfer_dev_fused_plan")
+    return dict(zip(("chunks", "chunk_neurons", "compute_waves", "loads_per_row", "workgroups"), list(out)))
 
 
 def keep_count(frac: float, n: int) -> int:
@@ -267,6 +277,13 @@ def compact_down_ld(K: int, dtype: torch.dtype) -> int:
     ld = _i64(0)
     _check(_lib.coreinfer_compact_down_ld(int(K), DTYPE_CODE[dtype], ctypes.byref(ld)), "coreinfer_compact_down_ld")
     return ld.value
+
+
+def compact_preferred_layout(K: int, d: int, dtype: torch.dtype, act: str) -> str:
+    out = _int(0)
+    _check(_lib.coreinfer_compact_preferred_layout(int(K), int(d), DTYPE_CODE[dtype], ACT_CODE[act], ctypes.byref(out)),
+           "coreinfer_compact_preferred_layout")
+    return "out_major" if out.value == CI_DOWN_OUT_MAJOR else "neuron_major"
 
 
 def compact_buffers(K: int, d: int, dtype: torch.dtype, device, gate: bool, bias: bool,

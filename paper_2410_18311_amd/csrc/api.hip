@@ -5,6 +5,8 @@
 
 #include <mutex>
 
+#include <algorithm>
+
 #include "common.hpp"
 #include "coreinfer_dev.h"
 
@@ -72,6 +74,12 @@ const char* coreinfer_strerror(int status) {
 
 int coreinfer_version(void) { return 2; }
 
+int coreinfer_dev_fused_plan(int64_t K, int64_t d, int dtype, int act, int* out) {
+  if (!out || K < 1 || d < 1 || d > (1 << 15)) return CI_ERR_INVALID_ARG;
+  if (act != CI_ACT_RELU && act != CI_ACT_SWIGLU) return CI_ERR_INVALID_ARG;
+  return fused_decode_plan(K, d, dtype, act, out);
+}
+
 // Development hook (coreinfer_dev.h), not part of the installed interface: launch-shape
 // parameters for tuning sweeps.  Returns CI_ERR_INVALID_ARG for unknown names.
 int coreinfer_dev_set_param(const char* name, int value) {
@@ -86,6 +94,7 @@ int coreinfer_dev_set_param(const char* name, int value) {
   else if (!strcmp(name, "fused_depth") && (value == 4 || value == 8)) p.fused_depth = value;
   else if (!strcmp(name, "fused_threads") && value >= 0 && value <= 1024) p.fused_threads = value;
   else if (!strcmp(name, "fused_chunks") && value >= 2 && value <= 64) p.fused_chunks = value;
+  else if (!strcmp(name, "fused_chunk_size") && value >= 0 && value <= 6144) p.fused_chunk_size = value;
   else if (!strcmp(name, "fused_wgs") && value >= 0 && value <= 1024) p.fused_wgs = value;
   else if (!strcmp(name, "fused_guard_us10") && value >= 0 && value <= 1000) p.fused_guard_us10 = value;
   else if (!strcmp(name, "fused_chunk_cost10") && value >= 0 && value <= 1000) p.fused_chunk_cost10 = value;
@@ -272,6 +281,21 @@ int coreinfer_compact_down_ld(int64_t K, int dtype, int64_t* ld) {
   return CI_OK;
 }
 
+int coreinfer_compact_preferred_layout(int64_t K, int64_t d, int dtype, int act, int* down_c_layout) {
+  if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
+  if (!down_c_layout || K < 0 || K > CI_MAX_NEURONS || d < 1 || d > CI_MAX_DMODEL) return CI_ERR_INVALID_ARG;
+  *down_c_layout = CI_DOWN_NEURON_MAJOR;
+  if (K < 1 || d % vec_of(dtype) != 0) return CI_OK;
+  int plan[5];
+  if (fused_decode_plan(K, d, dtype, act, plan) != CI_OK) return CI_OK;
+  // Measured on MI355X (OPT-6.7B / Llama-2-7B / Llama-2-13B shapes): the two paths are within 2 % of
+  // each other; the single launch wins from about 120 MB of weights per token on, where its fixed
+  // cost (the exchange of the hidden values between the workgroups) is spread over more bytes.
+  const double bytes = (double)(act == CI_ACT_SWIGLU ? 3 : 2) * (double)K * (double)d * (double)elem_bytes(dtype);
+  if (bytes >= 120e6) *down_c_layout = CI_DOWN_OUT_MAJOR;
+  return CI_OK;
+}
+
 int coreinfer_compact(const void* w_up, const void* w_gate, const void* b_up, const void* w_down,
                       int down_layout, int dtype, int act, int64_t d, int64_t N,
                       const int32_t* core_idx, int64_t K, void* w_up_c, void* w_gate_c,
@@ -333,7 +357,7 @@ int coreinfer_ffn_decode_workspace_size(int64_t B, int64_t K, int64_t d, size_t*
   const int64_t splits = K < kMaxSplits ? K : kMaxSplits;
   const size_t two = round256((size_t)B * (size_t)splits * (size_t)d * sizeof(float)) + 256;
   const size_t one = round256(fused_decode_ws_bytes(K));
-  *bytes = two > one ? two : one;
+  *bytes = std::max(two, one);
   return CI_OK;
 }
 

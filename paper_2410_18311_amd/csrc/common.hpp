@@ -137,12 +137,13 @@ struct Params {
   Knob fused_depth{4};     // single-launch decode: rows in flight per thread (4, 8 or 16)
   Knob fused_threads{0};   // 0 = derived from d
   Knob fused_chunks{2};    // least number of neuron chunks
+  Knob fused_chunk_size{0}; // 0 = chosen by the cost model, else neurons per chunk (used if it respects the limits)
   Knob fused_wgs{0};       // 0 = one workgroup per compute unit
   Knob fused_ablate{0};    // development builds only
   Knob fused_chunk_cost10{80};  // tenths of a ring slot that a chunk's two barriers are counted as
   Knob fused_window_slots{13};  // ring slots the exchange of a chunk needs between its publication and its use
   Knob fused_guard_us10{12}; // tenths of a microsecond after a phase's end at which its hidden values are collected
-  Knob fused_aux{0};       // ring loads: buffer loads with these cache-policy bits (0, 16), or global loads (-1 non-temporal, -2 plain)
+  Knob fused_aux{-1};       // ring loads: buffer loads with these cache-policy bits (0, 16), or global loads (-1 non-temporal, -2 plain)
 };
 Params& params();
 
@@ -203,6 +204,7 @@ int launch_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dty
 int launch_decode_reduce(const float* partial, const void* b_down, void* y, int n_wg, int d, int B,
                          int dtype, hipStream_t s);
 size_t fused_decode_ws_bytes(int64_t K);
+int fused_decode_plan(int64_t K, int64_t d, int dtype, int act, int* out);
 int launch_ffn_decode_fused(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act, void* y,
                             void* ws, hipStream_t s);
 int union_up_chunks(int64_t vecs);

@@ -10,9 +10,16 @@
  *   derive from d, else a multiple of 64 up to 1024), "decode_depth" (4, 8 or 16
  *   weight rows in flight per thread), "reduce_cq" (4, 8, 16 column quads per
  *   reduction workgroup), "decode_nt_store" (0/1): two-launch decode;
- *   "fused_depth" (4, 8, 16), "fused_threads" (0 or a multiple of 64 up to 1024),
- *   "fused_chunks" (2..64), "fused_wgs" (0 = one workgroup per compute unit, else
- *   fewer): single-launch decode;
+ *   "fused_depth" (4, 8), "fused_threads" (0 or a multiple of 64 up to 896),
+ *   "fused_chunks" (least number of neuron chunks, 2..64),
+ *   "fused_chunk_size" (0 = cost model, else neurons per chunk, a multiple of the
+ *   elements per 16 bytes; ignored where it breaks a limit), "fused_wgs" (0 = one
+ *   workgroup per compute unit, else fewer), "fused_chunk_cost10" and
+ *   "fused_window_slots" (weights of the chunk-size cost model, 0..1000),
+ *   "fused_guard_us10" (tenths of a microsecond between a chunk's publication
+ *   and its collection, 0..1000), "fused_aux" (cache policy of the weight
+ *   loads: -1 non-temporal, -2 plain, 0 / 16 buffer loads without / with device
+ *   scope), "fused_ablate" (timing builds only): single-launch decode;
  *   "select_wgs_per_cu" (1..8; 1 keeps the per-token kernel at one workgroup per
  *   compute unit also for prompts longer than the chip has compute units),
  *   "select_def2_single" (0/1: 1 runs Def. 2 in one workgroup even where the
@@ -31,11 +38,20 @@
 #ifndef COREINFER_DEV_H_
 #define COREINFER_DEV_H_
 
+#include <stdint.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
 
 int coreinfer_dev_set_param(const char* name, int value);
+
+/* The launch shape the single-launch decode would use for K core neurons of a
+ * layer with model width d under the current settings: out[0..4] = chunks,
+ * neurons per chunk, compute waves per workgroup, 16-byte loads per thread and
+ * row, workgroups.  Host arrays; CI_ERR_UNSUPPORTED where that path does not
+ * apply. */
+int coreinfer_dev_fused_plan(int64_t K, int64_t d, int dtype, int act, int* out);
 
 #ifdef __cplusplus
 }

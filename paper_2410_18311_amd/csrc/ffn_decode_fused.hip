@@ -602,8 +602,12 @@ void plan_chunks(int K, int d, int n_wg, int ndot, int depth, int vec, int ni, i
     }
     if (best < 0 || cost < best - 1e-9) { best = cost; best_S = S; best_C = C; }
   };
-  for (int64_t S = U; S <= cap; S += U) consider(S);
-  for (int64_t C = min_chunks; C <= min_chunks + 6; ++C) consider(round_up((K + C - 1) / C, vec));
+  const int forced = params().fused_chunk_size;
+  if (forced > 0) consider(forced);
+  if (best < 0)
+    for (int64_t S = U; S <= cap; S += U) consider(S);
+  if (forced <= 0 || best < 0)
+    for (int64_t C = min_chunks; C <= min_chunks + 6; ++C) consider(round_up((K + C - 1) / C, vec));
   if (best < 0) {
     // larger minimum number of chunks than the aligned sizes allow, or K below two positions
     for (int64_t C = min_chunks; C <= 4096 && best < 0; ++C) consider(round_up((K + C - 1) / C, vec));
@@ -635,8 +639,9 @@ int launch_depth(const FusedArgs& a, int nt, size_t lds, hipStream_t s) {
   return launch_aux<D, NI, SWIGLU, 4>(a, nt, lds, s);
 }
 
+// The launch shape of a call: loads per thread and row (ni), compute threads (ntc), chunks.
 template <class D>
-int launch_dtype(FusedArgs a, int act, hipStream_t s) {
+int plan_dtype(FusedArgs& a, int act, int* ni_out, int* ntc_out) {
   constexpr int VEC = D::VEC;
   const int vecs = a.d / VEC;
   // one 16-byte load per compute thread and row up to 896 threads (14 waves + the service waves),
@@ -655,15 +660,32 @@ int launch_dtype(FusedArgs a, int act, hipStream_t s) {
   // slots (see plan_chunks).
   const bool swiglu = act == CI_ACT_SWIGLU;
   const int depth = ni >= 2 ? 4 : (params().fused_depth == 8 ? 8 : 4);
-  const int64_t cap = std::min<int64_t>(std::min<int64_t>((int64_t)ntc * ni * VEC, (int64_t)kSuper * a.n_wg), 6144);
-  plan_chunks(a.K, a.d, a.n_wg, swiglu ? 2 : 1, depth, VEC, ni, nwc, cap, &a.C, &a.S, &a.hcap);
   a.rmax = (a.d + a.n_wg - 1) / a.n_wg;
+  // two chunk buffers of fp32 hidden values must fit into what the other arrays leave of 64 KB of LDS
+  const int64_t lds_left = 16384 - lds_red_floats(nwc, swiglu ? 2 : 1) - lds_yred_floats(nwc, a.rmax);
+  if (lds_left < 2 * VEC) return CI_ERR_UNSUPPORTED;
+  const int64_t cap = std::min<int64_t>(std::min<int64_t>(std::min<int64_t>((int64_t)ntc * ni * VEC, (int64_t)kSuper * a.n_wg),
+                                                          6144), lds_left / 2 / VEC * VEC);
+  plan_chunks(a.K, a.d, a.n_wg, swiglu ? 2 : 1, depth, VEC, ni, nwc, cap, &a.C, &a.S, &a.hcap);
   a.spin_limit = 1 << 16;
-  const size_t lds = ((size_t)lds_red_floats(nwc, swiglu ? 2 : 1) + (size_t)lds_yred_floats(nwc, a.rmax) +
-                      (size_t)2 * a.hcap) * sizeof(float);
   // the service waves start collecting a chunk this long after it was published here, by which time the
   // other workgroups have published too
   a.guard_ticks = params().fused_guard_us10 * 10;
+  *ni_out = ni;
+  *ntc_out = ntc;
+  return CI_OK;
+}
+
+template <class D>
+int launch_dtype(FusedArgs a, int act, hipStream_t s) {
+  int ni = 0, ntc = 0;
+  const int rc = plan_dtype<D>(a, act, &ni, &ntc);
+  if (rc != CI_OK) return rc;
+  const int nwc = ntc / 64;
+  const bool swiglu = act == CI_ACT_SWIGLU;
+  const size_t lds = ((size_t)lds_red_floats(nwc, swiglu ? 2 : 1) + (size_t)lds_yred_floats(nwc, a.rmax) +
+                      (size_t)2 * a.hcap) * sizeof(float);
+  if (lds > 64 * 1024) return CI_ERR_UNSUPPORTED;
   const int nt = ntc + 64 * kServiceWaves;
   switch (ni) {
     case 1: return swiglu ? launch_depth<D, 1, true>(a, nt, lds, s) : launch_depth<D, 1, false>(a, nt, lds, s);
@@ -672,16 +694,40 @@ int launch_dtype(FusedArgs a, int act, hipStream_t s) {
   }
 }
 
+int device_cus() {
+  DeviceInfo di;
+  return device_info(&di) == CI_OK ? di.cus : 256;
+}
+
 }  // namespace
 
 // Workspace of the single-launch decode: a 256-byte header and one 8-byte word per neuron.
 size_t fused_decode_ws_bytes(int64_t K) { return 256 + ((size_t)K + 16) * 8; }
 
+// Development aid: the launch shape the single-launch decode would use.  out[0..4] = chunks, neurons
+// per chunk, compute waves, loads per thread and row, workgroups.
+int fused_decode_plan(int64_t K, int64_t d, int dtype, int act, int* out) {
+  FusedArgs a = {};
+  a.K = (int)K;
+  a.d = (int)d;
+  const int cus = device_cus();
+  const int want_wgs = params().fused_wgs;
+  a.n_wg = want_wgs > 0 && want_wgs < cus ? want_wgs : cus;
+  int ni = 0, ntc = 0, rc;
+  switch (dtype) {
+    case CI_F32: rc = plan_dtype<F32>(a, act, &ni, &ntc); break;
+    case CI_F16: rc = plan_dtype<F16>(a, act, &ni, &ntc); break;
+    case CI_BF16: rc = plan_dtype<BF16>(a, act, &ni, &ntc); break;
+    default: return CI_ERR_BAD_DTYPE;
+  }
+  if (rc != CI_OK) return rc;
+  out[0] = a.C; out[1] = a.S; out[2] = ntc / 64; out[3] = ni; out[4] = a.n_wg;
+  return CI_OK;
+}
+
 int launch_ffn_decode_fused(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act, void* y,
                             void* ws, hipStream_t s) {
-  DeviceInfo di;
-  int cus = 256;
-  if (device_info(&di) == CI_OK) cus = di.cus;
+  const int cus = device_cus();
   FusedArgs a;
   a.w_up = w->w_up;
   a.w_gate = w->w_gate;

@@ -84,7 +84,7 @@ def main():
         layers.append((ci.make_weights(up, gate, bias, down, None, core_idx=idx), (up, gate, bias, down, idx)))
     x = mk(B, d) * 50
     y = torch.empty_like(x)
-    ws = torch.empty(ci.ffn_decode_workspace_size(B, K, d), dtype=torch.uint8, device=dev)
+    ws = ci.decode_workspace(B, K, d, dev)
     if args.what == "union":
         rows_total = 0
         for _ in range(args.reps):

@@ -1006,7 +1006,7 @@ def test_decode_graph_replays_match_eager(lib):
     desc = lib.make_weights(c["w_up_c"], None, c["b_up_c"], c["w_down_c"], w["b_down"])
     x = torch.randn(1, d, generator=torch.Generator().manual_seed(2)).half().to(DEV)
     y = torch.empty_like(x)
-    ws = torch.empty(lib.ffn_decode_workspace_size(1, K, d), dtype=torch.uint8, device=DEV)
+    ws = lib.decode_workspace(1, K, d, DEV)
     lib.ffn_decode(x, desc, "relu", y=y, ws=ws)
     torch.cuda.synchronize()
     eager = y.clone()
