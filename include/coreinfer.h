@@ -306,9 +306,9 @@ typedef struct {
  *     workgroups through ws as self-validating words.  For this path ws must
  *     have been ZEROED ONCE (hipMemsetAsync) before its first use and must not
  *     be written by anything else afterwards; every call leaves it ready for
- *     the next one, also when replayed from a HIP graph.  A workspace is bound
- *     to the (B, K, d) it was sized for: zero it again before using it with
- *     other sizes.  The launch needs one workgroup per compute unit resident at
+ *     the next one, also when replayed from a HIP graph.  A workspace that has
+ *     served a neuron-major or gathered call (which fills it with partial sums)
+ *     must be zeroed again before an output-major call.  The launch needs one workgroup per compute unit resident at
  *     the same time; if other work keeps compute units busy for long, a
  *     workgroup gives up waiting after a bounded number of polls, the call's
  *     output is then unspecified and the int32 at ws + 4 is set to 1 (it is 0
@@ -322,6 +322,26 @@ int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w,
 /* Enqueues a copy of the workspace's error word (see above) to *status_out, a
  * device int32; valid after the stream has been synchronised. */
 int coreinfer_ffn_decode_status(const void* ws, int32_t* status_out, void* stream);
+
+/*
+ * coreinfer_ffn_decode for callers that cannot allocate device memory or have
+ * none to pass: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and same results as
+ * coreinfer_ffn_decode, but the workspace is a static array inside the library
+ * (17 MiB of device memory on every GPU the library runs on, held until the
+ * process ends); the call allocates nothing.  Limits: output-major compact
+ * buffers: K <= 131024; neuron-major and gathered calls: B * slices * d * 4
+ * bytes <= 16 MiB, slices = min(K, compute units / B) (e.g. B = 8, d = 9216 on
+ * 256 compute units needs 9 MiB).  Beyond them: CI_ERR_WORKSPACE, nothing is
+ * launched.  status_out: NULL, or a device int32 that receives the call's error
+ * word (0, or 1 if a single-launch call gave up waiting; see above) by a copy
+ * enqueued after the kernels.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams, different host threads) race and give wrong
+ * results; calls on one stream are fine.  Nothing needs zeroing by the caller.
+ */
+int coreinfer_ffn_decode_static(const void* x, int64_t B, const ci_ffn_weights* w,
+                                int dtype, int act, void* y, int32_t* status_out, void* stream);
 
 /*
  * Union-batched decode.  Several sentences, each with its own frozen core set

@@ -73,6 +73,7 @@ _SIGNATURES = {
     "coreinfer_ffn_decode": (_int, [_vp, _i64, ctypes.POINTER(ci_ffn_weights), _int, _int, _vp,
                                     _vp, _sz, _vp]),
     "coreinfer_ffn_decode_status": (_int, [_vp, _vp, _vp]),
+    "coreinfer_ffn_decode_static": (_int, [_vp, _i64, ctypes.POINTER(ci_ffn_weights), _int, _int, _vp, _vp, _vp]),
     "coreinfer_union_workspace_size": (_int, [_i64, ctypes.POINTER(_sz)]),
     "coreinfer_union_build": (_int, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_ffn_decode_union_workspace_size": (_int, [_i64, _i64, _i64, _int, _int, ctypes.POINTER(_sz)]),
@@ -396,6 +397,20 @@ def ffn_decode(x: torch.Tensor, weights: ci_ffn_weights, act: str, y: Optional[t
     _check(_lib.coreinfer_ffn_decode(_ptr(x2), B, ctypes.byref(weights), DTYPE_CODE[x.dtype],
                                      ACT_CODE[act], _ptr(y), _ptr(ws), ws.numel(), _stream(x)),
            "coreinfer_ffn_decode")
+    return y if x.dim() == 2 else y.squeeze(0)
+
+
+def ffn_decode_static(x: torch.Tensor, weights: ci_ffn_weights, act: str, y: Optional[torch.Tensor] = None,
+                      status: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """coreinfer_ffn_decode_static on x [B, d] (or [d]): the library's own scratch, no allocation in the call
+    (pass y to keep this wrapper from allocating the output)."""
+    x2 = x if x.dim() == 2 else x.unsqueeze(0)
+    B, d = x2.shape
+    if y is None:
+        y = torch.empty_like(x2)
+    _check(_lib.coreinfer_ffn_decode_static(_ptr(x2), B, ctypes.byref(weights), DTYPE_CODE[x.dtype],
+                                            ACT_CODE[act], _ptr(y), _ptr(status), _stream(x)),
+           "coreinfer_ffn_decode_static")
     return y if x.dim() == 2 else y.squeeze(0)
 
 

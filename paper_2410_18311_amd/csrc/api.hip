@@ -361,8 +361,10 @@ int coreinfer_ffn_decode_workspace_size(int64_t B, int64_t K, int64_t d, size_t*
   return CI_OK;
 }
 
-int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,
-                         void* y, void* ws, size_t ws_bytes, void* stream) {
+namespace {
+
+// Argument checks common to the decode entry points (everything but the workspace).
+int decode_check(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act, void* y) {
   if (!w) return CI_ERR_INVALID_ARG;
   if (!dtype_ok(dtype) || !act_ok(act)) return CI_ERR_BAD_DTYPE;
   if (!layout_ok(w->down_layout)) return CI_ERR_BAD_LAYOUT;
@@ -381,10 +383,76 @@ int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int 
   if (!aligned16(x) || !aligned16(y) || !aligned16(w->w_up) || !aligned16(w->w_gate) ||
       !aligned16(w->w_down) || (reinterpret_cast<uintptr_t>(w->core_idx) & 3u))
     return CI_ERR_BAD_LAYOUT;
+  return CI_OK;
+}
+
+// Scratch of coreinfer_ffn_decode_static: device memory that belongs to the library, one copy per
+// GPU the library runs on, held until the process ends.  Two parts that are never mixed: the tagged
+// words of the single-launch path (zero when the module is loaded, which is all that path asks
+// for: a call's tag is one more than the epoch the last call left) and the partial outputs of the
+// two-launch path.
+constexpr size_t kStaticWords = (size_t)1 << 20;     // header + 8 bytes per neuron: K <= 131024
+constexpr size_t kStaticPartial = (size_t)16 << 20;  // B * slices * d fp32 partial outputs
+static __device__ __align__(256) unsigned char scratch[kStaticWords + kStaticPartial];
+
+// The array's address on the current device.  `scratch` itself is a host-side stand-in, not a device
+// address: only the pointer obtained here may be handed to kernels and copies.
+int static_scratch(unsigned char** out) {
+  static std::mutex mu;
+  static unsigned char* ptr[64] = {nullptr};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CI_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    unsigned char* p = nullptr;
+    if (hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)) != hipSuccess || !p) return CI_ERR_HIP;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return CI_OK;
+}
+
+}  // namespace
+
+int coreinfer_ffn_decode(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,
+                         void* y, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = decode_check(x, B, w, dtype, act, y);
+  if (rc != CI_OK) return rc;
+  size_t need = 0;
+  if (coreinfer_ffn_decode_workspace_size(B, w->K, w->d, &need) != CI_OK) return CI_ERR_INVALID_ARG;
   if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
   if (!aligned16(ws)) return CI_ERR_BAD_LAYOUT;
-  if (out_major && w->K > 0) return launch_ffn_decode_fused(x, B, w, dtype, act, y, ws, (hipStream_t)stream);
+  if (w->down_layout == CI_DOWN_OUT_MAJOR && w->K > 0)
+    return launch_ffn_decode_fused(x, B, w, dtype, act, y, ws, (hipStream_t)stream);
   return launch_ffn_decode(x, B, w, dtype, act, y, reinterpret_cast<float*>(ws), (hipStream_t)stream);
+}
+
+int coreinfer_ffn_decode_static(const void* x, int64_t B, const ci_ffn_weights* w, int dtype, int act,
+                                void* y, int32_t* status_out, void* stream) {
+  const int rc = decode_check(x, B, w, dtype, act, y);
+  if (rc != CI_OK) return rc;
+  if (reinterpret_cast<uintptr_t>(status_out) & 3u) return CI_ERR_BAD_LAYOUT;
+  const bool single = w->down_layout == CI_DOWN_OUT_MAJOR && w->K > 0;
+  // what THIS call needs (not the device-independent bound of coreinfer_ffn_decode_workspace_size)
+  const size_t need = single ? fused_decode_ws_bytes(w->K)
+                             : (size_t)B * (size_t)decode_splits(B, w->K) * (size_t)w->d * sizeof(float);
+  if (need > (single ? kStaticWords : kStaticPartial)) return CI_ERR_WORKSPACE;
+  unsigned char* base = nullptr;
+  const int rs = static_scratch(&base);
+  if (rs != CI_OK) return rs;
+  hipStream_t s = (hipStream_t)stream;
+  if (!single) {
+    const int rl = launch_ffn_decode(x, B, w, dtype, act, y, reinterpret_cast<float*>(base + kStaticWords), s);
+    if (rl != CI_OK || !status_out) return rl;
+    // the two-launch path has no bounded waits: nothing to report.  A copy, not a memset: callers may
+    // be under graph capture, and base + 8 is a word of the header that no kernel writes.
+    return hipMemcpyAsync(status_out, base + 8, sizeof(int32_t), hipMemcpyDeviceToDevice, s) == hipSuccess ? CI_OK
+                                                                                                         : CI_ERR_HIP;
+  }
+  const int rl = launch_ffn_decode_fused(x, B, w, dtype, act, y, base, s);
+  if (rl != CI_OK || !status_out) return rl;
+  return hipMemcpyAsync(status_out, base + 4, sizeof(int32_t), hipMemcpyDeviceToDevice, s) == hipSuccess ? CI_OK
+                                                                                                       : CI_ERR_HIP;
 }
 
 int coreinfer_ffn_decode_status(const void* ws, int32_t* status_out, void* stream) {
