@@ -112,8 +112,8 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
     A_buf = torch.empty((B * M, N), dtype=torch.float32, device=dev)
     Y_buf = torch.empty((B * M, d), dtype=dtype, device=dev)
     dense_ws = torch.empty(ci.ffn_dense_workspace_size(B * M, d, N, dtype), dtype=torch.uint8, device=dev)
-    sel_ws = torch.empty(ci.select_workspace_size(M, N), dtype=torch.uint8, device=dev)
-    counts = torch.empty(N, dtype=torch.int32, device=dev)
+    sel_ws = torch.empty(ci.select_batch_workspace_size(B, M, N), dtype=torch.uint8, device=dev)
+    counts = torch.empty((B, N), dtype=torch.int32, device=dev)
     core_idx = torch.empty((L, B, K), dtype=torch.int32, device=dev)
     # zeroed once: the single-launch decode exchanges hidden values through tagged words in it
     dec_ws = ci.decode_workspace(B, K, d, dev)
@@ -139,8 +139,8 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
     def prefill_layer(l):
         w = weights[l]
         dense_layer(l)
-        for s in range(B):
-            ci.select(A_buf[s * M:(s + 1) * M], cfg.alpha, beta, core_idx=core_idx[l, s], counts=counts, ws=sel_ws)
+        # all sentences of the batch in one set of launches
+        ci.select_batch(A_buf, B, cfg.alpha, beta, core_idx=core_idx[l], counts=counts, ws=sel_ws)
         if not gathered:
             ci.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act,
                        core_idx[l, 0], out=cbuf[l])
@@ -221,8 +221,13 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
 
     dense_ms = timed(lambda: [dense_layer(l) for l in range(L)]) / L   # per layer, all B sentences together
     scratch_idx = torch.empty(K, dtype=torch.int32, device=dev)   # keeps the real core sets intact
-    select_ms = timed_graph(lambda: [ci.select(A_buf[:M], cfg.alpha, beta, core_idx=scratch_idx, counts=counts,
+    select_ms = timed_graph(lambda: [ci.select(A_buf[:M], cfg.alpha, beta, core_idx=scratch_idx, counts=counts[0],
                                                ws=sel_ws) for l in range(L)]) / L
+    select_batch_ms = None
+    if B > 1:
+        scratch_idx_b = torch.empty((B, K), dtype=torch.int32, device=dev)
+        select_batch_ms = timed_graph(lambda: [ci.select_batch(A_buf, B, cfg.alpha, beta, core_idx=scratch_idx_b,
+                                                               counts=counts, ws=sel_ws) for l in range(L)]) / L
     # the same prefill without an fp32 score matrix: the dense FFN hands out the hidden matrix in the
     # element type and the selection ranks it (reported beside the default path, never part of `value`)
     hidden_prefill = None
@@ -428,6 +433,7 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
         "decode_hbm_frac_whole_phase": e2e_gbps / HBM_PEAK_GBPS,
         "decode_status_word": decode_status,
         "select_us_per_layer": select_ms * 1e3,
+        "select_batch_us_per_layer": None if select_batch_ms is None else select_batch_ms * 1e3,
         "compact_us_per_layer": None if compact_ms is None else compact_ms * 1e3,
         "dense_prefill_ms_per_layer": dense_ms,
         "dense_prefill_tflops": dense_flops / (dense_ms * 1e-3) / 1e12,

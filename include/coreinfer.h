@@ -111,6 +111,21 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld,
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same selection for B sentences at once (independent sentences batched,
+ * each with its own core set): sentence b is rows [b M, (b + 1) M) of
+ * act [B M, N]; core_idx [B, K] and counts [B, N] (may be NULL) hold its
+ * results, exactly those of coreinfer_select on its rows.  One set of launches
+ * serves all sentences where Def. 2 runs in parallel (M < 2048 and
+ * N <= 65536); otherwise the sentences are taken one after the other.
+ * ws: at least coreinfer_select_batch_workspace_size(B, M, N) bytes.
+ * Limits: 1 <= B <= 65535, B * M <= CI_MAX_TOKENS * 64.
+ */
+int coreinfer_select_batch_workspace_size(int64_t B, int64_t M, int64_t N, size_t* bytes);
+int coreinfer_select_batch(const float* act, int64_t B, int64_t M, int64_t N, int64_t ld,
+                           double alpha, double beta, int32_t* core_idx, int32_t* counts,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/*
  * The same selection on the hidden matrix as the FFN holds it, in the layer's
  * element type, so that no fp32 copy of the activations has to be written for
  * it (Sec. 1 calls the prefill-stage selection free of extra cost; Def. 1

@@ -54,6 +54,8 @@ _SIGNATURES = {
     "coreinfer_keep_count": (_int, [_dbl, _i64, ctypes.POINTER(_i64)]),
     "coreinfer_select_workspace_size": (_int, [_i64, _i64, ctypes.POINTER(_sz)]),
     "coreinfer_select": (_int, [_vp, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
+    "coreinfer_select_batch_workspace_size": (_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
+    "coreinfer_select_batch": (_int, [_vp, _i64, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_select_hidden": (_int, [_vp, _int, _int, _i64, _i64, _i64, _dbl, _dbl, _vp, _vp, _vp, _sz, _vp]),
     "coreinfer_count_tokens": (_int, [_vp, _i64, _i64, _i64, _dbl, _vp, _int, _vp, _sz, _vp]),
     "coreinfer_count_select": (_int, [_vp, _i64, _i64, _dbl, _vp, _vp, _sz, _vp]),
@@ -169,6 +171,30 @@ def select(act: torch.Tensor, alpha: float, beta: float, core_idx: Optional[torc
     _check(_lib.coreinfer_select(_ptr(act), M, N, act.stride(0), float(alpha), float(beta),
                                  _ptr(core_idx), _ptr(counts), _ptr(ws), ws.numel(), _stream(act)),
            "coreinfer_select")
+    return core_idx, counts
+
+
+def select_batch_workspace_size(B: int, M: int, N: int) -> int:
+    b = _sz(0)
+    _check(_lib.coreinfer_select_batch_workspace_size(B, M, N, ctypes.byref(b)), "coreinfer_select_batch_workspace_size")
+    return b.value
+
+
+def select_batch(act: torch.Tensor, B: int, alpha: float, beta: float, core_idx: Optional[torch.Tensor] = None,
+                 counts: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """coreinfer_select_batch on act [B * M, N] (fp32): returns (core_idx [B, K], counts [B, N])."""
+    BM, N = act.shape
+    M = BM // B
+    assert M * B == BM
+    K = keep_count(beta, N)
+    if core_idx is None:
+        core_idx = torch.empty((B, K), dtype=torch.int32, device=act.device)
+    if counts is None:
+        counts = torch.empty((B, N), dtype=torch.int32, device=act.device)
+    if ws is None:
+        ws = _workspace(select_batch_workspace_size(B, M, N), act)
+    _check(_lib.coreinfer_select_batch(_ptr(act), B, M, N, act.stride(0), float(alpha), float(beta), _ptr(core_idx),
+                                       _ptr(counts), _ptr(ws), ws.numel(), _stream(act)), "coreinfer_select_batch")
     return core_idx, counts
 
 

@@ -158,6 +158,45 @@ int coreinfer_select(const float* act, int64_t M, int64_t N, int64_t ld, double 
                        (hipStream_t)stream);
 }
 
+int coreinfer_select_batch_workspace_size(int64_t B, int64_t M, int64_t N, size_t* bytes) {
+  if (!bytes || B < 1 || B > 65535 || M < 1 || M > CI_MAX_TOKENS || N < 1 || N > CI_MAX_NEURONS ||
+      B * M > (int64_t)CI_MAX_TOKENS * 64)
+    return CI_ERR_INVALID_ARG;
+  SelectWs w;
+  select_ws_layout(M, N, &w, B);
+  *bytes = w.total;
+  return CI_OK;
+}
+
+int coreinfer_select_batch(const float* act, int64_t B, int64_t M, int64_t N, int64_t ld, double alpha, double beta,
+                           int32_t* core_idx, int32_t* counts, void* ws, size_t ws_bytes, void* stream) {
+  size_t need = 0;
+  if (coreinfer_select_batch_workspace_size(B, M, N, &need) != CI_OK) return CI_ERR_INVALID_ARG;
+  if (!act || !core_idx) return CI_ERR_INVALID_ARG;
+  const int64_t qa = fraction_ppm(alpha), qb = fraction_ppm(beta);
+  if (qa == 0 || qb == 0) return CI_ERR_INVALID_ARG;
+  if (ld < N) return CI_ERR_BAD_LAYOUT;
+  if ((reinterpret_cast<uintptr_t>(act) & 3u) || (reinterpret_cast<uintptr_t>(core_idx) & 3u) ||
+      (reinterpret_cast<uintptr_t>(counts) & 3u))
+    return CI_ERR_BAD_LAYOUT;
+  if (!ws || ws_bytes < need) return CI_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 15u) return CI_ERR_BAD_LAYOUT;
+  const int64_t K = keep(qb, N);
+  SelectWs w;
+  select_ws_layout(M, N, &w, B);
+  int32_t* cnt = counts ? counts : reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + w.off_counts);
+  if (B == 1 || select_batch_ok(M, N))
+    return launch_select(act, CI_F32, 0, M, N, ld, qa, K, M, core_idx, cnt, ws, kSelTokens | kSelFinal,
+                         (hipStream_t)stream, (int)B, N);
+  // one sentence after the other; a sentence's thresholds and histogram fit the front of the batch's workspace
+  for (int64_t b = 0; b < B; ++b) {
+    const int rc = launch_select(act + (size_t)b * M * ld, CI_F32, 0, M, N, ld, qa, K, M, core_idx + b * K, cnt + b * N,
+                                 ws, kSelTokens | kSelFinal, (hipStream_t)stream);
+    if (rc != CI_OK) return rc;
+  }
+  return CI_OK;
+}
+
 int coreinfer_select_hidden(const void* hidden, int dtype, int act, int64_t M, int64_t N, int64_t ld, double alpha,
                             double beta, int32_t* core_idx, int32_t* counts, void* ws, size_t ws_bytes,
                             void* stream) {

@@ -174,11 +174,12 @@ enum { kSelZero = 1, kSelTokens = 2, kSelFinal = 4, kSelAccumulate = 8 };
 struct SelectWs {
   size_t off_thr, off_hist, off_counts, total;
 };
-void select_ws_layout(int64_t M, int64_t N, SelectWs* w);
+void select_ws_layout(int64_t M, int64_t N, SelectWs* w, int64_t B = 1);
+bool select_batch_ok(int64_t M, int64_t N);
 // ws: laid out by select_ws_layout (may be null when only kSelZero is asked for)
 int launch_select(const void* act, int act_dtype, int take_abs, int64_t M, int64_t N, int64_t ld, int64_t q_alpha,
                   int64_t K, int64_t max_count, int32_t* core_idx, int32_t* counts, void* ws, int what,
-                  hipStream_t s);
+                  hipStream_t s, int B = 1, int64_t counts_stride = 0);
 int launch_scatter_count(const int32_t* idx, int64_t n_idx, int64_t N, int32_t* counts, hipStream_t s);
 int launch_similarity(const int32_t* a, int64_t Ka, const int32_t* b, int64_t Kb, int32_t* out, hipStream_t s);
 int launch_assign_group(const int32_t* set, int64_t K, const int32_t* groups, int64_t G, int64_t Kg,

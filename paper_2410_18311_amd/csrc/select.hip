@@ -27,7 +27,8 @@
 //     and n <= cut).  Nine barriers per token in the usual fp32 case (no tie
 //     cut, at most 64 keys left after two digits).
 // count_kernel -- Eq. 3.  Counting is a second pass over the activations by
-//     neuron: a workgroup owns 256 neurons, walks all tokens, compares every
+//     neuron: a workgroup owns 64 neurons (256 when that still gives more
+//     workgroups than half the compute units), walks all tokens, compares every
 //     activation with its token's (T, cut) and keeps the tallies in registers
 //     -- no atomics on the counters, and the counts are the same whatever the
 //     scheduling.  It also adds its neurons' counts to a histogram of count
@@ -286,7 +287,7 @@ template <int ITEMS, bool TWO, class IN>  // TWO: registers capped so that two w
 __global__ __launch_bounds__(kThreads, TWO ? 8 : 4) void token_threshold_kernel(const typename IN::T* __restrict__ act,
                                                                int M, int N, int64_t ld, int64_t q_alpha,
                                                                uint32_t sign_mask, uint32_t* __restrict__ thr,
-                                                               uint32_t* ghist) {
+                                                               uint32_t* ghist, int ghist_words) {
   using TI = typename IN::T;
   constexpr bool kNarrow = sizeof(TI) == 2;  // the fp32 image of a 16-bit value has nothing below bit 13
   __shared__ SelShared sh;
@@ -303,7 +304,7 @@ __global__ __launch_bounds__(kThreads, TWO ? 8 : 4) void token_threshold_kernel(
   const int n_iter = (N + nt - 1) / nt;
   init_shared(&sh);
   if (ghist)  // cleared here, a slice per workgroup, for the counting launch that follows
-    for (int j = blockIdx.x * nt + tid; j < kCountBins * kHistCopies; j += gridDim.x * nt) ghist[j] = 0u;
+    for (int j = blockIdx.x * nt + tid; j < ghist_words; j += gridDim.x * nt) ghist[j] = 0u;
 
   for (int m = blockIdx.x; m < M; m += gridDim.x) {
     const TI* row = act + (size_t)m * ld;
@@ -518,7 +519,13 @@ __device__ __forceinline__ void count_tokens_of_lane(const typename IN::T* __res
 template <int NPW, class IN>
 __global__ __launch_bounds__(1024) void count_kernel(const typename IN::T* __restrict__ act, int M, int N, int64_t ld,
                                                      uint32_t sign_mask, const uint32_t* __restrict__ thr, int vec_ok,
-                                                     int32_t* counts, int accumulate, uint32_t* ghist) {
+                                                     int32_t* counts, int accumulate, uint32_t* ghist,
+                                                     int64_t counts_stride) {
+  // blockIdx.y: the sentence of a batch (M rows, M thresholds, its own counters and histogram)
+  act += (size_t)blockIdx.y * M * ld;
+  thr += (size_t)blockIdx.y * M * 2;
+  counts += (size_t)blockIdx.y * counts_stride;
+  if (ghist) ghist += (size_t)blockIdx.y * kCountBins * kHistCopies;
   constexpr int TPW = 256 / NPW;   // tokens per wave instruction
   constexpr int LPR = 64 / TPW;    // lanes per token row
   __shared__ uint32_t tally[NPW];
@@ -569,7 +576,11 @@ __global__ __launch_bounds__(1024) void count_kernel(const typename IN::T* __res
 // N <= 65536 keeps that to a few MB in all).
 __global__ __launch_bounds__(1024) void def2_parallel_kernel(const int32_t* __restrict__ counts,
                                                              const uint32_t* __restrict__ ghist, int N, int K,
-                                                             int32_t* __restrict__ core_idx, int vec_ok) {
+                                                             int32_t* __restrict__ core_idx, int vec_ok,
+                                                             int64_t counts_stride) {
+  counts += (size_t)blockIdx.y * counts_stride;  // blockIdx.y: the sentence of a batch
+  ghist += (size_t)blockIdx.y * kCountBins * kHistCopies;
+  core_idx += (size_t)blockIdx.y * K;
   __shared__ __attribute__((aligned(16))) uint32_t wtot[4], wg[kMaxWaves], we[kMaxWaves];
   __shared__ uint32_t T_s, need_s;
   const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6;
@@ -896,13 +907,13 @@ __global__ __launch_bounds__(1024) void best_group_kernel(const int32_t* __restr
 
 template <int ITEMS, bool TWO, class IN>
 int launch_threshold(const typename IN::T* act, int M, int N, int64_t ld, int64_t q_alpha, uint32_t sign_mask,
-                     uint32_t* thr, uint32_t* ghist, int grid, hipStream_t s) {
+                     uint32_t* thr, uint32_t* ghist, int ghist_words, int grid, hipStream_t s) {
   static std::atomic<uint64_t> attr_seen{0};  // raise the dynamic-LDS ceiling once (64 KB by default)
   if (allow_dynamic_lds(attr_seen, reinterpret_cast<const void*>(&token_threshold_kernel<ITEMS, TWO, IN>), 156 * 1024) != CI_OK)
     return CI_ERR_HIP;
   hipLaunchKernelGGL((token_threshold_kernel<ITEMS, TWO, IN>), dim3(grid), dim3(kThreads),
                      (size_t)(kHistWords + kHist2Words) * 4, s, act,
-                     M, N, ld, q_alpha, sign_mask, thr, ghist);
+                     M, N, ld, q_alpha, sign_mask, thr, ghist, ghist_words);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
@@ -910,11 +921,13 @@ int launch_threshold(const typename IN::T* act, int M, int N, int64_t ld, int64_
 // Def. 1 and Eq. 3 for an activation matrix of element type IN::T.  The fp32 path has a kernel for
 // every keys-per-thread step; the 16-bit types share three of them (16, 40, streaming).
 template <class IN>
-int launch_tokens(const void* act_v, int M, int N, int64_t ld, int64_t q_alpha, uint32_t sign_mask, uint32_t* thr,
-                  uint32_t* ghist, int32_t* counts, int accumulate, int nt, int items, int nblocks, int cus,
-                  hipStream_t s) {
+int launch_tokens(const void* act_v, int B, int M_each, int N, int64_t ld, int64_t q_alpha, uint32_t sign_mask,
+                  uint32_t* thr, uint32_t* ghist, int32_t* counts, int64_t counts_stride, int accumulate, int nt,
+                  int items, int nblocks, int cus, hipStream_t s) {
   using TI = typename IN::T;
   const TI* act = reinterpret_cast<const TI*>(act_v);
+  const int M = B * M_each;  // Def. 1 treats the rows of all sentences alike
+  const int ghist_words = B * kCountBins * kHistCopies;
   // more tokens than compute units and at most 16 keys per thread: two workgroups per compute
   // unit (a token round is half instruction issue, half barriers and latency; the register cap
   // this needs costs a single workgroup about 10 %, so it is not used for short prompts)
@@ -923,7 +936,7 @@ int launch_tokens(const void* act_v, int M, int N, int64_t ld, int64_t q_alpha, 
   if (grid > M) grid = M;
   if (grid < 1) grid = 1;
   int rc = CI_OK;
-#define CI_THR(I, W) launch_threshold<I, W, IN>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, grid, s)
+#define CI_THR(I, W) launch_threshold<I, W, IN>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, ghist_words, grid, s)
   if constexpr (sizeof(TI) == 4) {
     if (two && items <= 8) rc = CI_THR(8, true);
     else if (two) rc = CI_THR(16, true);
@@ -947,12 +960,12 @@ int launch_tokens(const void* act_v, int M, int N, int64_t ld, int64_t q_alpha, 
   const uintptr_t quad = 4 * sizeof(TI);
   const int vec_ok = ((reinterpret_cast<uintptr_t>(act) & (quad - 1)) == 0 && ld % 4 == 0) ? 1 : 0;
   // 64 neurons per workgroup when blocks of 256 would leave more than half of the chip idle
-  if (nblocks <= cus / 2)
-    hipLaunchKernelGGL((count_kernel<64, IN>), dim3((N + 63) / 64), dim3(nt), 0, s, act, M, N, ld, sign_mask, thr,
-                       vec_ok, counts, accumulate, ghist);
+  if (nblocks * B <= cus / 2)
+    hipLaunchKernelGGL((count_kernel<64, IN>), dim3((N + 63) / 64, B), dim3(nt), 0, s, act, M_each, N, ld, sign_mask,
+                       thr, vec_ok, counts, accumulate, ghist, counts_stride);
   else
-    hipLaunchKernelGGL((count_kernel<256, IN>), dim3(nblocks), dim3(nt), 0, s, act, M, N, ld, sign_mask, thr,
-                       vec_ok, counts, accumulate, ghist);
+    hipLaunchKernelGGL((count_kernel<256, IN>), dim3(nblocks, B), dim3(nt), 0, s, act, M_each, N, ld, sign_mask, thr,
+                       vec_ok, counts, accumulate, ghist, counts_stride);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }
@@ -974,20 +987,27 @@ size_t round256z(size_t n) { return (n + 255) / 256 * 256; }
 
 // Workspace of one selection: per-token (T, cut) pairs, the histogram of count
 // values, and counters for callers that pass none.
-void select_ws_layout(int64_t M, int64_t N, SelectWs* w) {
+void select_ws_layout(int64_t M, int64_t N, SelectWs* w, int64_t B) {
   w->off_thr = 0;
-  w->off_hist = round256z((size_t)(M > 0 ? M : 1) * 2 * sizeof(uint32_t));
-  w->off_counts = w->off_hist + round256z((size_t)kCountBins * kHistCopies * sizeof(uint32_t));
-  w->total = w->off_counts + round256z((size_t)N * sizeof(int32_t));
+  w->off_hist = round256z((size_t)B * (size_t)(M > 0 ? M : 1) * 2 * sizeof(uint32_t));
+  w->off_counts = w->off_hist + round256z((size_t)B * kCountBins * kHistCopies * sizeof(uint32_t));
+  w->total = w->off_counts + round256z((size_t)B * (size_t)N * sizeof(int32_t));
 }
 
 // The stages of the selection, individually switchable:
 //   kSelZero       clear the counters (before members are scattered into them)
 //   kSelTokens     Def. 1 over the M rows of act, then Eq. 3 (kSelAccumulate: added to the counters)
 //   kSelFinal      Def. 2 on the counters (values <= max_count)
+// B > 1: a batch of sentences, sentence b being rows [b M, (b + 1) M) of act, with counts [B, N]
+// (row stride counts_stride) and core_idx [B, K]; only for the whole selection in one go
+// (kSelTokens | kSelFinal) where Def. 2 runs in parallel (select_batch_ok).
+bool select_batch_ok(int64_t M, int64_t N) {
+  return M < kCountBins && (N + 255) / 256 <= 256 && params().select_def2_single == 0;
+}
+
 int launch_select(const void* act, int act_dtype, int take_abs, int64_t M64, int64_t N64, int64_t ld,
                   int64_t q_alpha, int64_t K64, int64_t max_count, int32_t* core_idx, int32_t* counts, void* ws,
-                  int what, hipStream_t s) {
+                  int what, hipStream_t s, int B, int64_t counts_stride) {
   const int M = (what & kSelTokens) ? (int)M64 : 0, N = (int)N64, K = (int)K64;
   DeviceInfo di;
   int rc = device_info(&di);
@@ -1007,22 +1027,27 @@ int launch_select(const void* act, int act_dtype, int take_abs, int64_t M64, int
                               max_count < kCountBins && nblocks <= 256 && params().select_def2_single == 0;
   if (what & kSelTokens) {
     SelectWs w;
-    select_ws_layout(M, N, &w);
+    select_ws_layout(M, N, &w, B);
+    if (B > 1 && !parallel_final) return CI_ERR_UNSUPPORTED;
     char* base = reinterpret_cast<char*>(ws);
     uint32_t* thr = reinterpret_cast<uint32_t*>(base + w.off_thr);
     uint32_t* ghist = parallel_final ? reinterpret_cast<uint32_t*>(base + w.off_hist) : nullptr;
     const uint32_t sign_mask = take_abs ? 0x7fffffffu : 0xffffffffu;
     const int acc = (what & kSelAccumulate) ? 1 : 0;
     if (act_dtype == CI_F16)
-      rc = launch_tokens<InF16>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, acc, nt, items, nblocks, di.cus, s);
+      rc = launch_tokens<InF16>(act, B, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, counts_stride, acc, nt, items,
+                               nblocks, di.cus, s);
     else if (act_dtype == CI_BF16)
-      rc = launch_tokens<InBF16>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, acc, nt, items, nblocks, di.cus, s);
+      rc = launch_tokens<InBF16>(act, B, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, counts_stride, acc, nt, items,
+                               nblocks, di.cus, s);
     else
-      rc = launch_tokens<InF32>(act, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, acc, nt, items, nblocks, di.cus, s);
+      rc = launch_tokens<InF32>(act, B, M, N, ld, q_alpha, sign_mask, thr, ghist, counts, counts_stride, acc, nt, items,
+                               nblocks, di.cus, s);
     if (rc != CI_OK) return rc;
     if (parallel_final) {
       const int cvec = (reinterpret_cast<uintptr_t>(counts) & 15u) == 0 ? 1 : 0;
-      hipLaunchKernelGGL(def2_parallel_kernel, dim3(nblocks), dim3(1024), 0, s, counts, ghist, N, K, core_idx, cvec);
+      hipLaunchKernelGGL(def2_parallel_kernel, dim3(nblocks, B), dim3(1024), 0, s, counts, ghist, N, K, core_idx,
+                         cvec && counts_stride % 4 == 0, counts_stride);
       CI_HIP_CHECK_LAUNCH();
       return CI_OK;
     }

@@ -1,7 +1,7 @@
 """Small driver for hardware-counter runs of the decode kernel.
 
     rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d OUT -- \
-        python3 -m paper_2410_18311_amd.pmc_probe --workload opt6.7b_relu_f16
+        python3 pmc_probe.py --workload opt6.7b_relu_f16
 
 It launches (a) a plain device-to-device copy of a known size (the calibration
 against which the FETCH_SIZE / WRITE_SIZE readings are scaled) and (b) the
@@ -20,8 +20,8 @@ import argparse
 
 import torch
 
-from . import coreinfer as ci
-from . import workloads as wl
+from paper_2410_18311_amd import coreinfer as ci
+from paper_2410_18311_amd import workloads as wl
 
 COPY_BYTES = 256 << 20
 

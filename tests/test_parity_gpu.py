@@ -257,6 +257,26 @@ def test_compact_matches_oracle(lib, dt, act, layout, d, N, K):
         assert np.array_equal(f64(out["b_up_c"]), ref["b_up_c"])
 
 
+@pytest.mark.parametrize("B,M,N,alpha,beta,kind", [(8, 64, 5000, 0.2, 0.4, "relu"), (2, 300, 1000, 0.3, 0.25, "abs"),
+                                                   (3, 2100, 520, 0.2, 0.4, "relu"), (5, 1, 4097, 0.5, 0.1, "relu"),
+                                                   (4, 37, 70000, 0.1, 0.3, "relu"), (1, 40, 300, 0.2, 0.4, "relu")])
+def test_select_batch_matches_oracle(lib, B, M, N, alpha, beta, kind):
+    """Several sentences selected by one call: each sentence's core set and counts bit-exact against
+    the oracle on its own rows (one set of launches where Def. 2 runs in parallel; M >= 2048 or
+    N > 65536 take the sentences one after the other), also with a padded row stride."""
+    _say("select batch case", B, M, N, alpha, beta, kind)
+    A = wl.activation_like(B * M, N, seed=B * 1000 + M + N, kind=kind, levels=16 if M < 100 else 0)
+    buf = torch.zeros(B * M, N + 4, dtype=torch.float32, device=DEV)
+    buf[:, :N] = torch.from_numpy(A).to(DEV)
+    S, counts = lib.select_batch(buf[:, :N], B, alpha, beta)
+    torch.cuda.synchronize()
+    assert S.shape == (B, orc.keep_count(beta, N)) and counts.shape == (B, N)
+    for b in range(B):
+        S_ref, c_ref = orc.select(A[b * M:(b + 1) * M], alpha, beta)
+        assert counts[b].cpu().numpy().tolist() == c_ref.tolist(), f"sentence {b}: counts"
+        assert S[b].cpu().numpy().tolist() == S_ref.tolist(), f"sentence {b}: core set"
+
+
 @pytest.mark.parametrize("dt,act,layout", [("f16", "relu", "out_major"), ("bf16", "swiglu", "out_major"),
                                            ("f32", "relu", "neuron_major"), ("f16", "swiglu", "neuron_major")])
 @pytest.mark.parametrize("d,N,K,turnover", [(64, 200, 77, 0.3), (1024, 3000, 1201, 0.1), (256, 500, 500, 0.0),
