@@ -32,11 +32,15 @@ def main():
     p.add_argument("--layers", type=int, default=8)
     p.add_argument("--reps", type=int, default=3)
     p.add_argument("--what", choices=["decode", "prefill", "union"], default="decode")
+    p.add_argument("--beta", type=float, default=None, help="sentence keep fraction (default: the workload's first)")
+    p.add_argument("--down-layout", choices=["auto", "out_major", "neuron_major"], default="auto",
+                   help="compact down matrix of the decode run (auto: the library's preference for the shape)")
     args = p.parse_args()
     cfg = wl.WORKLOADS[args.workload]
     dev = "cuda:0"
     d, N, B = cfg.d, cfg.N, cfg.sentences
-    K = ci.keep_count(cfg.betas[0], N)
+    beta = cfg.betas[0] if args.beta is None else args.beta
+    K = ci.keep_count(beta, N)
     dt = cfg.torch_dtype
 
     if args.what == "prefill":
@@ -53,7 +57,7 @@ def main():
         for _ in range(args.reps):
             ci.ffn_dense(X, w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"], cfg.down_layout, cfg.act,
                          want_y=True, want_a=True, Y=Y, A=A, ws=dws)
-            ci.select(A, cfg.alpha, cfg.betas[0], core_idx=core, counts=cnt, ws=sws)
+            ci.select(A, cfg.alpha, beta, core_idx=core, counts=cnt, ws=sws)
             if B == 1:
                 bufs = ci.compact(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], cfg.down_layout, cfg.act, core,
                                   out=bufs)
@@ -73,15 +77,21 @@ def main():
     gathered = B > 1
     rows = N if gathered else K
     layers = []
+    layout = "neuron_major"
+    if not gathered and args.what == "decode":
+        layout = ci.compact_preferred_layout(K, d, dt, cfg.act) if args.down_layout == "auto" else args.down_layout
+    ld = ci.compact_down_ld(K, dt)
     for _ in range(args.layers):
-        up, down = mk(rows, d), mk(rows, d)
+        up = mk(rows, d)
+        down = mk(d, ld) if layout == "out_major" else mk(rows, d)
         gate = mk(rows, d) if cfg.act == "swiglu" else None
-        bias = mk(rows) if cfg.b_up is not None else None
+        bias = mk(ld if layout == "out_major" else rows) if cfg.b_up is not None else None
         idx = None
         if gathered:
             idx = torch.stack([torch.sort(torch.randperm(N, generator=g, device=dev)[:K]).values
                                for _ in range(B)]).to(torch.int32).contiguous()
-        layers.append((ci.make_weights(up, gate, bias, down, None, core_idx=idx), (up, gate, bias, down, idx)))
+        layers.append((ci.make_weights(up, gate, bias, down, None, core_idx=idx, down_layout=layout),
+                       (up, gate, bias, down, idx)))
     x = mk(B, d) * 50
     y = torch.empty_like(x)
     ws = ci.decode_workspace(B, K, d, dev)
@@ -106,7 +116,7 @@ def main():
     torch.cuda.synchronize()
     n_mat = cfg.n_mat
     e = 2 if cfg.dtype != "f32" else 4
-    print(f"workload {cfg.name}: K={K} d={d} B={B}; algorithmic bytes per decode launch = "
+    print(f"workload {cfg.name}: K={K} d={d} B={B} beta={beta} compact down matrix {layout}; algorithmic bytes per decode launch = "
           f"{B * (n_mat * K * d * e + (K * e if cfg.b_up is not None else 0) + 2 * d * e)}; "
           f"calibration copy = {COPY_BYTES} bytes read + {COPY_BYTES} bytes written")
 
