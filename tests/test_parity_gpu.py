@@ -739,6 +739,18 @@ def test_full_size_layer_hidden_ranked(lib, name, beta):
     S_ref, c_ref = orc.select(ranked, cfg.alpha, beta)
     assert counts.cpu().numpy().tolist() == c_ref.tolist()
     assert S.cpu().numpy().tolist() == S_ref.tolist()
+    # What ranking the 16-bit hidden values instead of the fp32 scores costs: the similarity of
+    # Insight-2 (Sec. 3.2) between the two core sets of the same prompt (the rounding merges
+    # neighbouring scores, which moves neurons at the Def. 1 and Def. 2 boundaries).
+    _, A32 = lib.ffn_dense(X[:cfg.M].contiguous(), w["w_up"], w["w_gate"], w["b_up"], None, None, cfg.down_layout,
+                           cfg.act, want_y=False, want_a=True)
+    S32, _ = lib.select(A32, cfg.alpha, beta)
+    torch.cuda.synchronize()
+    sim = orc.core_similarity(S32.cpu().numpy(), S_ref)
+    _say(f"  hidden-ranked vs fp32-ranked core set of layer 0, first prompt: similarity {sim:.4f} "
+         f"({len(set(S32.cpu().numpy().tolist()) - set(S_ref.tolist()))} of {len(S_ref)} neurons differ)")
+    assert sim >= 0.9
+    del A32
     # sampled rows and columns of H against the oracle's hidden state
     rng = np.random.default_rng(4)
     rows = np.unique(rng.integers(0, X.shape[0], size=6))
