@@ -112,6 +112,71 @@ def test_compact_rejects_bad_arguments_without_a_gpu(lib):
     assert lib.raw.coreinfer_compact_down_ld(8, 1, None) == lib.CI_ERR_INVALID_ARG
 
 
+def test_preferred_compact_layout_and_its_arguments(lib):
+    """Pure host function: small layers -> neuron-major, large ones -> output-major, shapes the
+    single-launch decode does not take -> neuron-major."""
+    import torch
+    out = ctypes.c_int(-1)
+    r = lib.raw.coreinfer_compact_preferred_layout
+    assert r(2765, 5120, lib.CI_BF16, lib.CI_ACT_SWIGLU, ctypes.byref(out)) == lib.CI_OK
+    assert out.value == lib.CI_DOWN_NEURON_MAJOR
+    assert r(8295, 5120, lib.CI_BF16, lib.CI_ACT_SWIGLU, ctypes.byref(out)) == lib.CI_OK
+    assert out.value == lib.CI_DOWN_OUT_MAJOR
+    assert r(20000, 32768, lib.CI_F16, lib.CI_ACT_RELU, ctypes.byref(out)) == lib.CI_OK   # d beyond the single launch
+    assert out.value == lib.CI_DOWN_NEURON_MAJOR
+    assert r(0, 4096, lib.CI_F16, lib.CI_ACT_RELU, ctypes.byref(out)) == lib.CI_OK and out.value == lib.CI_DOWN_NEURON_MAJOR
+    assert r(10, 4096, 9, lib.CI_ACT_RELU, ctypes.byref(out)) == lib.CI_ERR_BAD_DTYPE
+    assert r(10, 0, lib.CI_F16, lib.CI_ACT_RELU, ctypes.byref(out)) == lib.CI_ERR_INVALID_ARG
+    assert r(-1, 64, lib.CI_F16, lib.CI_ACT_RELU, ctypes.byref(out)) == lib.CI_ERR_INVALID_ARG
+    assert r(10, 64, lib.CI_F16, lib.CI_ACT_RELU, None) == lib.CI_ERR_INVALID_ARG
+    assert lib.compact_preferred_layout(6554, 4096, torch.float16, "relu") in ("neuron_major", "out_major")
+    plan = lib.dev_fused_plan(6554, 4096, torch.float16, "relu")
+    assert plan["chunks"] >= 2 and plan["chunks"] * plan["chunk_neurons"] >= 6554 and plan["loads_per_row"] == 1
+    assert (plan["chunks"] - 1) * plan["chunk_neurons"] < 6554
+
+
+def test_select_batch_rejects_bad_arguments_without_a_gpu(lib):
+    r = lib.raw.coreinfer_select_batch
+    ok_ws = 1 << 22
+    b = ctypes.c_size_t(0)
+    assert lib.raw.coreinfer_select_batch_workspace_size(8, 512, 36864, ctypes.byref(b)) == lib.CI_OK
+    assert b.value >= 8 * 36864 * 4 + 8 * 512 * 8
+    assert lib.select_batch_workspace_size(1, 256, 16384) == lib.select_workspace_size(256, 16384)
+    assert lib.raw.coreinfer_select_batch_workspace_size(0, 4, 64, ctypes.byref(b)) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_select_batch_workspace_size(70000, 4, 64, ctypes.byref(b)) == lib.CI_ERR_INVALID_ARG
+    assert lib.raw.coreinfer_select_batch_workspace_size(2, 4, 64, None) == lib.CI_ERR_INVALID_ARG
+    # (act, B, M, N, ld, alpha, beta, core_idx, counts, ws, ws_bytes, stream)
+    assert r(None, 2, 4, 64, 64, 0.2, 0.4, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 2, 4, 64, 64, 0.2, 0.4, None, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 0, 4, 64, 64, 0.2, 0.4, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 2, 4, 64, 64, 0.2, 2.0, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_INVALID_ARG
+    assert r(FAKE, 2, 4, 64, 32, 0.2, 0.4, FAKE, None, FAKE, ok_ws, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(FAKE, 2, 4, 64, 64, 0.2, 0.4, FAKE + 2, None, FAKE, ok_ws, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(FAKE, 2, 4, 64, 64, 0.2, 0.4, FAKE, None, None, ok_ws, None) == lib.CI_ERR_WORKSPACE
+    assert r(FAKE, 2, 4, 64, 64, 0.2, 0.4, FAKE, None, FAKE, 16, None) == lib.CI_ERR_WORKSPACE
+
+
+def test_static_decode_rejects_bad_arguments_without_a_gpu(lib):
+    """coreinfer_ffn_decode_static validates like coreinfer_ffn_decode and turns down what its
+    scratch cannot hold before any HIP call."""
+    r = lib.raw.coreinfer_ffn_decode_static
+    F = FAKE
+    def desc(K=8, d=64, N=128, layout=1, ld=0, core=None, gate=None, bias=None):
+        return lib.ci_ffn_weights(F, gate, bias, F, None, core, K, d, N, ld, layout)
+    # (x, B, w, dtype, act, y, status_out, stream)
+    assert r(F, 1, None, 1, 0, F, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(None, 1, ctypes.byref(desc()), 1, 0, F, None, None) == lib.CI_ERR_INVALID_ARG
+    assert r(F, 1, ctypes.byref(desc()), 7, 0, F, None, None) == lib.CI_ERR_BAD_DTYPE
+    assert r(F, 1, ctypes.byref(desc(layout=5)), 1, 0, F, None, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 1, ctypes.byref(desc(gate=F)), 1, 0, F, None, None) == lib.CI_ERR_INVALID_ARG       # gate with ReLU
+    assert r(F, 1, ctypes.byref(desc(gate=F, bias=F)), 1, 1, F, None, None) == lib.CI_ERR_INVALID_ARG  # bias with SwiGLU
+    assert r(F, 1, ctypes.byref(desc(d=60)), 1, 0, F, None, None) == lib.CI_ERR_BAD_LAYOUT
+    assert r(F, 1, ctypes.byref(desc(layout=0, ld=4)), 1, 0, F, None, None) == lib.CI_ERR_BAD_LAYOUT  # ld < K
+    assert r(F, 1, ctypes.byref(desc()), 1, 0, F, F + 2, None) == lib.CI_ERR_BAD_LAYOUT               # status_out misaligned
+    assert r(F, 1, ctypes.byref(desc(K=200000, N=200000, layout=0, ld=200000)), 1, 0, F, None, None) == lib.CI_ERR_WORKSPACE
+    assert r(F, 8, ctypes.byref(desc(K=4096, d=32768, N=4096)), 1, 0, F, None, None) == lib.CI_ERR_WORKSPACE
+
+
 def test_compact_update_rejects_bad_arguments_without_a_gpu(lib):
     r = lib.raw.coreinfer_compact_update
     F = FAKE
