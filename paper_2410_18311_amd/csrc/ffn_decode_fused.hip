@@ -16,17 +16,21 @@
 // were published C - 1 phases earlier, so in the normal case they are there
 // long before they are needed and no workgroup waits for another.
 //
-// Waves.  All waves but the last are COMPUTE waves: they do nothing but stream
-// weight rows through a register ring (DEPTH rows in flight per thread, a slot
-// refilled right after it has been consumed) and dot them with a register
-// resident vector (x in A, the chunk's hidden values in B); the ring never
-// drains between phases, the loads of the next phase are issued one group
-// ahead by a cursor that walks the same (phase, group) sequence.  The last
-// wave is the SERVICE wave: at the end of A(i) it sums the compute waves'
-// partial dots, applies bias and activation and publishes the workgroup's
-// hidden values; it then collects the whole chunk (everybody's values) into
-// LDS, from where the compute waves take their 16-byte position at the start
-// of B(i).  The two kinds of waves meet only at the workgroup barrier that
+// Waves.  All waves but the last two are COMPUTE waves: they do nothing but
+// stream weight rows through a register ring (DEPTH rows in flight per thread,
+// a slot refilled right after it has been consumed) and dot them with a
+// register resident vector (x in A, the chunk's hidden values in B); the ring
+// never drains between phases, the loads of the next phase are issued one
+// group ahead by a cursor that walks the same (phase, group) sequence.  Where a
+// chunk's row segment of w_down_o is narrower than the workgroup, several
+// output rows are dotted side by side by sets of waves.  The last two waves
+// are SERVICE waves: at the end of A(i) the first of them sums the compute
+// waves' partial dots, applies bias and activation and publishes the
+// workgroup's hidden values; both then collect the whole chunk (everybody's
+// values) into LDS, from where the compute waves take their 16-byte position
+// at the start of B(i); at the end of B(i) the first folds the compute waves'
+// partial outputs into the workgroup's outputs and, after the last phase,
+// writes y.  The two kinds of waves meet only at the workgroup barrier that
 // ends each phase.
 //
 // Exchange of the hidden values.  Each value is one 8-byte word {tag, fp32
