@@ -301,7 +301,9 @@ typedef struct {
   int64_t K;               /* core neurons per sentence                 */
   int64_t d;               /* d_model                                   */
   int64_t N;               /* rows of the resident weights (gathered)   */
-  int64_t ld_down;         /* row length of an output-major w_down (>= K, whole 16-byte vectors) */
+  int64_t ld_down;         /* row length of an output-major w_down (>= K, whole 16-byte vectors;
+                              the columns K .. ld_down-1 must hold finite values, e.g. the zeros
+                              coreinfer_compact writes: they are multiplied by zero) */
   int32_t down_layout;     /* ci_down_layout of w_down                  */
 } ci_ffn_weights;
 
