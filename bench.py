@@ -267,6 +267,24 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
     dense_decode()
     dense_decode_ms = timed(dense_decode, reps=3)
 
+    # what a launch of the decode's size reaches on this chip when it only streams: a plain GEMV over
+    # rows of w_up of (about) the same byte count per layer, no dependency between workgroups, one
+    # dependent launch per layer from a HIP graph like the decode
+    stream_ref = None
+    if not gathered:
+        rows = min(N, n_mat * K) // 64 * 64
+        a_ref = torch.empty((1, rows), dtype=torch.float32, device=dev)
+
+        def stream_layers():
+            for l in range(L):
+                ci.ffn_dense(x_cur[l, :1], weights[l]["w_up"][:rows], None, None, None, None, cfg.down_layout, "relu",
+                             want_y=False, want_a=True, A=a_ref, ws=dws)
+        s_ms = timed_graph(stream_layers, reps=5) / L
+        s_bytes = rows * d * e
+        stream_ref = {"kernel": "up_rows_kernel (one GEMV over rows of w_up, no dependency between workgroups)",
+                      "bytes_per_launch": s_bytes, "us_per_launch": s_ms * 1e3,
+                      "gbps": s_bytes / (s_ms * 1e-3) / 1e9, "frac_of_hbm_peak": s_bytes / (s_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
     # --------------------- several sentences: the same decode through the union of their core sets
     # (a different algorithm from the gathered decode that `value` reports: every union row is read
     # once for all its owners; reported beside it, never as `value`)
@@ -440,6 +458,7 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
         "dense_prefill_mfma_frac": dense_flops / (dense_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype],
         "dense_decode_tokens_per_s": B / (dense_decode_ms * 1e-3),
         "roofline": roofline,
+        "streaming_reference": stream_ref,
         "hidden_ranked_prefill": hidden_prefill,
         "union_batched_decode": union,
         "cpu_baseline": cpu,
