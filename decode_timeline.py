@@ -57,6 +57,9 @@ def main():
     p.add_argument("--workload", default="llama2_13b_swiglu_bf16")
     p.add_argument("--beta", type=float, default=None)
     p.add_argument("--layers", type=int, default=6)
+    p.add_argument("--skew", action="store_true",
+                   help="instead of the timelines: end times of the workgroups of ffn_decode_kernel over 48 launches, "
+                        "by compute die (workgroup number modulo 8)")
     args = p.parse_args()
     cfg = wl.WORKLOADS[args.workload]
     beta = cfg.betas[0] if args.beta is None else args.beta
@@ -81,6 +84,32 @@ def main():
             descs[layout].append(ci.make_compact_weights(c, w["b_down"]))
             keep.append(c)
         keep.append(w)
+
+    if args.skew:
+        ws = torch.zeros(WS_BYTES, dtype=torch.uint8, device=DEV)
+        ends = []
+        for rep in range(48 // L + 1):
+            for l in range(L):
+                ci.ffn_decode(xs[l], descs["neuron_major"][l], cfg.act, y=ys[l], ws=ws)
+                torch.cuda.synchronize()
+                raw = ws[(8 << 20):(8 << 20) + 256 * 8 * 8].view(torch.int64).cpu().numpy().reshape(256, 8).astype(np.float64)
+                if raw.max() <= 0:
+                    print("no stamps: this is not a -DCI_FUSED_STAMPS build")
+                    return
+                ends.append((raw[:, 5] - raw[:, 0].min()) / 100.0)
+        E = np.array(ends[:48])
+        m = E.mean(0)
+        print(f"-- ffn_decode_kernel, 256 workgroups, {E.shape[0]} launches: time from the first workgroup's start to each "
+              f"workgroup's end, us")
+        print(f"   mean over workgroups and launches {E.mean():.2f}; first to end (mean over launches) {E.min(1).mean():.2f}; "
+              f"last to end {E.max(1).mean():.2f}")
+        print(f"   per-workgroup mean: min {m.min():.2f}, max {m.max():.2f}, standard deviation {m.std():.3f}; "
+              f"launch-to-launch standard deviation within a workgroup {E.std(0).mean():.3f}")
+        print("   mean end by compute die (workgroup number modulo 8): " + " ".join(f"{m[x::8].mean():.2f}" for x in range(8)))
+        half = E.shape[0] // 2
+        cc = np.corrcoef(E[:half].mean(0), E[half:].mean(0))[0, 1]
+        print(f"   correlation of the per-workgroup mean end between the first and the second half of the launches: {cc:.3f}")
+        return
 
     for layout in ("neuron_major", "out_major"):
         ws = torch.zeros(WS_BYTES, dtype=torch.uint8, device=DEV)
