@@ -111,6 +111,7 @@ int coreinfer_dev_set_param(const char* name, int value) {
   else if (!strcmp(name, "union_down_threads") && value >= 64 && value <= 512) p.union_down_threads = value;
   else if (!strcmp(name, "union_up_wgs_per_cu") && value >= 1 && value <= 8) p.union_up_wgs_per_cu = value;
   else if (!strcmp(name, "union_down_wgs_per_cu") && value >= 1 && value <= 16) p.union_down_wgs_per_cu = value;
+  else if (!strcmp(name, "union_super") && (value == 0 || (value >= 16 && value <= 256))) p.union_super = value;
   else return CI_ERR_INVALID_ARG;
   return CI_OK;
 }

@@ -134,6 +134,7 @@ struct Params {
   Knob union_down_threads{384};   // threads (= 16-byte column vectors) per down-phase workgroup
   Knob union_up_wgs_per_cu{1};
   Knob union_down_wgs_per_cu{2};
+  Knob union_super{0};            // cap on the rows between two ring drains (0: 256 or what LDS holds)
   Knob fused_depth{4};     // single-launch decode: rows in flight per thread (4, 8 or 16)
   Knob fused_threads{0};   // 0 = derived from d
   Knob fused_chunks{2};    // least number of neuron chunks

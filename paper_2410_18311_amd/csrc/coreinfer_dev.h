@@ -29,7 +29,8 @@
  *   register ring), "gemm_big" (0 never, 1 when the grid is large enough, 2
  *   whenever the shape divides: the 256 x 256-tile GEMM kernel);
  *   "union_depth" (8, 16), "union_down_threads" (64..512), "union_up_wgs_per_cu"
- *   (1..8), "union_down_wgs_per_cu" (1..16): union-batched decode.
+ *   (1..8), "union_down_wgs_per_cu" (1..16), "union_super" (0 = default, 16..256:
+ *   cap on the rows between two drains of the load ring): union-batched decode.
  * Unknown name or value out of range: CI_ERR_INVALID_ARG.  The values are
  * relaxed atomics: a call that runs while one is being changed sees the old or
  * the new value of that parameter.  A workspace size must be queried under the

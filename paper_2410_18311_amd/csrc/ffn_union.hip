@@ -23,6 +23,7 @@ namespace ci {
 namespace {
 
 constexpr int SB = 8;  // sentences per batch (bits of the owner mask that the kernels look at)
+constexpr int kSuperMax = 256;  // most rows of a slice between two drains of the load ring
 
 struct UnionArgs {
   const void* x;
@@ -38,6 +39,7 @@ struct UnionArgs {
   int B, d, N, cap, vecs;
   int vc;  // up phase: 16-byte vectors of a row per column chunk
   int n_up, c_up, n_down, c_down;
+  int ks_up, ks_down;  // most rows of a slice handled between two drains of the load ring
 };
 
 __global__ void union_zero_kernel(uint32_t* owners, int64_t n) {
@@ -173,9 +175,10 @@ __global__ __launch_bounds__(512) void union_up_kernel(UnionArgs a) {
   const int r1 = (int)(((int64_t)(slice + 1) * Ku) / a.n_up);
   const int R = r1 - r0;
 
-  float* red = smem;                                            // [nw][NDOT * kSuper][SB]
-  int* sidx = reinterpret_cast<int*>(red + nw * NDOT * kSuper * SB);  // [kSuper]
-  uint32_t* smask = reinterpret_cast<uint32_t*>(sidx + kSuper);       // [kSuper]
+  const int ks = a.ks_up;
+  float* red = smem;                                              // [nw][NDOT * ks][SB]
+  int* sidx = reinterpret_cast<int*>(red + nw * NDOT * ks * SB);  // [ks]
+  uint32_t* smask = reinterpret_cast<uint32_t*>(sidx + ks);       // [ks]
 
   const size_t rowbytes = (size_t)a.d * sizeof(T);
   const char* up = reinterpret_cast<const char*>(a.w_up);
@@ -198,8 +201,11 @@ __global__ __launch_bounds__(512) void union_up_kernel(UnionArgs a) {
     }
   }
 
-  for (int s0 = 0; s0 < R; s0 += kSuper) {
-    const int Rs = min(kSuper, R - s0);
+  // super-chunks of equal size (a short last one would pay a full drain and refill of the ring)
+  const int nsc = (R + ks - 1) / ks;
+  const int step = nsc > 0 ? (R + nsc - 1) / nsc : 1;
+  for (int s0 = 0; s0 < R; s0 += step) {
+    const int Rs = min(step, R - s0);
     const int QB = NDOT * Rs;
     const int QBp = (QB + DEPTH - 1) / DEPTH * DEPTH;
     __syncthreads();  // previous super-chunk done with sidx / smask / red
@@ -237,7 +243,7 @@ __global__ __launch_bounds__(512) void union_up_kernel(UnionArgs a) {
         CI_UISSUE(pos + DEPTH, s);
         __builtin_amdgcn_sched_barrier(0);
         halve_rows<SB, 32>(p, lane);  // lanes 8t .. 8t+7 now hold sentence t's wave sum
-        if ((lane & 7) == 0 && pos < QB) red[((wave * NDOT * kSuper) + pos) * SB + (lane >> 3)] = p[0];
+        if ((lane & 7) == 0 && pos < QB) red[((wave * NDOT * ks) + pos) * SB + (lane >> 3)] = p[0];
       }
     }
     // filler loads issued past the end are still outstanding
@@ -248,7 +254,7 @@ __global__ __launch_bounds__(512) void union_up_kernel(UnionArgs a) {
     for (int o = tid; o < QB * SB; o += nt) {
       const int q = o / SB, t = o % SB;
       float z = 0.f;
-      for (int w = 0; w < nw; ++w) z += red[((w * NDOT * kSuper) + q) * SB + t];
+      for (int w = 0; w < nw; ++w) z += red[((w * NDOT * ks) + q) * SB + t];
       const int mat = (SWIGLU && q >= Rs) ? 1 : 0;
       const int r = q - mat * Rs;
       a.hp[(((size_t)chunk * NDOT + mat) * a.cap + (size_t)(r0 + s0 + r)) * SB + t] = z;
@@ -272,9 +278,9 @@ __global__ __launch_bounds__(512) void union_down_kernel(UnionArgs a) {
   constexpr int VEC = D::VEC;
   constexpr int NDOT = SWIGLU ? 2 : 1;
 
-  __shared__ float hbuf[kSuper * SB];
-  __shared__ int sidx[kSuper];
-  __shared__ uint32_t smask[kSuper];
+  __shared__ float hbuf[kSuperMax * SB];
+  __shared__ int sidx[kSuperMax];
+  __shared__ uint32_t smask[kSuperMax];
   const int tid = threadIdx.x, nt = blockDim.x;
   const int slice = blockIdx.x, chunk = blockIdx.y;
   const int Ku = union_rows_clamped(a);
@@ -295,8 +301,10 @@ __global__ __launch_bounds__(512) void union_down_kernel(UnionArgs a) {
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[t][v] = 0.f;
 
-  for (int s0 = 0; s0 < R; s0 += kSuper) {
-    const int Rs = min(kSuper, R - s0);
+  const int nsc = (R + a.ks_down - 1) / a.ks_down;
+  const int step = nsc > 0 ? (R + nsc - 1) / nsc : 1;
+  for (int s0 = 0; s0 < R; s0 += step) {
+    const int Rs = min(step, R - s0);
     const int QBp = (Rs + DEPTH - 1) / DEPTH * DEPTH;
     __syncthreads();  // previous super-chunk done with hbuf / sidx / smask
     union_stage(a, r0 + s0, Rs, sidx, smask);
@@ -370,10 +378,14 @@ __global__ __launch_bounds__(512) void union_down_kernel(UnionArgs a) {
   }
 }
 
+inline size_t union_up_lds(int t_up, int ndot, int ks) {
+  return (size_t)(t_up / 64) * ndot * ks * SB * sizeof(float) + 2 * (size_t)ks * sizeof(int);
+}
+
 template <class D, int NI, bool SWIGLU>
 void launch_union_up(const UnionArgs& a, int t_up, hipStream_t s) {
   constexpr int NDOT = SWIGLU ? 2 : 1;
-  const size_t lds = (size_t)(t_up / 64) * NDOT * kSuper * SB * sizeof(float) + 2 * kSuper * sizeof(int);
+  const size_t lds = union_up_lds(t_up, NDOT, a.ks_up);
   const dim3 g(a.n_up, a.c_up);
   // about 16 loads in flight per thread
   if constexpr (NI >= 3) hipLaunchKernelGGL((union_up_kernel<D, NI, SWIGLU, 4>), g, dim3(t_up), lds, s, a);
@@ -466,6 +478,16 @@ int launch_ffn_decode_union(const void* x, int64_t B, const ci_ffn_weights* w, c
   if (a.n_down > a.cap) a.n_down = a.cap;
   if (a.n_up < 1) a.n_up = 1;
   if (a.n_down < 1) a.n_down = 1;
+
+  // rows between two drains: as many as 64 KB of LDS hold (wave sums of the up phase)
+  a.ks_up = kSuperMax;
+  while (a.ks_up > 64 && union_up_lds(t_up, ndot, a.ks_up) > 65536) a.ks_up >>= 1;
+  a.ks_down = kSuperMax;
+  const int ks_cap = params().union_super;
+  if (ks_cap > 0) {
+    if (a.ks_up > ks_cap) a.ks_up = ks_cap;
+    if (a.ks_down > ks_cap) a.ks_down = ks_cap;
+  }
 
   a.hp = ws;
   const size_t hp_floats = ((size_t)a.c_up * ndot * (size_t)a.cap * SB + 63) / 64 * 64;
