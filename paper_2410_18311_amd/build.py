@@ -15,7 +15,7 @@ INCLUDE = os.path.join(ROOT, "include")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libcoreinfer.so")
 
-SOURCES = ["api.hip", "ffn_decode.hip", "ffn_decode_fused.hip", "ffn_union.hip", "select.hip", "compact.hip", "centroid.hip", "gemv.hip", "gemm_mfma.hip"]
+SOURCES = ["api.hip", "ffn_decode.hip", "ffn_decode_fused.hip", "ffn_union.hip", "select.hip", "compact.hip", "centroid.hip", "gemv.hip", "gemm_mfma.hip", "stream_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -42,7 +42,7 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = False) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
     r = subprocess.run(cmd, capture_output=True, text=True)

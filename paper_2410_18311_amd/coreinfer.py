@@ -100,6 +100,10 @@ _lib.coreinfer_dev_set_param.restype = _int
 _lib.coreinfer_dev_set_param.argtypes = [ctypes.c_char_p, _int]
 _lib.coreinfer_dev_fused_plan.restype = _int
 _lib.coreinfer_dev_fused_plan.argtypes = [_i64, _i64, _int, _int, ctypes.POINTER(_int)]
+_lib.coreinfer_dev_stream_probe.restype = _int
+_lib.coreinfer_dev_stream_probe.argtypes = [_vp, _i64, _i64, _int, _int, _int, _int, _int, _vp, _vp]
+_lib.coreinfer_dev_tile_probe.restype = _int
+_lib.coreinfer_dev_tile_probe.argtypes = [_vp, _i64, _i64, _int, _int, _int, _int, _int, _vp, _vp]
 
 
 class CoreInferError(RuntimeError):
@@ -142,6 +146,22 @@ def dev_fused_plan(K: int, d: int, dtype: torch.dtype, act: str) -> dict:
     out = (_int * 5)()
     _check(_lib.coreinfer_dev_fused_plan(K, d, DTYPE_CODE[dtype], ACT_CODE[act], out), "coreinfer_dev_fused_plan")
     return dict(zip(("chunks", "chunk_neurons", "compute_waves", "loads_per_row", "workgroups"), list(out)))
+
+
+def dev_stream_probe(buf: torch.Tensor, window_bytes: int, per_workgroup: bool, workgroups: int, threads: int,
+                     depth: int, iters: int, out: torch.Tensor) -> None:
+    """Measurement aid: streams 16-byte loads over windows of `buf` (see csrc/coreinfer_dev.h)."""
+    _check(_lib.coreinfer_dev_stream_probe(_ptr(buf), buf.numel() * buf.element_size(), int(window_bytes),
+                                           int(bool(per_workgroup)), int(workgroups), int(threads), int(depth),
+                                           int(iters), _ptr(out), _stream(buf)), "coreinfer_dev_stream_probe")
+
+
+def dev_tile_probe(buf: torch.Tensor, pitch_bytes: int, shared: bool, workgroups: int, depth: int, ksteps: int,
+                   iters: int, out: torch.Tensor) -> None:
+    """Measurement aid: the load stream of a GEMM operand tile (see csrc/coreinfer_dev.h)."""
+    _check(_lib.coreinfer_dev_tile_probe(_ptr(buf), buf.numel() * buf.element_size(), int(pitch_bytes),
+                                         int(bool(shared)), int(workgroups), int(depth), int(ksteps), int(iters),
+                                         _ptr(out), _stream(buf)), "coreinfer_dev_tile_probe")
 
 
 def keep_count(frac: float, n: int) -> int:

@@ -54,6 +54,28 @@ int coreinfer_dev_set_param(const char* name, int value);
  * apply. */
 int coreinfer_dev_fused_plan(int64_t K, int64_t d, int dtype, int act, int* out);
 
+/* Measurement aid: `workgroups` workgroups of `threads` threads (a multiple of
+ * 64 up to 512) each stream 16-byte loads, `depth` (2, 4, 8, 16) in flight per
+ * thread, `iters` * depth per thread in all, round and round over a window of
+ * `window_bytes` (a multiple of 16, at least 16 * threads) of the device buffer
+ * `buf` (16-byte aligned, `buf_bytes` long): the same window for all
+ * (`per_workgroup` = 0) or consecutive windows, one each (then window_bytes *
+ * workgroups <= buf_bytes).  `out`: device, 4 * workgroups bytes, receives a
+ * checksum.  Asynchronous on `stream`; the caller times it. */
+int coreinfer_dev_stream_probe(const void* buf, int64_t buf_bytes, int64_t window_bytes, int per_workgroup,
+                               int workgroups, int threads, int depth, int iters, void* out, void* stream);
+
+/* Measurement aid: the load stream of a GEMM operand tile without the
+ * arithmetic.  Workgroups of 256 threads; a load instruction takes 128 bytes
+ * of each of 32 rows `pitch_bytes` apart, `depth` (4, 8, 16) instructions = 32 *
+ * depth rows in flight, then the same rows 128 bytes further along, `ksteps`
+ * times (ksteps * 128 <= pitch_bytes keeps the rows apart), round and round for
+ * `iters` steps.  `shared` != 0: every workgroup reads the same rows; else
+ * workgroup w reads rows [32 * depth * w, 32 * depth * (w + 1)).  Everything it
+ * touches must lie inside `buf` (checked). */
+int coreinfer_dev_tile_probe(const void* buf, int64_t buf_bytes, int64_t pitch_bytes, int shared,
+                             int workgroups, int depth, int ksteps, int iters, void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -393,6 +393,31 @@ def test_development_hook_validation(lib):
     assert "coreinfer_dev_set_param" not in _declared_symbols()
 
 
+def test_development_probes_validate_before_launching(lib):
+    """csrc/coreinfer_dev.h: the load-stream probes reject anything that would read outside the buffer."""
+    import ctypes
+    vp, i64, ci_ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    sp = lib.raw.coreinfer_dev_stream_probe
+    sp.restype = ci_
+    sp.argtypes = [vp, i64, i64, ci_, ci_, ci_, ci_, ci_, vp, vp]
+    F = 0x100000
+    assert sp(None, 1 << 20, 1 << 16, 0, 4, 64, 8, 1, F, None) == lib.CI_ERR_INVALID_ARG
+    assert sp(F, 1 << 20, 1 << 16, 1, 17, 64, 8, 1, F, None) == lib.CI_ERR_INVALID_ARG   # 17 windows of 64 KB > 1 MB
+    assert sp(F, 1 << 20, 512, 0, 4, 64, 8, 1, F, None) == lib.CI_ERR_INVALID_ARG         # window < 16 * threads
+    assert sp(F, 1 << 20, 1 << 16, 0, 4, 96, 8, 1, F, None) == lib.CI_ERR_INVALID_ARG     # threads not whole waves
+    assert sp(F, 1 << 20, 1 << 16, 0, 4, 64, 3, 1, F, None) == lib.CI_ERR_INVALID_ARG     # depth
+    assert sp(F + 8, 1 << 20, 1 << 16, 0, 4, 64, 8, 1, F, None) == lib.CI_ERR_BAD_LAYOUT
+    tp = lib.raw.coreinfer_dev_tile_probe
+    tp.restype = ci_
+    tp.argtypes = [vp, i64, i64, ci_, ci_, ci_, ci_, ci_, vp, vp]
+    # 256 rows of 8 KB per workgroup: two workgroups need 4 MB - 8 KB + 64 * 128 bytes
+    assert tp(F, (4 << 20) - 1, 8192, 0, 2, 8, 64, 1, F, None) == lib.CI_ERR_INVALID_ARG
+    assert tp(F, 1 << 20, 8192, 1, 2, 8, 64, 1, F, None) == lib.CI_ERR_INVALID_ARG        # shared rows: 2 MB needed
+    assert tp(F, 1 << 30, 64, 1, 2, 8, 1, 1, F, None) == lib.CI_ERR_INVALID_ARG           # pitch < 128
+    assert tp(F, 1 << 30, 8192, 1, 2, 5, 64, 1, F, None) == lib.CI_ERR_INVALID_ARG        # depth
+    assert "coreinfer_dev_stream_probe" not in _declared_symbols()
+
+
 def test_workloads_module_has_the_five_configurations():
     from paper_2410_18311_amd import workloads as wl
     assert len(wl.WORKLOADS) == 5
