@@ -73,6 +73,35 @@ def main():
                       f"{depth * 4:3d} KB in flight per CU: {us:8.1f} us, {total / us / 1e6:6.2f} TB/s, "
                       f"{total / us / 1e3 / CUS:6.1f} GB/s per CU", flush=True)
 
+    # launches of the size of one decode layer: every byte read once, dependent launches replayed from a HIP graph
+    print("-- read-only launches of a decode layer's size, 20 launches over different parts of the buffer in a HIP graph")
+    for wgs, threads, depth in ((256, 512, 8), (512, 512, 8), (256, 512, 4)):
+        for mb in (42, 85, 107, 141, 212, 425):
+            per_iter = threads * depth * 16
+            iters = max(1, mb * 1000000 // (wgs * per_iter))
+            win = iters * per_iter
+            nbytes = win * wgs
+            regions = min(20, buf.numel() // nbytes)
+            def layers():
+                for r in range(regions):
+                    ci.dev_stream_probe(buf[r * nbytes:(r + 1) * nbytes], win, True, wgs, threads, depth, iters, out)
+            layers()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                layers()
+            g.replay()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(10):
+                g.replay()
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) / 10 / regions * 1e3
+            print(f"   {wgs:4d} workgroups x {threads} threads x {depth} loads, {nbytes / 1e6:6.1f} MB per launch: {us:6.2f} us launch to launch, "
+                  f"{nbytes / us / 1e6:5.2f} TB/s = {nbytes / us / 1e6 / 8:.3f} of 8 TB/s", flush=True)
+
 
 if __name__ == "__main__":
     main()
