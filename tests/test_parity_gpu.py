@@ -872,6 +872,34 @@ def test_decode_union_matches_oracle_and_gathered(lib, dt, act, d, N, K, B, over
         assert_close_rms(yg[b], ref, dtype, f"gathered b={b}")
 
 
+@pytest.mark.parametrize("dt,act", [("f16", "relu"), ("bf16", "swiglu")])
+def test_decode_union_several_drains_per_slice(lib, dt, act):
+    """Slices longer than the rows handled between two drains of the load ring (forced small through the
+    development hook): equal parts with a ragged last one; the result does not depend on the split."""
+    d, N, K, B = 320, 12000, 5000, 3
+    dtype = DTYPES[dt]
+    _say("union drains case", dt, act, d, N, K, B)
+    w = rand_weights(d, N, dtype, act, "neuron_major", seed=77, device=DEV)
+    S = np.sort(_random_sets(np.random.default_rng(91), B, K, N, 0.2), axis=1)
+    idx = torch.from_numpy(S.astype(np.int32)).to(DEV)
+    x = torch.randn(B, d, generator=torch.Generator().manual_seed(4)).to(dtype).to(DEV)
+    uidx, umask, ucount = lib.union_build(idx, N)
+    resident = lib.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"])
+    y_default = lib.ffn_decode_union(x, resident, uidx, umask, ucount, act)
+    torch.cuda.synchronize()
+    assert int(ucount.item()) > 256 * 17  # every slice of the up phase has more than 16 rows
+    try:
+        for cap in (16, 23):
+            lib.dev_set_param("union_super", cap)
+            y = lib.ffn_decode_union(x, resident, uidx, umask, ucount, act)
+            torch.cuda.synchronize()
+            assert torch.equal(y, y_default), f"rows between drains capped at {cap}"
+    finally:
+        lib.dev_set_param("union_super", 0)
+    for b in range(B):
+        assert_close_rms(y_default[b], _oracle_ffn(act, x[b], S[b], w, "neuron_major"), dtype, f"union b={b}")
+
+
 def test_decode_union_empty_sets_give_the_output_bias(lib):
     d, N, B = 128, 256, 3
     w = rand_weights(d, N, torch.float16, "relu", "neuron_major", seed=5, device=DEV)
