@@ -338,6 +338,30 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
     kgraph.replay()
     kernel_ms = timed(kgraph.replay, reps=args.kernel_reps) / L
     del kgraph
+
+    # the least a launch of that size can take (measured last: it leaves the roofline figure above alone): a kernel that only reads the same number of bytes
+    # (16-byte loads, 64 KB in flight per compute unit, no arithmetic, nothing passed from one half to
+    # the other, nothing written), again one dependent launch per layer from a HIP graph
+    read_ref = None
+    if not gathered:
+        per_iter = 512 * 8 * 16
+        want = n_mat * K * d * e
+        iters = max(1, want // (256 * per_iter))
+        r_bytes = iters * per_iter * 256
+        regions = max(4, min(L, -(-(600 << 20) // r_bytes)))   # more than the memory-side cache holds
+        probe_buf = torch.ones(regions * r_bytes, dtype=torch.uint8, device=dev)
+        probe_out = torch.zeros(256, dtype=torch.int32, device=dev)
+
+        def read_layers():
+            for r in range(regions):
+                ci.dev_stream_probe(probe_buf[r * r_bytes:(r + 1) * r_bytes], iters * per_iter, True, 256, 512, 8, iters,
+                                    probe_out)
+        r_ms = timed_graph(read_layers, reps=5) / regions
+        read_ref = {"kernel": "stream_probe_kernel (reads only: no dots, no dependency, no output)",
+                    "bytes_per_launch": r_bytes, "us_per_launch": r_ms * 1e3,
+                    "gbps": r_bytes / (r_ms * 1e-3) / 1e9, "frac_of_hbm_peak": r_bytes / (r_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        del probe_buf
+
     bytes_per_launch = B * (n_mat * K * d * e + (K * e if cfg.b_up is not None else 0) + 2 * d * e)
     if gathered:
         bytes_per_launch += B * K * 4
@@ -459,6 +483,7 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
         "dense_decode_tokens_per_s": B / (dense_decode_ms * 1e-3),
         "roofline": roofline,
         "streaming_reference": stream_ref,
+        "read_only_reference": read_ref,
         "hidden_ranked_prefill": hidden_prefill,
         "union_batched_decode": union,
         "cpu_baseline": cpu,
