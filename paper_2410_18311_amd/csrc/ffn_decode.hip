@@ -279,16 +279,21 @@ __global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(Decode
 }
 
 // y[b, c] = sum_w partial[b, w, c] + b_down[c].  256 threads = CQ column quads
-// (4 * CQ columns, contiguous in every partial row) x 256 / CQ partial groups;
-// the order of summation is fixed, so the result is deterministic.
+// (4 * CQ columns, contiguous in every partial row) x 256 / CQ groups of
+// partial rows.  A thread adds up the rows of its group (all its loads in
+// flight at once), the groups that share a wave are added by a butterfly over
+// the lanes (every lane of a column quad ends with the same sum), the four
+// waves through LDS with a single barrier.  The order of summation is fixed,
+// so the result is deterministic.
 template <class D, int CQ>
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ partial,
                                                             const void* __restrict__ b_down,
                                                             void* __restrict__ y, int n_wg, int d) {
   using T = typename D::T;
   constexpr int G = 256 / CQ;
-  __shared__ float4 sm[G][CQ + 1];
+  __shared__ float4 sm[4][CQ];
   const int tx = threadIdx.x % CQ, ty = threadIdx.x / CQ;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = (blockIdx.x * CQ + tx) * 4;
   const int b = blockIdx.y;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -300,21 +305,23 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
       s.x += u2f(t[0]); s.y += u2f(t[1]); s.z += u2f(t[2]); s.w += u2f(t[3]);
     }
   }
-  sm[ty][tx] = s;
-  __syncthreads();
-  // tree over the G groups, pairwise in a fixed order
+  // lanes tx, tx + CQ, tx + 2 CQ, ... of a wave hold the same columns
 #pragma unroll
-  for (int half = G / 2; half >= 1; half >>= 1) {
-    if (ty < half) {
-      const float4 v = sm[ty + half][tx];
-      float4 t = sm[ty][tx];
-      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
-      sm[ty][tx] = t;
-    }
-    __syncthreads();
+  for (int m = CQ; m < 64; m <<= 1) {
+    s.x += __shfl_xor(s.x, m);
+    s.y += __shfl_xor(s.y, m);
+    s.z += __shfl_xor(s.z, m);
+    s.w += __shfl_xor(s.w, m);
   }
-  if (ty == 0 && c < d) {
-    const float4 t = sm[0][tx];
+  if (lane < CQ) sm[wave][lane] = s;
+  __syncthreads();
+  if (threadIdx.x < CQ && c < d) {
+    float4 t = sm[0][tx];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const float4 v = sm[w][tx];
+      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+    }
     float o[4] = {t.x, t.y, t.z, t.w};
     if (b_down) {
 #pragma unroll
