@@ -506,7 +506,8 @@ int coreinfer_ffn_decode_status(const void* ws, int32_t* status_out, void* strea
 
 int coreinfer_union_workspace_size(int64_t N, size_t* bytes) {
   if (!bytes || N < 1 || N > CI_MAX_NEURONS) return CI_ERR_INVALID_ARG;
-  *bytes = round256((size_t)N * sizeof(uint32_t));
+  // owner masks [N] and the number of owned neurons per block of 1024
+  *bytes = round256(((size_t)(N + 63) / 64 * 64 + 1024) * sizeof(uint32_t));
   return CI_OK;
 }
 

@@ -5,7 +5,7 @@
 // sets is read ONCE and applied to the sentences that own it (a bit mask per
 // row).  The result per sentence is exactly its own sparse FFN (Sec. 4.2).
 //
-//   union_scatter / union_compact : owner masks [N] -> ascending row list + masks + count
+//   union_scatter / union_count / union_place : owner masks [N] -> ascending row list + masks + count
 //   union_up_kernel   : partial dots of the up (and gate) rows with every owner's x,
 //                       per column chunk -> hp[chunk][matrix][row][sentence]
 //   union_down_kernel : h = act(sum of chunks [+ bias]) for the owners, then
@@ -56,40 +56,63 @@ __global__ void union_scatter_kernel(const int32_t* __restrict__ core_idx, int64
   if (n >= 0 && n < N) atomicOr(&owners[n], 1u << (uint32_t)(i / K));
 }
 
-// Ordered compaction of the neurons with a non-empty owner mask (one
-// workgroup; runs once per batch, at prefill time).
-__global__ __launch_bounds__(1024) void union_compact_kernel(const uint32_t* __restrict__ owners, int N,
-                                                             int cap, int32_t* __restrict__ uidx,
-                                                             uint32_t* __restrict__ umask,
-                                                             int32_t* __restrict__ ucount) {
+// Ordered compaction of the neurons with a non-empty owner mask, in two launches over blocks of 1024
+// neurons: the number of owned neurons per block, then every block adds up the blocks before it and
+// places its own neurons behind them (ascending, so the result does not depend on the scheduling).
+constexpr int kUnionBlock = 1024;
+
+__global__ __launch_bounds__(kUnionBlock) void union_count_kernel(const uint32_t* __restrict__ owners, int N,
+                                                                  uint32_t* __restrict__ blkcnt) {
   __shared__ int wsum[16];
-  __shared__ int base_s;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) base_s = 0;
+  const int i = blockIdx.x * kUnionBlock + tid;
+  const uint32_t m = i < N ? owners[i] : 0u;
+  const uint64_t bal = __ballot(m != 0u);
+  if (lane == 0) wsum[wave] = __popcll(bal);
   __syncthreads();
-  for (int i0 = 0; i0 < N; i0 += 1024) {
-    const int i = i0 + tid;
-    const uint32_t m = i < N ? owners[i] : 0u;
-    const uint64_t bal = __ballot(m != 0u);
-    const int before = __popcll(bal & lanemask_lt());
-    if (lane == 0) wsum[wave] = __popcll(bal);
-    __syncthreads();
-    int off = base_s;
-    for (int w = 0; w < wave; ++w) off += wsum[w];
-    const int pos = off + before;
-    if (m != 0u && pos < cap) {
-      uidx[pos] = i;
-      umask[pos] = m;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      int t = 0;
-      for (int w = 0; w < 16; ++w) t += wsum[w];
-      base_s += t;
-    }
-    __syncthreads();
+  if (tid == 0) {
+    int t = 0;
+    for (int w = 0; w < 16; ++w) t += wsum[w];
+    blkcnt[blockIdx.x] = (uint32_t)t;
   }
-  if (tid == 0) ucount[0] = base_s < cap ? base_s : cap;
+}
+
+__global__ __launch_bounds__(kUnionBlock) void union_place_kernel(const uint32_t* __restrict__ owners, int N,
+                                                                  int cap, const uint32_t* __restrict__ blkcnt,
+                                                                  int32_t* __restrict__ uidx,
+                                                                  uint32_t* __restrict__ umask,
+                                                                  int32_t* __restrict__ ucount) {
+  __shared__ int wsum[16];
+  __shared__ int bsum[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int blk = blockIdx.x;
+  const int i = blk * kUnionBlock + tid;
+  const uint32_t m = i < N ? owners[i] : 0u;
+  const uint64_t bal = __ballot(m != 0u);
+  const int before = __popcll(bal & lanemask_lt());
+  if (lane == 0) wsum[wave] = __popcll(bal);
+  // owned neurons in the blocks before mine (at most 1024 blocks: one per thread)
+  int c = tid < blk ? (int)blkcnt[tid] : 0;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off);
+  if (lane == 0) bsum[wave] = c;
+  __syncthreads();
+  int base = 0, own = 0;
+  for (int w = 0; w < 16; ++w) {
+    base += bsum[w];
+    own += wsum[w];
+  }
+  int off = base;
+  for (int w = 0; w < wave; ++w) off += wsum[w];
+  const int pos = off + before;
+  if (m != 0u && pos < cap) {
+    uidx[pos] = i;
+    umask[pos] = m;
+  }
+  if (blk == (int)gridDim.x - 1 && tid == 0) {
+    const int total = base + own;
+    ucount[0] = total < cap ? total : cap;
+  }
 }
 
 __device__ __forceinline__ int union_rows_clamped(const UnionArgs& a) {
@@ -425,7 +448,10 @@ int launch_union_build(const int32_t* core_idx, int64_t B, int64_t K, int64_t N,
   if (n_idx > 0)
     hipLaunchKernelGGL(union_scatter_kernel, dim3((unsigned)((n_idx + 255) / 256)), dim3(256), 0, s,
                        core_idx, n_idx, K, N, owners);
-  hipLaunchKernelGGL(union_compact_kernel, dim3(1), dim3(1024), 0, s, owners, (int)N, (int)cap, uidx,
+  const unsigned nblk = (unsigned)((N + kUnionBlock - 1) / kUnionBlock);  // <= 1024: N <= CI_MAX_NEURONS
+  uint32_t* blkcnt = owners + (N + 63) / 64 * 64;
+  hipLaunchKernelGGL(union_count_kernel, dim3(nblk), dim3(kUnionBlock), 0, s, owners, (int)N, blkcnt);
+  hipLaunchKernelGGL(union_place_kernel, dim3(nblk), dim3(kUnionBlock), 0, s, owners, (int)N, (int)cap, blkcnt, uidx,
                      umask, ucount);
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;

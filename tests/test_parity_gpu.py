@@ -831,7 +831,8 @@ def _random_sets(rng, B, K, N, overlap):
 
 
 @pytest.mark.parametrize("B,K,N,overlap", [(1, 7, 40, 0.0), (3, 100, 300, 0.5), (8, 410, 1024, 0.0),
-                                           (8, 2000, 5000, 0.9), (5, 0, 64, 0.0), (2, 3000, 3000, 1.0)])
+                                           (8, 2000, 5000, 0.9), (5, 0, 64, 0.0), (2, 3000, 3000, 1.0),
+                                           (4, 30000, 150000, 0.5), (2, 1025, 1 << 20, 0.0)])
 def test_union_build_matches_oracle(lib, B, K, N, overlap):
     _say("union build case", B, K, N, overlap)
     S = _random_sets(np.random.default_rng(B * 31 + K), B, K, N, overlap)
