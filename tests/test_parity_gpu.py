@@ -1107,7 +1107,10 @@ def test_prefill_graph_replays_match_eager(lib):
                        torch.arange(K, dtype=torch.int32, device=DEV))
     sets = torch.stack([torch.sort(torch.randperm(N, generator=torch.Generator().manual_seed(s))[:K]).values
                         for s in range(B)]).to(torch.int32).to(DEV)
-    uws = torch.empty(N * 4 + 256, dtype=torch.uint8, device=DEV)
+    import ctypes
+    need = ctypes.c_size_t(0)
+    lib._check(lib.raw.coreinfer_union_workspace_size(N, ctypes.byref(need)), "union_workspace_size")
+    uws = torch.empty(need.value, dtype=torch.uint8, device=DEV)
     uidx = torch.empty(N, dtype=torch.int32, device=DEV)
     umask = torch.empty(N, dtype=torch.int32, device=DEV)
     ucount = torch.empty(1, dtype=torch.int32, device=DEV)
