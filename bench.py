@@ -291,7 +291,9 @@ def run_workload(inp: Inputs, beta: float, steps: int, warmup: int, args, cpu_se
     union = None
     if gathered and B <= 8:
         resident = [ci.make_weights(w["w_up"], w["w_gate"], w["b_up"], w["w_down"], w["b_down"]) for w in weights]
-        ubuild_ms = timed(lambda: [ci.union_build(core_idx[l], N) for l in range(L)]) / L
+        # GPU time of the build's launches (replayed from a HIP graph: launched one by one from Python the
+        # host's output allocations and four launches per call would be what is measured)
+        ubuild_ms = timed_graph(lambda: [ci.union_build(core_idx[l], N) for l in range(L)]) / L
         unions = [ci.union_build(core_idx[l], N) for l in range(L)]
         u_ws = torch.empty(ci.ffn_decode_union_workspace_size(B, min(N, B * K), d, dtype, cfg.act),
                            dtype=torch.uint8, device=dev)
