@@ -90,6 +90,7 @@ int coreinfer_dev_set_param(const char* name, int value) {
   else if (!strcmp(name, "decode_threads") && value >= 0 && value <= 1024) p.decode_threads = value;
   else if (!strcmp(name, "decode_depth") && (value == 4 || value == 8 || value == 16)) p.decode_depth = value;
   else if (!strcmp(name, "reduce_cq") && (value == 4 || value == 8 || value == 16)) p.reduce_cq = value;
+  else if (!strcmp(name, "reduce_threads") && (value == 64 || value == 128 || value == 256 || value == 512 || value == 1024)) p.reduce_threads = value;
   else if (!strcmp(name, "decode_nt_store") && (value == 0 || value == 1)) p.decode_nt_store = value;
   else if (!strcmp(name, "fused_depth") && (value == 4 || value == 8)) p.fused_depth = value;
   else if (!strcmp(name, "fused_threads") && value >= 0 && value <= 1024) p.fused_threads = value;

@@ -128,6 +128,7 @@ struct Params {
   Knob gemm_ring{1};         // register-ring GEMM kernel where it applies
   Knob gemm_direct{1};       // 128 x 128 tiles loaded straight into LDS instead of through the register ring
   Knob gemm_big{1};          // 256 x 256 tiles: 0 never, 1 when there are enough of them, 2 whenever the shape divides
+  Knob reduce_threads{256};  // threads per reduce workgroup (64, 128, 256)
   Knob reduce_cq{8};         // column quads per reduce workgroup (4, 8, 16)
   Knob decode_nt_store{1};   // non-temporal stores for the partial sums
   Knob union_depth{8};            // union-batched decode: rows in flight per thread (8 or 16)

@@ -9,7 +9,8 @@
  *   number of neuron slices per sentence, up to 1024), "decode_threads" (0 =
  *   derive from d, else a multiple of 64 up to 1024), "decode_depth" (4, 8 or 16
  *   weight rows in flight per thread), "reduce_cq" (4, 8, 16 column quads per
- *   reduction workgroup), "decode_nt_store" (0/1): two-launch decode;
+ *   reduction workgroup), "reduce_threads" (64 .. 1024, a power of two: threads per reduction
+ *   workgroup), "decode_nt_store" (0/1): two-launch decode;
  *   "fused_depth" (4, 8), "fused_threads" (0 or a multiple of 64 up to 896),
  *   "fused_chunks" (least number of neuron chunks, 2..64),
  *   "fused_chunk_size" (0 = cost model, else neurons per chunk, a multiple of the

@@ -285,19 +285,25 @@ __global__ __launch_bounds__(NI >= 4 ? 1024 : 512) void ffn_decode_kernel(Decode
 // the lanes (every lane of a column quad ends with the same sum), the four
 // waves through LDS with a single barrier.  The order of summation is fixed,
 // so the result is deterministic.
-template <class D, int CQ>
-__global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ partial,
-                                                            const void* __restrict__ b_down,
-                                                            void* __restrict__ y, int n_wg, int d) {
+template <class D, int CQ, int NT>
+__global__ __launch_bounds__(NT) void decode_reduce_kernel(const float* __restrict__ partial,
+                                                           const void* __restrict__ b_down,
+                                                           void* __restrict__ y, int n_wg, int d) {
   using T = typename D::T;
-  constexpr int G = 256 / CQ;
-  __shared__ float4 sm[4][CQ];
+  constexpr int G = NT / CQ;
+  constexpr int NW = NT / 64;
+  __shared__ float4 sm[NW][CQ];
   const int tx = threadIdx.x % CQ, ty = threadIdx.x / CQ;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = (blockIdx.x * CQ + tx) * 4;
   const int b = blockIdx.y;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  float bias[4] = {0.f, 0.f, 0.f, 0.f};
   if (c < d) {
+    if (b_down && threadIdx.x < CQ) {  // requested ahead of the partial sums
+#pragma unroll
+      for (int k = 0; k < 4; ++k) bias[k] = to_float<D>(reinterpret_cast<const T*>(b_down)[c + k]);
+    }
     const float* p = partial + (size_t)b * n_wg * d + c;
 #pragma unroll 8
     for (int w = ty; w < n_wg; w += G) {
@@ -313,20 +319,21 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
     s.z += __shfl_xor(s.z, m);
     s.w += __shfl_xor(s.w, m);
   }
-  if (lane < CQ) sm[wave][lane] = s;
-  __syncthreads();
+  if constexpr (NW > 1) {
+    if (lane < CQ) sm[wave][lane] = s;
+    __syncthreads();
+  }
   if (threadIdx.x < CQ && c < d) {
-    float4 t = sm[0][tx];
+    float4 t = s;
+    if constexpr (NW > 1) {
+      t = sm[0][tx];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) {
-      const float4 v = sm[w][tx];
-      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+      for (int w = 1; w < NW; ++w) {
+        const float4 v = sm[w][tx];
+        t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+      }
     }
-    float o[4] = {t.x, t.y, t.z, t.w};
-    if (b_down) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) o[k] += to_float<D>(reinterpret_cast<const T*>(b_down)[c + k]);
-    }
+    const float o[4] = {t.x + bias[0], t.y + bias[1], t.z + bias[2], t.w + bias[3]};
     T* yo = reinterpret_cast<T*>(y) + (size_t)b * d + c;
 #pragma unroll
     for (int k = 0; k < 4; ++k) yo[k] = from_float<D>(o[k]);
@@ -336,19 +343,22 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
 template <class D>
 int launch_reduce_typed(const float* partial, const void* b_down, void* y, int n_wg, int d, int B,
                         hipStream_t s) {
+  const int rt = params().reduce_threads;
+#define CI_REDUCE(CQ_, NT_)                                                                              \
+  hipLaunchKernelGGL((decode_reduce_kernel<D, CQ_, NT_>), dim3((d + 4 * CQ_ - 1) / (4 * CQ_), B), dim3(NT_), 0, s, \
+                     partial, b_down, y, n_wg, d)
   switch (params().reduce_cq) {
     case 4:
-      hipLaunchKernelGGL((decode_reduce_kernel<D, 4>), dim3((d + 15) / 16, B), dim3(256), 0, s,
-                         partial, b_down, y, n_wg, d);
+      if (rt == 64) CI_REDUCE(4, 64); else if (rt == 128) CI_REDUCE(4, 128); else CI_REDUCE(4, 256);
       break;
     case 16:
-      hipLaunchKernelGGL((decode_reduce_kernel<D, 16>), dim3((d + 63) / 64, B), dim3(256), 0, s,
-                         partial, b_down, y, n_wg, d);
+      if (rt == 64) CI_REDUCE(16, 64); else if (rt == 128) CI_REDUCE(16, 128); else CI_REDUCE(16, 256);
       break;
     default:
-      hipLaunchKernelGGL((decode_reduce_kernel<D, 8>), dim3((d + 31) / 32, B), dim3(256), 0, s,
-                         partial, b_down, y, n_wg, d);
+      if (rt == 64) CI_REDUCE(8, 64); else if (rt == 128) CI_REDUCE(8, 128); else if (rt == 512) CI_REDUCE(8, 512);
+      else if (rt == 1024) CI_REDUCE(8, 1024); else CI_REDUCE(8, 256);
   }
+#undef CI_REDUCE
   CI_HIP_CHECK_LAUNCH();
   return CI_OK;
 }

@@ -554,7 +554,8 @@ def test_dense_many_tiles_with_split_down_projection(lib, layout):
 @pytest.mark.parametrize("knob,value,default", [("gemm_ring", 0, 1), ("gemm_direct", 0, 1), ("gemm_big", 0, 1), ("select_wgs_per_cu", 1, 2),
                                                 ("select_def2_single", 1, 0), ("decode_depth", 8, 4), ("decode_depth", 16, 4),
                                                 ("decode_wgs_per_cu", 2, 1), ("decode_nt_store", 0, 1),
-                                                ("reduce_cq", 4, 8), ("reduce_cq", 16, 8), ("union_depth", 16, 8),
+                                                ("reduce_cq", 4, 8), ("reduce_cq", 16, 8), ("reduce_threads", 64, 256), ("reduce_threads", 1024, 256),
+                                                ("union_depth", 16, 8),
                                                 ("union_down_threads", 128, 384), ("decode_threads", 512, 0), ("decode_threads", 64, 0),
                                                 ("decode_wgs", 7, 0), ("decode_wgs", 1024, 0), ("union_up_wgs_per_cu", 3, 1),
                                                 ("union_down_wgs_per_cu", 1, 2)])
